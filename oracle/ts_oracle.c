@@ -1,0 +1,349 @@
+/*
+ * CPU oracle for query-aware page selection + sparse decode attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code with the HIP path, is never
+ * called by the product path, and is written directly from the paper's
+ * definitions (TinyServe, Section 3.4 "query-aware routing at page
+ * granularity", Section 3.5 "Query-Aware Page Selection", Eq. 1-2, and the
+ * four steps of Algorithm 1).  All arithmetic is fp64; inputs are bf16 bit
+ * patterns decoded exactly to double.
+ *
+ * Inputs are the *logical* tensors of the paper (keys and values indexed by
+ * sequence, KV head and token position); paging through a block table is a
+ * storage matter of the GPU library and does not appear here.
+ *
+ * Logical shapes (row-major, last index fastest):
+ *   K, V       bf16 bits  [B][Hkv][Lmax][d]     tokens t >= seq_lens[b] ignored
+ *   q          bf16 bits  [B][Hq][d]            Hq = G * Hkv, q head g belongs
+ *                                               to KV head g / G
+ *   page_min,
+ *   page_max   bf16 bits  [B][Hkv][Pmax][d]
+ *   scores     double     [B][Hkv][Pmax]        -inf for pages j >= P_b
+ *   sel        int32      [B][Hkv][Kmax]        ascending page ids, -1 padded
+ *   sel_count  int32      [B]
+ *   out        double     [B][Hq][d]
+ * with P_b = ceil(seq_lens[b] / S)  (Section 3.5: P = ceil(t / S)).
+ *
+ * Pins (tests/test_oracle_pins.py): hand-worked two-page example, the bound
+ * invariant r >= max q.k, K = P  ==> dense softmax attention (checked against
+ * a library routine), brute force over all page subsets on tiny inputs,
+ * closed forms for constant pages, append == rebuild.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double bf16_to_double(uint16_t bits) {
+  uint32_t w = ((uint32_t)bits) << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return (double)f;
+}
+
+static int pages_of(int len, int S) { return (len + S - 1) / S; }
+
+int tso_version(void) { return 1; }
+
+int tso_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Section 3.4 / Eq. 1: phi(K_j) = (m_j, M_j), the channel-wise min and max of
+ * the keys stored in page j.  Only tokens t < seq_lens[b] exist; a partly
+ * filled last page is summarised over the tokens it holds.  Rows of pages
+ * j >= P_b are left untouched. */
+void tso_build_page_meta(const uint16_t* K, const int32_t* seq_lens, int B, int Hkv, int Lmax,
+                         int d, int S, int Pmax, uint16_t* page_min, uint16_t* page_max) {
+  for (int b = 0; b < B; ++b) {
+    int Pb = pages_of(seq_lens[b], S);
+    for (int h = 0; h < Hkv; ++h) {
+      const uint16_t* Kbh = K + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+      for (int j = 0; j < Pb && j < Pmax; ++j) {
+        int t0 = j * S;
+        int t1 = t0 + S < seq_lens[b] ? t0 + S : seq_lens[b];
+        uint16_t* mrow = page_min + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        uint16_t* Mrow = page_max + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        for (int c = 0; c < d; ++c) {
+          uint16_t lo = Kbh[(size_t)t0 * d + c], hi = lo;
+          for (int t = t0 + 1; t < t1; ++t) {
+            uint16_t x = Kbh[(size_t)t * d + c];
+            if (bf16_to_double(x) < bf16_to_double(lo)) lo = x;
+            if (bf16_to_double(x) > bf16_to_double(hi)) hi = x;
+          }
+          mrow[c] = lo;
+          Mrow[c] = hi;
+        }
+      }
+    }
+  }
+}
+
+/* Section 3.4 says the metadata "is maintained" while the cache grows; the
+ * reading taken here: the token appended at position p = seq_lens[b] belongs
+ * to page p / S; it opens that page when p % S == 0 (m = M = k) and otherwise
+ * widens the page's box.  seq_lens is NOT modified (the caller advances it). */
+void tso_append_token_meta(const uint16_t* k_new /*[B][Hkv][d]*/, const int32_t* seq_lens, int B,
+                           int Hkv, int d, int S, int Pmax, uint16_t* page_min,
+                           uint16_t* page_max) {
+  for (int b = 0; b < B; ++b) {
+    int p = seq_lens[b];
+    int j = p / S;
+    if (j >= Pmax) continue;
+    for (int h = 0; h < Hkv; ++h) {
+      uint16_t* mrow = page_min + (((size_t)b * Hkv + h) * Pmax + j) * d;
+      uint16_t* Mrow = page_max + (((size_t)b * Hkv + h) * Pmax + j) * d;
+      const uint16_t* k = k_new + ((size_t)b * Hkv + h) * d;
+      for (int c = 0; c < d; ++c) {
+        if (p % S == 0) {
+          mrow[c] = k[c];
+          Mrow[c] = k[c];
+        } else {
+          if (bf16_to_double(k[c]) < bf16_to_double(mrow[c])) mrow[c] = k[c];
+          if (bf16_to_double(k[c]) > bf16_to_double(Mrow[c])) Mrow[c] = k[c];
+        }
+      }
+    }
+  }
+}
+
+/* Eq. 2 (and step 1 of Algorithm 1): the directional bounding-box estimator
+ *   r(q, phi_j) = sum_i  q_i * (q_i >= 0 ? M_ji : m_ji).
+ * For grouped-query attention the page score of a KV head is the sum of r over
+ * the G query heads that share it.  form == 1 evaluates the equivalent
+ * max(q_i*m_ji, q_i*M_ji) expression instead of the sign test. */
+void tso_score_pages(const uint16_t* q, const uint16_t* page_min, const uint16_t* page_max,
+                     const int32_t* seq_lens, int B, int Hq, int Hkv, int d, int S, int Pmax,
+                     int form, double* scores) {
+  int G = Hq / Hkv;
+  for (int b = 0; b < B; ++b) {
+    int Pb = pages_of(seq_lens[b], S);
+    for (int h = 0; h < Hkv; ++h) {
+      for (int j = 0; j < Pmax; ++j) {
+        double* out = scores + ((size_t)b * Hkv + h) * Pmax + j;
+        if (j >= Pb) {
+          *out = -INFINITY;
+          continue;
+        }
+        const uint16_t* mrow = page_min + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        const uint16_t* Mrow = page_max + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        double s = 0.0;
+        for (int g = 0; g < G; ++g) {
+          const uint16_t* qg = q + ((size_t)b * Hq + (size_t)h * G + g) * d;
+          for (int c = 0; c < d; ++c) {
+            double qc = bf16_to_double(qg[c]);
+            double lo = bf16_to_double(mrow[c]), hi = bf16_to_double(Mrow[c]);
+            if (form == 1) {
+              double a = qc * lo, bb = qc * hi;
+              s += a > bb ? a : bb;
+            } else {
+              s += qc >= 0.0 ? qc * hi : qc * lo;
+            }
+          }
+        }
+        *out = s;
+      }
+    }
+  }
+}
+
+typedef struct {
+  double score;
+  int32_t id;
+} tso_cand;
+
+static int cand_before(const void* pa, const void* pb) {
+  const tso_cand* a = (const tso_cand*)pa;
+  const tso_cand* b = (const tso_cand*)pb;
+  if (a->score > b->score) return -1;
+  if (a->score < b->score) return 1;
+  return (a->id > b->id) - (a->id < b->id); /* equal scores: lower page id first */
+}
+
+static int int_asc(const void* pa, const void* pb) {
+  int32_t a = *(const int32_t*)pa, b = *(const int32_t*)pb;
+  return (a > b) - (a < b);
+}
+
+/* Section 3.5 (S_t = TopK_j r, |S_t| = K; step 2 of Algorithm 1).  Pages are
+ * ranked by (score descending, page id ascending); the first
+ * K_b = min(K, P_b) are kept and reported in ascending page id.  K is
+ * topk_per_seq[b] when that pointer is non-NULL, else topk.
+ * gap (nullable) receives, per (b, h), the relative distance between the last
+ * kept and the first dropped score, |s_K - s_{K+1}| / max(|s_K|, |s_{K+1}|),
+ * or +inf when nothing is dropped. */
+void tso_select_topk_pages(const double* scores, const int32_t* seq_lens, int B, int Hkv, int S,
+                           int Pmax, int topk, const int32_t* topk_per_seq, int Kmax,
+                           int32_t* sel, int32_t* sel_count, double* gap) {
+  tso_cand* cand = (tso_cand*)malloc(sizeof(tso_cand) * (size_t)(Pmax > 0 ? Pmax : 1));
+  for (int b = 0; b < B; ++b) {
+    int Pb = pages_of(seq_lens[b], S);
+    if (Pb > Pmax) Pb = Pmax;
+    int K = topk_per_seq ? topk_per_seq[b] : topk;
+    int Kb = K < Pb ? K : Pb;
+    if (Kb > Kmax) Kb = Kmax;
+    if (Kb < 0) Kb = 0;
+    sel_count[b] = Kb;
+    for (int h = 0; h < Hkv; ++h) {
+      const double* s = scores + ((size_t)b * Hkv + h) * Pmax;
+      int32_t* row = sel + ((size_t)b * Hkv + h) * Kmax;
+      for (int j = 0; j < Pb; ++j) {
+        cand[j].score = s[j];
+        cand[j].id = j;
+      }
+      qsort(cand, (size_t)Pb, sizeof(tso_cand), cand_before);
+      for (int i = 0; i < Kmax; ++i) row[i] = i < Kb ? cand[i].id : -1;
+      qsort(row, (size_t)Kb, sizeof(int32_t), int_asc);
+      if (gap) {
+        double g = INFINITY;
+        if (Kb > 0 && Kb < Pb) {
+          double a = cand[Kb - 1].score, c = cand[Kb].score;
+          double den = fabs(a) > fabs(c) ? fabs(a) : fabs(c);
+          g = den > 0.0 ? fabs(a - c) / den : 0.0;
+        }
+        gap[(size_t)b * Hkv + h] = g;
+      }
+    }
+  }
+  free(cand);
+}
+
+/* Section 3.5, SparseAttn, and steps 3-4 of Algorithm 1: logits
+ * a_i = scale * q.k_i over the tokens of the selected pages only,
+ * alpha = softmax(a) over exactly those tokens, o = sum_i alpha_i v_i.
+ * (The paper writes softmax(q.k) with no scale: scale = 1 is its literal
+ * form.)  A (sequence, head) with no selected token yields o = 0. */
+void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uint16_t* V,
+                                 const int32_t* sel, const int32_t* sel_count,
+                                 const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
+                                 int S, int Kmax, double scale, double* out) {
+  int G = Hq / Hkv;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+  for (int bh = 0; bh < B * Hq; ++bh) {
+    int b = bh / Hq, g = bh % Hq, h = g / G;
+    const uint16_t* qg = q + ((size_t)b * Hq + g) * d;
+    const uint16_t* Kbh = K + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+    const uint16_t* Vbh = V + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+    const int32_t* row = sel + ((size_t)b * Hkv + h) * Kmax;
+    double* o = out + ((size_t)b * Hq + g) * d;
+    int n = sel_count[b];
+    int L = seq_lens[b];
+    double* a = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * S);
+    int32_t* tok = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1) * S);
+    int cnt = 0;
+    double amax = -INFINITY;
+    for (int i = 0; i < n; ++i) {
+      int j = row[i];
+      for (int t = j * S; t < (j + 1) * S && t < L; ++t) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c)
+          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+        a[cnt] = scale * dot;
+        tok[cnt] = t;
+        if (a[cnt] > amax) amax = a[cnt];
+        ++cnt;
+      }
+    }
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    double denom = 0.0;
+    for (int i = 0; i < cnt; ++i) {
+      a[i] = exp(a[i] - amax);
+      denom += a[i];
+    }
+    for (int i = 0; i < cnt; ++i) {
+      double w = a[i] / denom;
+      for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)tok[i] * d + c]);
+    }
+    free(a);
+    free(tok);
+  }
+}
+
+/* Dense decode attention over every cached token (the "Attn(q_t, K, V)"
+ * expression opening Section 3.5); used only as the K = P special case. */
+void tso_dense_decode_attention(const uint16_t* q, const uint16_t* K, const uint16_t* V,
+                                const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
+                                double scale, double* out) {
+  int G = Hq / Hkv;
+  for (int b = 0; b < B; ++b) {
+    int L = seq_lens[b];
+    for (int g = 0; g < Hq; ++g) {
+      int h = g / G;
+      const uint16_t* qg = q + ((size_t)b * Hq + g) * d;
+      const uint16_t* Kbh = K + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+      const uint16_t* Vbh = V + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+      double* o = out + ((size_t)b * Hq + g) * d;
+      double* a = (double*)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+      double amax = -INFINITY;
+      for (int t = 0; t < L; ++t) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c)
+          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+        a[t] = scale * dot;
+        if (a[t] > amax) amax = a[t];
+      }
+      double denom = 0.0;
+      for (int t = 0; t < L; ++t) {
+        a[t] = exp(a[t] - amax);
+        denom += a[t];
+      }
+      for (int c = 0; c < d; ++c) o[c] = 0.0;
+      for (int t = 0; t < L; ++t) {
+        double w = a[t] / denom;
+        for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)t * d + c]);
+      }
+      free(a);
+    }
+  }
+}
+
+/* The whole decode step of Algorithm 1 for a batch: score -> select -> attend,
+ * with the metadata given.  scores / sel / sel_count / gap are outputs too so
+ * a caller can inspect every stage. */
+void tso_query_aware_decode(const uint16_t* q, const uint16_t* K, const uint16_t* V,
+                            const uint16_t* page_min, const uint16_t* page_max,
+                            const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
+                            int S, int Pmax, int topk, const int32_t* topk_per_seq, int Kmax,
+                            double scale, double* scores, int32_t* sel, int32_t* sel_count,
+                            double* gap, double* out) {
+  tso_score_pages(q, page_min, page_max, seq_lens, B, Hq, Hkv, d, S, Pmax, 0, scores);
+  tso_select_topk_pages(scores, seq_lens, B, Hkv, S, Pmax, topk, topk_per_seq, Kmax, sel,
+                        sel_count, gap);
+  tso_sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, B, Hq, Hkv, Lmax, d, S, Kmax,
+                              scale, out);
+}
+
+/* True per-page maximum of q.k for one query head (the quantity Eq. 2
+ * bounds from above); used by the invariant pin only.
+ * page_best: double [B][Hq][Pmax], -inf for pages j >= P_b. */
+void tso_true_page_max(const uint16_t* q, const uint16_t* K, const int32_t* seq_lens, int B,
+                       int Hq, int Hkv, int Lmax, int d, int S, int Pmax, double* page_best) {
+  int G = Hq / Hkv;
+  for (int b = 0; b < B; ++b) {
+    int L = seq_lens[b];
+    for (int g = 0; g < Hq; ++g) {
+      int h = g / G;
+      const uint16_t* qg = q + ((size_t)b * Hq + g) * d;
+      const uint16_t* Kbh = K + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+      double* row = page_best + ((size_t)b * Hq + g) * Pmax;
+      for (int j = 0; j < Pmax; ++j) row[j] = -INFINITY;
+      for (int t = 0; t < L; ++t) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c)
+          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+        if (t / S < Pmax && dot > row[t / S]) row[t / S] = dot;
+      }
+    }
+  }
+}

@@ -1,0 +1,168 @@
+"""ctypes front end of the CPU oracle (oracle/ts_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product path (paper_2509_12211_amd) never
+imports this module.
+
+Every array is a C-contiguous numpy array: bf16 tensors travel as uint16 bit
+patterns, lengths / selections as int32, results as float64.  Shapes follow the
+header comment of ts_oracle.c (logical [B][Hkv][Lmax][d] keys and values; no
+block table).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ts_oracle.c")
+_LIB = os.path.join(_HERE, "libts_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP for the timed attention loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.tso_version.restype = ctypes.c_int
+        _lib.tso_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().tso_max_threads())
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_pages(seq_lens, S):
+    return (np.asarray(seq_lens, dtype=np.int64) + S - 1) // S
+
+
+def build_page_meta(K, seq_lens, S, Pmax):
+    K = _u16(K)
+    B, Hkv, Lmax, d = K.shape
+    seq_lens = _i32(seq_lens)
+    pmin = np.zeros((B, Hkv, Pmax, d), dtype=np.uint16)
+    pmax = np.zeros((B, Hkv, Pmax, d), dtype=np.uint16)
+    _load().tso_build_page_meta(_p(K), _p(seq_lens), B, Hkv, Lmax, d, S, Pmax, _p(pmin), _p(pmax))
+    return pmin, pmax
+
+
+def append_token_meta(k_new, seq_lens, S, page_min, page_max):
+    """In place on page_min / page_max; seq_lens are the lengths BEFORE the append."""
+    k_new = _u16(k_new)
+    B, Hkv, d = k_new.shape
+    seq_lens = _i32(seq_lens)
+    assert page_min.flags.c_contiguous and page_max.flags.c_contiguous
+    Pmax = page_min.shape[2]
+    _load().tso_append_token_meta(_p(k_new), _p(seq_lens), B, Hkv, d, S, Pmax, _p(page_min),
+                                  _p(page_max))
+
+
+def score_pages(q, page_min, page_max, seq_lens, S, form=0):
+    q = _u16(q)
+    page_min, page_max = _u16(page_min), _u16(page_max)
+    B, Hq, d = q.shape
+    _, Hkv, Pmax, _ = page_min.shape
+    seq_lens = _i32(seq_lens)
+    scores = np.empty((B, Hkv, Pmax), dtype=np.float64)
+    _load().tso_score_pages(_p(q), _p(page_min), _p(page_max), _p(seq_lens), B, Hq, Hkv, d, S,
+                            Pmax, int(form), _p(scores))
+    return scores
+
+
+def select_topk_pages(scores, seq_lens, S, topk, Kmax, topk_per_seq=None):
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    B, Hkv, Pmax = scores.shape
+    seq_lens = _i32(seq_lens)
+    tps = None if topk_per_seq is None else _i32(topk_per_seq)
+    sel = np.empty((B, Hkv, Kmax), dtype=np.int32)
+    cnt = np.empty((B,), dtype=np.int32)
+    gap = np.empty((B, Hkv), dtype=np.float64)
+    _load().tso_select_topk_pages(_p(scores), _p(seq_lens), B, Hkv, S, Pmax, int(topk), _p(tps),
+                                  Kmax, _p(sel), _p(cnt), _p(gap))
+    return sel, cnt, gap
+
+
+def sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, S, scale):
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = K.shape
+    sel, sel_count, seq_lens = _i32(sel), _i32(sel_count), _i32(seq_lens)
+    Kmax = sel.shape[2]
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    _load().tso_sparse_decode_attention(_p(q), _p(K), _p(V), _p(sel), _p(sel_count), _p(seq_lens),
+                                        B, Hq, Hkv, Lmax, d, S, Kmax, ctypes.c_double(scale),
+                                        _p(out))
+    return out
+
+
+def dense_decode_attention(q, K, V, seq_lens, scale):
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = K.shape
+    seq_lens = _i32(seq_lens)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    _load().tso_dense_decode_attention(_p(q), _p(K), _p(V), _p(seq_lens), B, Hq, Hkv, Lmax, d,
+                                       ctypes.c_double(scale), _p(out))
+    return out
+
+
+def query_aware_decode(q, K, V, page_min, page_max, seq_lens, S, topk, Kmax, scale,
+                       topk_per_seq=None):
+    """score -> select -> attend.  Returns dict(scores, sel, sel_count, gap, out)."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    page_min, page_max = _u16(page_min), _u16(page_max)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = K.shape
+    Pmax = page_min.shape[2]
+    seq_lens = _i32(seq_lens)
+    tps = None if topk_per_seq is None else _i32(topk_per_seq)
+    scores = np.empty((B, Hkv, Pmax), dtype=np.float64)
+    sel = np.empty((B, Hkv, Kmax), dtype=np.int32)
+    cnt = np.empty((B,), dtype=np.int32)
+    gap = np.empty((B, Hkv), dtype=np.float64)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    _load().tso_query_aware_decode(_p(q), _p(K), _p(V), _p(page_min), _p(page_max), _p(seq_lens),
+                                   B, Hq, Hkv, Lmax, d, S, Pmax, int(topk), _p(tps), Kmax,
+                                   ctypes.c_double(scale), _p(scores), _p(sel), _p(cnt), _p(gap),
+                                   _p(out))
+    return dict(scores=scores, sel=sel, sel_count=cnt, gap=gap, out=out)
+
+
+def true_page_max(q, K, seq_lens, S, Pmax):
+    q, K = _u16(q), _u16(K)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = K.shape
+    seq_lens = _i32(seq_lens)
+    best = np.empty((B, Hq, Pmax), dtype=np.float64)
+    _load().tso_true_page_max(_p(q), _p(K), _p(seq_lens), B, Hq, Hkv, Lmax, d, S, Pmax, _p(best))
+    return best
