@@ -1,0 +1,303 @@
+"""Benchmark of the query-aware decode hot path on one MI355X.
+
+A step = one decode step of one attention layer over one synthetic batch:
+ts_append_token_meta (one new token per sequence: K/V slot write + incremental
+min/max) followed by the fused single-launch ts_query_aware_decode (score all
+pages, top-K, sparse attention).  Consecutive steps rotate over several
+independent layers (own KV pool, metadata and query), as a model's decode step
+does, so each step finds its metadata and KV pages in HBM rather than in the
+256 MB memory-side cache left warm by the previous step.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "query-aware decode attention µs/step and effective HBM GB/s (% of peak)"
+HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
+
+WORKLOAD_DESC = {
+    "tiny": "configs[0] tiny single-head: B1 1q/1kv d64 L4096 S16 K32",
+    "gpt2_345m": "configs[1] GPT2-345M-shaped MHA: B8 16q/16kv d64 L8192 S16 K64, permuted pool",
+    "tinyllama": "configs[2] TinyLLaMA-shaped GQA: B16 32q/4kv d64 L16384 S16 K128, outlier channels",
+    "longctx": "configs[3] long-context GQA: B4 32q/4kv d64 L131072 S32 K128, random-walk keys",
+    "ragged": "configs[4] ragged serving batch: 64 seqs L~U[1024,32768] 32q/32kv d128 S16 budget 25%",
+}
+
+
+class Layer:
+    """One attention layer's device state + pre-marshalled C arguments."""
+
+    def __init__(self, ts, wl, spec, seed, dev, n_q):
+        import torch
+        self.w = w = wl.make_workload(spec, dev, seed=seed, n_q=n_q, n_new=1, poison=0.0)
+        self.page_min = torch.zeros((spec.B, spec.Hkv, w.P_max, spec.d), dtype=torch.bfloat16,
+                                    device=dev)
+        self.page_max = torch.zeros_like(self.page_min)
+        self.seq_lens = w.seq_lens.clone()
+        self.layout = ts.make_layout(spec.B, spec.Hq, spec.Hkv, spec.d, spec.S, w.P_max, w.k_pool,
+                                     w.v_pool, w.block_table, self.seq_lens, self.page_min,
+                                     self.page_max)
+        self.out = torch.zeros((spec.B, spec.Hq, spec.d), dtype=torch.float32, device=dev)
+        self.ws = ts.new_workspace(self.layout, w.K_max, dev)
+        ts.build_page_meta(self.layout)
+        lib = ts.lib()
+        vp = ctypes.c_void_p
+        lay = ctypes.byref(self.layout)
+        scale = 1.0 / math.sqrt(spec.d)
+        tps = None if w.topk_per_seq is None else vp(w.topk_per_seq.data_ptr())
+        self._append = (lib.ts_append_token_meta, (lay, vp(w.k_new[0].data_ptr()),
+                                                   vp(w.v_new[0].data_ptr()), 1))
+        self._fused = [(lib.ts_query_aware_decode,
+                        (lay, vp(w.q[i].data_ptr()), w.topk, tps, w.K_max, scale,
+                         vp(self.out.data_ptr()), None, None, None, vp(self.ws.data_ptr()),
+                         self.ws.numel())) for i in range(n_q)]
+
+    def append(self, stream):
+        f, a = self._append
+        st = f(*a, stream)
+        if st != 0:
+            raise RuntimeError(f"ts_append_token_meta -> {st}")
+
+    def fused(self, stream, qi=0):
+        f, a = self._fused[qi % len(self._fused)]
+        st = f(*a, stream)
+        if st != 0:
+            raise RuntimeError(f"ts_query_aware_decode -> {st}")
+
+    def reset_lengths(self):
+        self.seq_lens.copy_(self.w.seq_lens)
+
+
+def time_region(torch, fn, n):
+    """Host wall time and HIP-event time of n calls of fn(i), synchronised on both sides."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(n):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0), e0.elapsed_time(e1) * 1e-3
+
+
+def cpu_baseline(spec, layer, wl, budget_s=20.0):
+    """The CPU oracle, as it stands, on the same step (score + select + attend over
+    the layer's metadata and KV) for a bounded number of sequences / repetitions."""
+    import numpy as np
+    from oracle import ts_oracle as oracle
+    w = layer.w
+    lens_all = layer.seq_lens.cpu()
+    # bound host memory / time: at most ~1 GiB of logical KV per tensor
+    per_seq = spec.Hkv * int(lens_all.max()) * spec.d * 2
+    n_seq = max(1, min(spec.B, (1 << 30) // max(per_seq, 1)))
+    seqs = list(range(n_seq))
+    K, V = wl.logical_kv(w, seqs=seqs, seq_lens=lens_all)
+    L = lens_all[:n_seq].numpy().astype(np.int32)
+    Kb, Vb, qb = wl.bits(K), wl.bits(V), wl.bits(w.q[0][:n_seq])
+    pmin, pmax = wl.bits(layer.page_min[:n_seq]), wl.bits(layer.page_max[:n_seq])
+    tps = None if w.topk_per_seq is None else w.topk_per_seq[:n_seq].cpu().numpy()
+    scale = 1.0 / math.sqrt(spec.d)
+    times = []
+    t_start = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        oracle.query_aware_decode(qb, Kb, Vb, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
+                                  topk_per_seq=tps)
+        times.append(time.perf_counter() - t0)
+        if len(times) >= 3 and time.perf_counter() - t_start > 0.5 * budget_s:
+            break
+        if time.perf_counter() - t_start > budget_s:
+            break
+    med = sorted(times)[len(times) // 2]
+    us_step = med * 1e6 * spec.B / n_seq
+    return {"value": round(us_step, 1), "unit": "us/step", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"{n_seq} of {spec.B} sequences (all KV heads), score+select+attend, "
+                      f"median of {len(times)} runs scaled by {spec.B}/{n_seq}; attention loop "
+                      f"OpenMP over query heads, scoring and selection single-threaded"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="tinyllama", choices=list(WORKLOAD_DESC))
+    ap.add_argument("--layers", type=int, default=0, help="independent layers rotated (0 = auto)")
+    ap.add_argument("--launch", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_12211_amd import tinyserve as ts
+    from paper_2509_12211_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    spec = wl.SPECS[args.workload]
+    lens_nom = torch.full((spec.B,), spec.L, dtype=torch.int32)
+    nominal = wl.algorithmic_bytes(spec, lens_nom) if not spec.L_min else None
+
+    # enough layers that one rotation touches >= 768 MiB (3x the memory-side cache)
+    step_bytes_guess = (nominal["total"] if nominal else 5 << 30)
+    n_layers = args.layers or int(min(16, max(1, math.ceil((768 << 20) / step_bytes_guess))))
+    steps, warmup = args.steps, args.warmup
+    appends_per_layer = (steps + warmup) // n_layers + 2
+    spec = wl.scaled(spec, headroom=max(16, appends_per_layer * 3 + 8))
+    n_q = 4
+    layers = [Layer(ts, wl, spec, 1000 + 17 * i, dev, n_q) for i in range(n_layers)]
+    torch.cuda.synchronize()
+    by = wl.algorithmic_bytes(spec, layers[0].seq_lens, layers[0].w.topk_per_seq)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def step(i):
+        ly = layers[i % n_layers]
+        ly.append(stream)
+        ly.fused(stream, i // n_layers)
+
+    def fused_only(i):
+        layers[i % n_layers].fused(stream, i // n_layers)
+
+    launch = args.launch
+
+    def capture(body):
+        """Capture one rotation over the layers (kernel nodes only, no memset nodes)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            gstream = ctypes.c_void_p(side.cuda_stream)
+            for i in range(n_layers):       # warm the kernels on the capture stream
+                body(layers[i], gstream)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(n_layers):
+                    body(layers[i], gstream)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return g
+
+    def body_step(ly, st):
+        ly.append(st)
+        ly.fused(st, 0)
+
+    def body_fused(ly, st):
+        ly.fused(st, 0)
+
+    graph = graph_fused = None
+    if launch == "graph":
+        try:
+            graph = capture(body_step)
+            graph_fused = capture(body_fused)
+        except Exception as e:   # fall back to eager launches, and say so
+            print(f"bench.py: graph capture failed ({e}); using eager launches", file=sys.stderr)
+            graph = graph_fused = None
+            launch = "eager"
+
+    # ---- timed region: exactly `steps` steps -------------------------------------
+    if graph is not None:
+        reps_w = max(1, warmup // n_layers)
+        reps = max(1, steps // n_layers)
+        steps, warmup = reps * n_layers, reps_w * n_layers
+        for _ in range(reps_w):
+            graph.replay()
+        wall, ev = time_region(torch, lambda i: graph.replay(), reps)
+    else:
+        for i in range(warmup):
+            step(i)
+        wall, ev = time_region(torch, step, steps)
+    us_step = wall / steps * 1e6
+    for ly in layers:
+        assert ts.workspace_status(ly.ws) == 0, "a bounded wait expired inside the fused kernel"
+
+    # ---- roofline leg: the fused kernel alone, HIP events on its stream -----------
+    n_roof = steps
+    if graph_fused is not None:
+        graph_fused.replay()
+        _, ev_fused = time_region(torch, lambda i: graph_fused.replay(), n_roof // n_layers)
+    else:
+        for i in range(min(warmup, 2 * n_layers)):
+            fused_only(i)
+        _, ev_fused = time_region(torch, fused_only, n_roof)
+    fused_us = ev_fused / n_roof * 1e6
+    achieved = by["total"] / (fused_us * 1e-6) / 1e9
+
+    # ---- other entry points, for the record ---------------------------------------
+    _, ev_b = time_region(torch, lambda i: ts.build_page_meta(layers[i % n_layers].layout),
+                          2 * n_layers)
+    build_us = ev_b / (2 * n_layers) * 1e6
+    for ly in layers:
+        ly.reset_lengths()
+        ts.build_page_meta(ly.layout)
+    _, ev_a = time_region(torch, lambda i: layers[i % n_layers].append(stream), 2 * n_layers)
+    append_us = ev_a / (2 * n_layers) * 1e6
+
+    result = {
+        "metric": METRIC,
+        "value": round(us_step, 3),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": round(us_step * 1e-3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "effective_GBps": round(by["total"] / (us_step * 1e-6) / 1e9, 1),
+        "pct_of_hbm_peak": round(100.0 * by["total"] / (us_step * 1e-6) / HBM_PEAK, 2),
+        "config": {
+            "workload": WORKLOAD_DESC[args.workload],
+            "step": "ts_append_token_meta + fused ts_query_aware_decode, one layer",
+            "layers_rotated": n_layers,
+            "launch": launch,
+            "softmax_scale": "1/sqrt(d)",
+            "bytes_per_step": by,
+            "device_event_us_per_step": round(ev / steps * 1e6, 3),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "query_aware_decode_kernel",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK / 1e9,
+            "unit": "GB/s",
+            "frac": round(achieved * 1e9 / HBM_PEAK, 4),
+            "traffic": None,
+            "us_per_launch": round(fused_us, 3),
+            "launches": n_roof,
+        },
+        "other_kernels_us": {"ts_build_page_meta": round(build_us, 2),
+                             "ts_append_token_meta": round(append_us, 2)},
+    }
+    if not args.no_cpu_baseline:
+        layers[0].reset_lengths()
+        ts.build_page_meta(layers[0].layout)
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = cpu_baseline(spec, layers[0], wl, args.cpu_budget)
+    print(json.dumps(result, ensure_ascii=False), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,169 @@
+/*
+ * tinyserve.h -- C ABI of the MI355X (gfx950) query-aware decode-attention library.
+ *
+ * The operations are the decode-time hot path of TinyServe:
+ *   - every KV page carries bounding-box metadata, the channel-wise min and max
+ *     of its keys (Section 3.4; Eq. 1, phi(K_j) = (m_j, M_j));
+ *   - a query scores every page with the directional bounding-box estimator
+ *     r(q, phi_j) = sum_i q_i * (q_i >= 0 ? M_ji : m_ji)
+ *                 = sum_i max(q_i * m_ji, q_i * M_ji)                    (Eq. 2);
+ *   - the K highest-scoring pages are selected (Section 3.5, S_t = TopK_j r);
+ *   - single-query softmax attention runs over the tokens of the selected
+ *     pages only (Section 3.5, SparseAttn; Algorithm 1, steps 3-4).
+ * Algorithm 1 fuses the last three into one kernel; ts_query_aware_decode is
+ * that fused, single-launch form.  The paper is silent on heads: here a unit of
+ * work is one (sequence, KV head); with grouped-query attention the page score
+ * of a KV head is the sum of r over the G = Hq / Hkv query heads sharing it.
+ *
+ * Conventions
+ *   - All pointers are DEVICE pointers unless marked "host".  The caller owns
+ *     every buffer; the library allocates nothing and keeps no state between
+ *     calls except what lives in the caller's workspace.
+ *   - bf16 tensors are raw 16-bit patterns.  `stream` is a hipStream_t cast to
+ *     void* (NULL = the default stream).  Calls enqueue work and return; they
+ *     never synchronise.
+ *   - Every function returns TS_OK or a negative ts_status.  Validation is done
+ *     on the host from the struct fields and scalar arguments only; device-side
+ *     contents (seq_lens, block_table, sel) are trusted: seq_lens[b] must lie in
+ *     [0, max_pages_per_seq * page_size], block_table entries of pages that
+ *     hold tokens must lie in [0, num_phys_pages).
+ *   - P_b = ceil(seq_lens[b] / page_size) is the number of pages of sequence b
+ *     (Section 3.5, P = ceil(t / S)).  A partly filled last page is summarised,
+ *     scored and attended over the tokens it holds; pool slots past seq_lens[b]
+ *     may hold anything (NaN included) and never influence a result.
+ *
+ * Supported shapes: head_dim in {64, 128}; page_size in {16, 32};
+ * 1 <= G = Hq / Hkv <= 16; max_pages_per_seq <= TS_MAX_PAGES_PER_SEQ.
+ */
+#ifndef TINYSERVE_H_
+#define TINYSERVE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TS_MAX_PAGES_PER_SEQ 32768
+
+typedef enum ts_status {
+  TS_OK = 0,
+  TS_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  TS_ERR_SHAPE = -2,       /* non-positive dimension, Hq % Hkv != 0, topk < 1, max_topk < topk */
+  TS_ERR_UNSUPPORTED = -3, /* head_dim / page_size / group size / page count outside the built set */
+  TS_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than ts_workspace_bytes()             */
+  TS_ERR_LAUNCH = -5,      /* the HIP runtime reported an error when enqueueing             */
+  TS_ERR_DEVICE = -6       /* no usable HIP device                                          */
+} ts_status;
+
+/* Paged KV cache of one attention layer plus its page metadata.
+ *   k_pool      bf16 [num_phys_pages][Hkv][S][d]   a (page, head) K tile is S*d contiguous
+ *   v_pool      bf16 [num_phys_pages][Hkv][d][S]   V tile stored channel-major (transposed),
+ *                                                  so the token axis is contiguous
+ *   block_table int32 [B][P_max]                   logical page -> physical page
+ *   seq_lens    int32 [B]                          tokens currently cached per sequence
+ *   page_min,
+ *   page_max    bf16 [B][Hkv][P_max][d]            metadata in LOGICAL page order, so the
+ *                                                  scoring pass is one contiguous stream
+ */
+typedef struct ts_layout {
+  int32_t num_seqs;          /* B                                   */
+  int32_t num_q_heads;       /* Hq                                  */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0                  */
+  int32_t head_dim;          /* d                                   */
+  int32_t page_size;         /* S                                   */
+  int32_t max_pages_per_seq; /* P_max: row stride of block_table, page_min, page_max, scores */
+  int32_t num_phys_pages;    /* pool capacity                       */
+  int32_t reserved;          /* must be 0                           */
+  void* k_pool;
+  void* v_pool;
+  const int32_t* block_table;
+  int32_t* seq_lens;
+  void* page_min;
+  void* page_max;
+} ts_layout;
+
+/* Section 3.4 / Eq. 1.  Rebuilds page_min / page_max of every page j < P_b of
+ * every (sequence, KV head) from k_pool.  Rows of pages j >= P_b are not
+ * written.  min / max of bf16 values are exact. */
+int ts_build_page_meta(const ts_layout* layout, void* stream);
+
+/* Section 3.4 ("metadata ... is maintained").  Appends one token per sequence
+ * at position p = seq_lens[b]: page j = p / S; if p % S == 0 the page is
+ * opened (m = M = k_new) else its box is widened.  k_new, v_new: bf16
+ * [B][Hkv][d].  If v_new != NULL the token's key and value are also stored
+ * into the pool slot (block_table[b][j], h, p % S); if v_new == NULL only the
+ * metadata is updated (the caller has stored K/V itself).  With
+ * advance_seq_lens != 0 the kernel increments seq_lens[b] after use.  A
+ * sequence whose page j would be >= P_max is left unchanged. */
+int ts_append_token_meta(const ts_layout* layout, const void* k_new, const void* v_new,
+                         int advance_seq_lens, void* stream);
+
+/* Eq. 2, step 1 of Algorithm 1.  q: bf16 [B][Hq][d].  scores: fp32
+ * [B][Hkv][P_max]; entry (b, h, j) is the group-summed bound for j < P_b and
+ * -inf for j >= P_b.  fp32 accumulation. */
+int ts_score_pages(const ts_layout* layout, const void* q, float* scores, void* stream);
+
+/* Section 3.5 (S_t = TopK_j r, |S_t| = K), step 2 of Algorithm 1.  For each
+ * (b, h) keeps the K_b = min(K, P_b, max_topk) pages with the largest score,
+ * equal scores resolved in favour of the lower page id; K = topk_per_seq[b] if
+ * that pointer is non-NULL, else topk.  sel: int32 [B][Hkv][max_topk], page
+ * ids ascending, padded with -1.  sel_count: int32 [B] = K_b.  The comparison
+ * is on the fp32 values as given (-0 ranks equal to +0; NaN is undefined). */
+int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t topk,
+                         const int32_t* topk_per_seq, int32_t max_topk, int32_t* sel,
+                         int32_t* sel_count, void* stream);
+
+/* Section 3.5 SparseAttn; steps 3-4 of Algorithm 1.  For every query head:
+ * logits softmax_scale * q.k over the valid tokens of the pages listed in sel
+ * (first sel_count[b] entries of each row), softmax over exactly those tokens,
+ * weighted sum of their values.  The paper writes softmax(q.k) with no factor:
+ * softmax_scale = 1 is its literal form, 1/sqrt(d) the usual one.
+ * out: fp32 [B][Hq][d]; a (b, head) with no token gets zeros.  bf16 inputs,
+ * fp32 accumulation.  workspace: ts_workspace_bytes(layout, max_topk) bytes,
+ * initialised once with ts_workspace_init. */
+int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
+                               const int32_t* sel_count, int32_t max_topk, float softmax_scale,
+                               float* out, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/* Algorithm 1 as ONE kernel launch: score -> select -> gather -> attend.
+ * Arguments as in the three staged calls.  scores_out (fp32 [B][Hkv][P_max]),
+ * sel_out (int32 [B][Hkv][max_topk]) and sel_count_out (int32 [B]) are
+ * optional (NULL = not reported). */
+int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
+                          const int32_t* topk_per_seq, int32_t max_topk, float softmax_scale,
+                          float* out, float* scores_out, int32_t* sel_out,
+                          int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* Host-only: bytes of workspace the two calls above need for this layout and
+ * max_topk (0 on invalid arguments).  Reads only the scalar fields. */
+size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk);
+
+/* Zeroes the workspace's control words.  Required once after allocation (and
+ * after a launch that was aborted); every call leaves them zero again, so
+ * repeated calls need no re-initialisation.  Calls sharing one workspace must
+ * be ordered on one stream. */
+int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* Blocking: copies the workspace's sticky error word to *status_host (host
+ * pointer).  0 = no error; non-zero = a bounded wait inside the fused kernel
+ * expired (results of that launch are invalid). */
+int ts_workspace_status(const void* workspace, int32_t* status_host);
+
+/* Launch-shape overrides for tuning sweeps; 0 restores the built-in choice.
+ *   scan_pages_per_task  pages one workgroup scores per work item (multiple of 32)
+ *   num_splits           workgroups sharing the selected pages of one (b, h)
+ *   workgroups_per_cu    resident workgroups per compute unit of the fused kernel
+ * Process-wide; affects ts_workspace_bytes too, so set it before sizing. */
+int ts_set_tuning(int32_t scan_pages_per_task, int32_t num_splits, int32_t workgroups_per_cu);
+
+const char* ts_strerror(int status);
+int ts_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TINYSERVE_H_ */

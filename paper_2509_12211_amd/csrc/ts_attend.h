@@ -1,0 +1,300 @@
+// Sparse single-query attention over the selected pages (Section 3.5 SparseAttn;
+// steps 3-4 of Algorithm 1) with bf16 MFMA and an online softmax, split over
+// workgroups (flash-decoding style partial softmax + combine).
+//
+// One wavefront processes whole pages.  Per 16-token tile it computes
+//   St[token][head] = K_tile[token][:] . Q^T[:][head]        (v_mfma_f32_16x16x16_bf16)
+//   Ot[chan ][head] += V_tile^T[chan][token] . P^T[token][head]
+// The accumulator layout of the first product (lane -> head lane%16, tokens
+// 4*(lane/16)..+3) is exactly the B-operand layout of the second, so the
+// softmax weights never leave their lane; the head index stays lane%16 in both
+// products, so the running max / sum / rescale factor are per-lane scalars.
+// K tiles [S][D] and V tiles [D][S] (channel-major) let every lane fetch its
+// operand with plain 8/16-byte loads; nothing is transposed on chip.
+#pragma once
+#include "ts_device.h"
+
+namespace ts {
+
+typedef uint32_t uint2v_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ short4_t as_short4(uint32_t a, uint32_t b) {
+  uint2v_t w = {a, b};
+  return __builtin_bit_cast(short4_t, w);
+}
+
+__device__ __forceinline__ float4_t mfma16(short4_t a, short4_t b, float4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+}
+
+struct AttendParams {
+  const uint16_t* q;           // [B][Hq][D]
+  const uint16_t* k_pool;      // [n_phys][Hkv][S][D]
+  const uint16_t* v_pool;      // [n_phys][Hkv][D][S]
+  const int32_t* block_table;  // [B][Pmax]
+  const int32_t* seq_lens;     // [B]
+  float* out;                  // [B][Hq][D]
+  float* partials;             // [B*Hkv][n_split][G][D+2]
+  int Hq, Hkv, G, Pmax, Kmax, n_phys, n_split, chunk;
+  float scale_log2;            // softmax_scale * log2(e)
+};
+
+template <int D, int S>
+struct PageFrag {
+  static constexpr int NT = S / 16;   // 16-token tiles per page
+  static constexpr int KQ = D / 32;   // 16-byte K loads per lane per tile (D/4 channels)
+  static constexpr int NCB = D / 16;  // 16-channel output blocks
+  uint4 k[NT][KQ];
+  uint2 v[NT][NCB];
+};
+
+// Token held by MFMA row r of tile t.  For S = 32 the rows are permuted so that
+// the eight tokens a lane needs for the two P.V products are contiguous in the
+// channel-major V tile.
+template <int S>
+__device__ __forceinline__ int tile_token(int t, int r) {
+  return S == 16 ? r : 8 * (r >> 2) + 4 * t + (r & 3);
+}
+
+template <int D, int S>
+__device__ __forceinline__ void zero_page(PageFrag<D, S>& f) {
+#pragma unroll
+  for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, S>::KQ; ++i) f.k[t][i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, S>::NCB; ++i) f.v[t][i] = make_uint2(0, 0);
+  }
+}
+
+template <int D, int S>
+__device__ __forceinline__ void load_page(PageFrag<D, S>& f, const uint16_t* ktile,
+                                          const uint16_t* vtile) {
+  const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
+#pragma unroll
+  for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
+    const uint16_t* krow = ktile + tile_token<S>(t, r) * D + kb * (D / 4);
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, S>::KQ; ++i)
+      f.k[t][i] = *reinterpret_cast<const uint4*>(krow + i * 8);
+  }
+#pragma unroll
+  for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) {
+    const uint16_t* vrow = vtile + (16 * cb + r) * S;
+    if (S == 16) {
+      f.v[0][cb] = *reinterpret_cast<const uint2*>(vrow + 4 * kb);
+    } else {
+      const uint4 w = *reinterpret_cast<const uint4*>(vrow + 8 * kb);
+      f.v[0][cb] = make_uint2(w.x, w.y);
+      f.v[S == 16 ? 0 : 1][cb] = make_uint2(w.z, w.w);
+    }
+  }
+}
+
+template <int D>
+struct WaveAcc {
+  float m, l;  // running max (log2 domain) and this lane's share of the running sum
+  float4_t o[D / 16];
+  __device__ __forceinline__ void init() {
+    m = -1e30f;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] = float4_t{0.f, 0.f, 0.f, 0.f};
+  }
+};
+
+// Query operand: lane (head = lane%16, kb = lane/16) holds q[head][kb*D/4 .. +D/4).
+template <int D>
+__device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16_t* q_group,
+                                            int G) {
+  const int lane = lane_id(), head = lane & 15, kb = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) {
+    uint4 w = make_uint4(0, 0, 0, 0);
+    if (head < G)
+      w = *reinterpret_cast<const uint4*>(q_group + (size_t)head * D + kb * (D / 4) + i * 8);
+    qf[2 * i] = as_short4(w.x, w.y);
+    qf[2 * i + 1] = as_short4(w.z, w.w);
+  }
+}
+
+// One page: logits, online-softmax update, weighted value accumulation.
+// `valid` = number of tokens the page holds (tokens >= valid are masked).
+template <int D, int S>
+__device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short4_t (&qf)[D / 16],
+                                            int valid, float scale_log2, WaveAcc<D>& a) {
+  constexpr int NT = PageFrag<D, S>::NT, NCB = PageFrag<D, S>::NCB;
+  const int kb = lane_id() >> 4;
+  float4_t sc[NT];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    sc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+      sc[t] = mfma16(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
+      sc[t] = mfma16(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int tok = tile_token<S>(t, 4 * kb + v);
+      const float x = tok < valid ? sc[t][v] * scale_log2 : -INFINITY;
+      sc[t][v] = x;
+      mx = fmaxf(mx, x);
+    }
+  }
+  mx = fmaxf(mx, shfl_xor_f(mx, 16));
+  mx = fmaxf(mx, shfl_xor_f(mx, 32));
+  const float m_new = fmaxf(a.m, mx);
+  const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
+  a.m = m_new;
+  a.l *= alpha;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) a.o[cb] *= alpha;
+  const bool partial = valid < S;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    // softmax weights split into two bf16 terms (truncated high part + remainder)
+    // so the P.V product keeps ~16 significant bits of each weight
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float pv = __builtin_amdgcn_exp2f(sc[t][v] - m_new);
+      a.l += pv;
+      hi[v] = __float_as_uint(pv) & 0xffff0000u;
+      lo[v] = __float_as_uint(pv - __uint_as_float(hi[v]));
+    }
+    const short4_t ph = as_short4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+    const short4_t pl = as_short4((lo[0] >> 16) | (lo[1] & 0xffff0000u),
+                                  (lo[2] >> 16) | (lo[3] & 0xffff0000u));
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      uint32_t v0 = f.v[t][cb].x, v1 = f.v[t][cb].y;
+      if (partial) {  // slots past the sequence end may hold anything: zero them
+        const int t0 = tile_token<S>(t, 4 * kb);
+        if (t0 + 0 >= valid) v0 &= 0xffff0000u;
+        if (t0 + 1 >= valid) v0 &= 0x0000ffffu;
+        if (t0 + 2 >= valid) v1 &= 0xffff0000u;
+        if (t0 + 3 >= valid) v1 &= 0x0000ffffu;
+      }
+      const short4_t vf = as_short4(v0, v1);
+      a.o[cb] = mfma16(vf, ph, a.o[cb]);
+      a.o[cb] = mfma16(vf, pl, a.o[cb]);
+    }
+  }
+}
+
+// The workgroup attends the selected pages sel_row[c_begin .. c_end) of unit
+// (b, h); wave w takes entries c_begin + w, + kWaves, ...  The four wave states
+// are merged through LDS (lds: kWaves * G * (D + 2) floats).  With n_split == 1
+// the normalised result goes to `out`; otherwise the unnormalised partial
+// (o[D], m, l per head) goes to p.partials for combine_splits().
+template <int D, int S>
+__device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
+                                             const int32_t* sel_row, int Kb, float* lds) {
+  const int lane = lane_id(), wave = wave_id();
+  const int head = lane & 15, kb = lane >> 4;
+  const int G = p.G;
+  const int L = uniform(p.seq_lens[b]);
+  Kb = uniform(Kb);
+  const int c_begin = min(split * p.chunk, Kb), c_end = min(c_begin + p.chunk, Kb);
+  const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
+
+  short4_t qf[D / 16];
+  load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  WaveAcc<D> acc;
+  acc.init();
+
+  for (int batch = c_begin + wave; batch < c_end; batch += kWave * kWaves) {
+    // lane x holds the ids of this wave's x-th page of the batch
+    const int my_i = batch + lane * kWaves;
+    int my_j = -1, my_phys = -1;
+    if (my_i < c_end) {
+      my_j = sel_row[my_i];
+      if (my_j >= 0 && my_j < p.Pmax) my_phys = bt_row[my_j];
+    }
+    const int n = min(kWave, (c_end - batch + kWaves - 1) / kWaves);
+    PageFrag<D, S> fa, fb;
+    auto issue = [&](PageFrag<D, S>& f, int x) -> int {
+      const int j = __builtin_amdgcn_readlane(my_j, x);
+      const int phys = __builtin_amdgcn_readlane(my_phys, x);
+      if (phys < 0 || phys >= p.n_phys) {
+        zero_page(f);
+        return 0;
+      }
+      const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)(S * D);
+      load_page<D, S>(f, p.k_pool + tile, p.v_pool + tile);
+      return max(0, min(S, L - j * S));
+    };
+    int va = issue(fa, 0), vb = 0;
+    for (int x = 0; x < n; x += 2) {
+      if (x + 1 < n) vb = issue(fb, x + 1);
+      attend_page<D, S>(fa, qf, va, p.scale_log2, acc);
+      if (x + 1 < n) {
+        if (x + 2 < n) va = issue(fa, x + 2);
+        attend_page<D, S>(fb, qf, vb, p.scale_log2, acc);
+      }
+    }
+  }
+
+  // merge the wave states
+  float l = acc.l;
+  l += shfl_xor_f(l, 16);
+  l += shfl_xor_f(l, 32);
+  constexpr int RS = D + 2;
+  if (head < G) {
+    float* row = lds + ((size_t)wave * G + head) * RS;
+#pragma unroll
+    for (int cb = 0; cb < D / 16; ++cb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) row[16 * cb + 4 * kb + v] = acc.o[cb][v];
+    if (kb == 0) { row[D] = acc.m; row[D + 1] = l; }
+  }
+  __syncthreads();
+  float* part = p.partials + (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
+  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    const int g = idx / D, c = idx % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, lds[((size_t)w * G + g) * RS + D]);
+    float Lsum = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float* row = lds + ((size_t)w * G + g) * RS;
+      const float wgt = __builtin_amdgcn_exp2f(row[D] - M);
+      Lsum += row[D + 1] * wgt;
+      O += row[c] * wgt;
+    }
+    if (p.n_split == 1) {
+      p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+    } else {
+      part[(size_t)g * RS + c] = O;
+      if (c == 0) { part[(size_t)g * RS + D] = M; part[(size_t)g * RS + D + 1] = Lsum; }
+    }
+  }
+  __syncthreads();  // lds is reused by the caller's next work item
+}
+
+// Merge the n_split partials of unit (b, h) and write the normalised output.
+// The caller has established that all partials are visible.
+template <int D>
+__device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int h) {
+  constexpr int RS = D + 2;
+  const int G = p.G;
+  const float* part = p.partials + ((size_t)b * p.Hkv + h) * p.n_split * (size_t)G * RS;
+  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    const int g = idx / D, c = idx % D;
+    float M = -INFINITY;
+    for (int s = 0; s < p.n_split; ++s) M = fmaxf(M, part[((size_t)s * G + g) * RS + D]);
+    float Lsum = 0.f, O = 0.f;
+    for (int s = 0; s < p.n_split; ++s) {
+      const float* row = part + ((size_t)s * G + g) * RS;
+      const float wgt = __builtin_amdgcn_exp2f(row[D] - M);
+      Lsum += row[D + 1] * wgt;
+      O += row[c] * wgt;
+    }
+    p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+  }
+}
+
+}  // namespace ts

@@ -1,0 +1,178 @@
+"""Thin ctypes binding over libtinyserve_hip.so (C ABI in include/tinyserve.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP
+kernels.  Tensors are torch CUDA(ROCm) tensors used purely as device buffers;
+the launch goes to torch's current stream.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtinyserve_hip.so")
+
+TS_OK = 0
+TS_ERR_NULL = -1
+TS_ERR_SHAPE = -2
+TS_ERR_UNSUPPORTED = -3
+TS_ERR_WORKSPACE = -4
+TS_ERR_LAUNCH = -5
+TS_ERR_DEVICE = -6
+
+EXPORTS = [
+    "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
+    "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_workspace_bytes",
+    "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
+]
+
+
+class TsLayout(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+        ("num_phys_pages", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+        ("page_min", ctypes.c_void_p), ("page_max", ctypes.c_void_p),
+    ]
+
+
+class TinyServeError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first "
+                "(python -c 'import __graft_entry__ as g; g.build()'); there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
+        lp = ctypes.POINTER(TsLayout)
+        L.ts_build_page_meta.argtypes = [lp, vp]
+        L.ts_append_token_meta.argtypes = [lp, vp, vp, ctypes.c_int, vp]
+        L.ts_score_pages.argtypes = [lp, vp, vp, vp]
+        L.ts_select_topk_pages.argtypes = [lp, vp, i32, vp, i32, vp, vp, vp]
+        L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_workspace_bytes.argtypes = [lp, i32]
+        L.ts_workspace_bytes.restype = sz
+        L.ts_workspace_init.argtypes = [vp, sz, vp]
+        L.ts_workspace_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
+        L.ts_set_tuning.argtypes = [i32, i32, i32]
+        L.ts_strerror.argtypes = [ctypes.c_int]
+        L.ts_strerror.restype = ctypes.c_char_p
+        L.ts_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().ts_strerror(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != TS_OK:
+        raise TinyServeError(status, where)
+
+
+def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, page_min,
+                page_max) -> TsLayout:
+    """Fill the C struct; tensors must stay alive while calls using it are in flight."""
+    n_phys = 0 if k_pool is None else k_pool.shape[0]
+    lay = TsLayout(B, Hq, Hkv, d, S, P_max, n_phys, 0,
+                   None if k_pool is None else k_pool.data_ptr(),
+                   None if v_pool is None else v_pool.data_ptr(),
+                   None if block_table is None else block_table.data_ptr(),
+                   None if seq_lens is None else seq_lens.data_ptr(),
+                   None if page_min is None else page_min.data_ptr(),
+                   None if page_max is None else page_max.data_ptr())
+    return lay
+
+
+def build_page_meta(layout):
+    _check(lib().ts_build_page_meta(ctypes.byref(layout), _stream()), "ts_build_page_meta")
+
+
+def append_token_meta(layout, k_new, v_new=None, advance_seq_lens=True):
+    _check(lib().ts_append_token_meta(ctypes.byref(layout), _ptr(k_new), _ptr(v_new),
+                                      1 if advance_seq_lens else 0, _stream()),
+           "ts_append_token_meta")
+
+
+def score_pages(layout, q, scores):
+    _check(lib().ts_score_pages(ctypes.byref(layout), _ptr(q), _ptr(scores), _stream()),
+           "ts_score_pages")
+
+
+def select_topk_pages(layout, scores, topk, max_topk, sel, sel_count, topk_per_seq=None):
+    _check(lib().ts_select_topk_pages(ctypes.byref(layout), _ptr(scores), int(topk),
+                                      _ptr(topk_per_seq), int(max_topk), _ptr(sel),
+                                      _ptr(sel_count), _stream()), "ts_select_topk_pages")
+
+
+def workspace_bytes(layout, max_topk) -> int:
+    return int(lib().ts_workspace_bytes(ctypes.byref(layout), int(max_topk)))
+
+
+def workspace_init(workspace):
+    _check(lib().ts_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream()), "ts_workspace_init")
+
+
+def workspace_status(workspace) -> int:
+    v = ctypes.c_int32(0)
+    _check(lib().ts_workspace_status(_ptr(workspace), ctypes.byref(v)), "ts_workspace_status")
+    return int(v.value)
+
+
+def new_workspace(layout, max_topk, device) -> torch.Tensor:
+    """Allocate (with torch) and initialise a workspace for this layout."""
+    n = workspace_bytes(layout, max_topk)
+    if n == 0:
+        raise TinyServeError(TS_ERR_SHAPE, "ts_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    workspace_init(ws)
+    return ws
+
+
+def sparse_decode_attention(layout, q, sel, sel_count, max_topk, softmax_scale, out, workspace):
+    _check(lib().ts_sparse_decode_attention(
+        ctypes.byref(layout), _ptr(q), _ptr(sel), _ptr(sel_count), int(max_topk),
+        float(softmax_scale), _ptr(out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream()), "ts_sparse_decode_attention")
+
+
+def query_aware_decode(layout, q, topk, max_topk, softmax_scale, out, workspace,
+                       topk_per_seq=None, scores_out=None, sel_out=None, sel_count_out=None):
+    _check(lib().ts_query_aware_decode(
+        ctypes.byref(layout), _ptr(q), int(topk), _ptr(topk_per_seq), int(max_topk),
+        float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out), _ptr(sel_count_out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+        "ts_query_aware_decode")
+
+
+def set_tuning(scan_pages_per_task=0, num_splits=0, workgroups_per_cu=0):
+    _check(lib().ts_set_tuning(int(scan_pages_per_task), int(num_splits),
+                               int(workgroups_per_cu)), "ts_set_tuning")

@@ -1,0 +1,116 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every
+symbol include/tinyserve.h declares, and validates arguments on the host
+(error codes come back without any device work)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_12211_amd import tinyserve as ts
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    with open(os.path.join(ROOT, "include", "tinyserve.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ts.lib()
+    names = declared_symbols()
+    assert set(names) == set(ts.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.ts_version() >= 1
+    assert ts.strerror(ts.TS_OK) == "ok"
+    assert "workspace" in ts.strerror(ts.TS_ERR_WORKSPACE)
+
+
+def _layout(**kw):
+    base = dict(num_seqs=2, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16,
+                max_pages_per_seq=64, num_phys_pages=128, reserved=0,
+                k_pool=0x1000, v_pool=0x1000, block_table=0x1000, seq_lens=0x1000,
+                page_min=0x1000, page_max=0x1000)
+    base.update(kw)
+    return ts.TsLayout(**base)
+
+
+def test_workspace_bytes_is_host_only_and_monotone():
+    lay = _layout()
+    n1 = ts.workspace_bytes(lay, 8)
+    n2 = ts.workspace_bytes(lay, 64)
+    assert 0 < n1 <= n2
+    assert ts.workspace_bytes(lay, 0) == 0
+    assert ts.workspace_bytes(_layout(head_dim=96), 8) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(num_seqs=0), ts.TS_ERR_SHAPE),
+    (dict(num_q_heads=7), ts.TS_ERR_SHAPE),
+    (dict(max_pages_per_seq=-1), ts.TS_ERR_SHAPE),
+    (dict(head_dim=96), ts.TS_ERR_UNSUPPORTED),
+    (dict(page_size=8), ts.TS_ERR_UNSUPPORTED),
+    (dict(num_q_heads=64, num_kv_heads=2), ts.TS_ERR_UNSUPPORTED),
+    (dict(max_pages_per_seq=1 << 20), ts.TS_ERR_UNSUPPORTED),
+    (dict(page_min=None), ts.TS_ERR_NULL),
+    (dict(seq_lens=None), ts.TS_ERR_NULL),
+])
+def test_layout_validation(kw, code):
+    lib = ts.lib()
+    lay = _layout(**kw)
+    q = ctypes.c_void_p(0x1000)
+    assert lib.ts_score_pages(ctypes.byref(lay), q, q, None) == code
+    assert lib.ts_build_page_meta(ctypes.byref(lay), None) == code
+    assert lib.ts_query_aware_decode(ctypes.byref(lay), q, 4, None, 4, 1.0, q, None, None, None, q,
+                                     1 << 30, None) == code
+
+
+def test_argument_validation():
+    lib = ts.lib()
+    lay = _layout()
+    p = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+    assert lib.ts_score_pages(None, p, p, None) == ts.TS_ERR_NULL
+    assert lib.ts_score_pages(ctypes.byref(lay), None, p, None) == ts.TS_ERR_NULL
+    assert lib.ts_append_token_meta(ctypes.byref(lay), None, None, 1, None) == ts.TS_ERR_NULL
+    assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 0, None, 8, p, p, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 9, None, 8, p, p, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 4, None, 8, None, p, None) == ts.TS_ERR_NULL
+    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, p, p, 16,
+                                          None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, None, p, big,
+                                          None) == ts.TS_ERR_NULL
+    assert lib.ts_query_aware_decode(ctypes.byref(lay), p, 4, None, 8, 1.0, p, None, None, None, p,
+                                     16, None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_query_aware_decode(ctypes.byref(lay), p, 0, None, 8, 1.0, p, None, None, None, p,
+                                     big, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_query_aware_decode(ctypes.byref(lay), p, 9, None, 8, 1.0, p, None, None, None, p,
+                                     big, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_workspace_init(None, 1024, None) == ts.TS_ERR_NULL
+    assert lib.ts_workspace_init(p, 8, None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_workspace_status(None, None) == ts.TS_ERR_NULL
+    assert lib.ts_set_tuning(-1, 0, 0) == ts.TS_ERR_SHAPE
+
+
+def test_tuning_changes_workspace_plan():
+    lay = _layout(num_seqs=16, max_pages_per_seq=1024)
+    try:
+        ts.set_tuning(0, 1, 0)
+        small = ts.workspace_bytes(lay, 128)
+        ts.set_tuning(0, 32, 0)
+        large = ts.workspace_bytes(lay, 128)
+        assert large > small
+    finally:
+        ts.set_tuning(0, 0, 0)
+
+
+def test_binding_raises_without_library(monkeypatch):
+    """No silent fallback: a missing library is an error."""
+    monkeypatch.setattr(ts, "_lib", None)
+    monkeypatch.setattr(ts, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        ts.lib()
