@@ -45,7 +45,7 @@
 extern "C" {
 #endif
 
-#define TS_MAX_PAGES_PER_SEQ 32768
+#define TS_MAX_PAGES_PER_SEQ 16384
 
 typedef enum ts_status {
   TS_OK = 0,

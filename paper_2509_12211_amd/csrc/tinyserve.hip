@@ -16,27 +16,29 @@ namespace ts {
 // ---------------------------------------------------------------------------
 // Work decomposition shared by host and device
 // ---------------------------------------------------------------------------
+// A unit is one (sequence, KV head).  A unit is worked on by a cluster of g
+// workgroups: each scores 1/g of the unit's pages and attends 1/g of its
+// selected pages.  g is chosen so that units * g is about two workgroups per
+// compute unit; with thousands of units g = 1 and nothing is exchanged
+// between workgroups at all.
 constexpr int kCtrlWords = 64;   // control words at the head of the workspace
-constexpr int kCtrlTicket = 0;   // next work item of the fused kernel
-constexpr int kCtrlExit = 1;     // workgroups that have left the fused kernel
 constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
-constexpr int kSpinLimit = 1 << 20;   // polls (>= ~1 us each) before a wait gives up
+constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
+constexpr int kTargetWorkgroups = 512;
+constexpr int kMaxCluster = 64;
 
 struct Plan {
-  int units;           // B * Hkv
-  int scan_pages;      // pages per scan work item
-  int scan_items;      // scan work items per unit
-  int n_split;         // attention work items per unit
-  int chunk;           // selected pages per attention work item
-  size_t off_unit;     // int32 [3][units]: scan_done, sel_ready, attend_done
-  size_t off_scores;   // fp32 [units][Pmax]
-  size_t off_sel;      // int32 [units][Kmax]
-  size_t off_part;     // fp32 [units][n_split][G][d+2]
+  int units;          // B * Hkv
+  int g;              // workgroups per unit (= attention splits = score slices)
+  int chunk;          // selected pages per workgroup
+  size_t off_unit;    // int32 [2][units]: scan_done, attend_done
+  size_t off_scores;  // fp32 [units][Pmax]
+  size_t off_part;    // fp32 [units][g][G][d+2]
   size_t total;
-  size_t lds_bytes;    // dynamic LDS of the select / attend / fused kernels
+  size_t lds_fused;   // dynamic LDS of the fused kernel
 };
 
-static int g_tune_scan_pages = 0, g_tune_splits = 0, g_tune_wg_per_cu = 0;
+static int g_tune_splits = 0, g_tune_wg_per_cu = 0, g_tune_reserved = 0;
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -45,36 +47,28 @@ static Plan make_plan(const ts_layout* L, int max_topk) {
   const int G = L->num_q_heads / L->num_kv_heads;
   const int Pmax = L->max_pages_per_seq;
   pl.units = L->num_seqs * L->num_kv_heads;
-  // scan items: 128 pages (32-64 KiB of metadata) each, coarser when there are
-  // already thousands of items
-  int sp = 128;
-  while ((long long)pl.units * ((Pmax + sp - 1) / sp) > 4096 && sp < 4096) sp *= 2;
-  if (g_tune_scan_pages > 0) sp = (g_tune_scan_pages + 31) / 32 * 32;
-  pl.scan_pages = sp;
-  pl.scan_items = (Pmax + sp - 1) / sp;
-  // attention items: aim at ~4 per compute unit (256 CUs), at least 4 pages each
-  int ns = (1024 + pl.units - 1) / pl.units;
-  const int cap = (max_topk + 3) / 4;
-  if (ns > cap) ns = cap;
-  if (ns > 64) ns = 64;
-  if (g_tune_splits > 0) ns = g_tune_splits;
-  if (ns > max_topk) ns = max_topk;
-  if (ns < 1) ns = 1;
-  pl.chunk = (max_topk + ns - 1) / ns;
-  pl.n_split = (max_topk + pl.chunk - 1) / pl.chunk;
+  int g = (kTargetWorkgroups + pl.units - 1) / pl.units;
+  const int cap = (max_topk + 3) / 4;  // at least one page per wave
+  if (g > cap) g = cap;
+  if (g > kMaxCluster) g = kMaxCluster;
+  if (g_tune_splits > 0) g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
+  if (g > max_topk) g = max_topk;
+  if (g < 1) g = 1;
+  pl.chunk = (max_topk + g - 1) / g;
+  pl.g = (max_topk + pl.chunk - 1) / pl.chunk;
   size_t off = kCtrlWords * sizeof(int32_t);
   pl.off_unit = off;
-  off = align_up(off + 3 * (size_t)pl.units * sizeof(int32_t), 256);
+  off = align_up(off + 2 * (size_t)pl.units * sizeof(int32_t), 256);
   pl.off_scores = off;
   off = align_up(off + (size_t)pl.units * Pmax * sizeof(float), 256);
-  pl.off_sel = off;
-  off = align_up(off + (size_t)pl.units * max_topk * sizeof(int32_t), 256);
   pl.off_part = off;
-  off = align_up(off + (size_t)pl.units * pl.n_split * G * (L->head_dim + 2) * sizeof(float), 256);
+  off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(float), 256);
   pl.total = off;
-  const size_t lds_sel = (size_t)Pmax * 4 + 256 * 4 + 16 * 4;
+  // fused kernel LDS: select scratch (keys, bins), the unit's block-table row,
+  // this workgroup's selected pages; the wave-merge area aliases the keys
+  const size_t lds_sel = select_lds_bytes(Pmax);
   const size_t lds_att = (size_t)kWaves * G * (L->head_dim + 2) * 4;
-  pl.lds_bytes = lds_sel > lds_att ? lds_sel : lds_att;
+  pl.lds_fused = (lds_sel > lds_att ? lds_sel : lds_att) + (size_t)Pmax * 4 + (size_t)pl.chunk * 4;
   return pl;
 }
 
@@ -82,44 +76,36 @@ struct FusedParams {
   AttendParams at;
   const uint16_t* page_min;
   const uint16_t* page_max;
-  float* scores;        // [units][Pmax]  (workspace or caller's)
-  int32_t* sel;         // [units][Kmax]
+  float* scores;        // [units][Pmax] exchange buffer (workspace)
+  float* scores_out;    // nullable, caller's
+  int32_t* sel_out;     // nullable [units][Kmax]
   int32_t* sel_count;   // nullable [B]
   const int32_t* topk_per_seq;
   int32_t* ctrl;        // control words
   int32_t* scan_done;   // [units]
-  int32_t* sel_ready;   // [units]
   int32_t* attend_done; // [units]
-  int topk, S, units, scan_pages, scan_items;
+  int topk, S, units, g;
 };
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
 
-__device__ __forceinline__ SelectScratch carve_select(unsigned char* smem, int Pmax) {
-  SelectScratch sc;
-  sc.keys = reinterpret_cast<uint32_t*>(smem);
-  sc.hist = sc.keys + Pmax;
-  sc.misc = reinterpret_cast<int*>(sc.hist + 256);
-  return sc;
-}
-
 // ---------------------------------------------------------------------------
 // Staged kernels
 // ---------------------------------------------------------------------------
+// grid (gx, units): workgroup x scores every gx-th group of pages of its unit.
 template <int D>
 __global__ __launch_bounds__(kThreads) void score_pages_kernel(const uint16_t* q,
                                                                const uint16_t* page_min,
                                                                const uint16_t* page_max,
                                                                const int32_t* seq_lens, float* scores,
-                                                               int Hq, int Hkv, int S, int Pmax,
-                                                               int scan_pages) {
+                                                               int Hq, int Hkv, int S, int Pmax) {
   const int u = blockIdx.y, b = u / Hkv, h = u % Hkv, G = Hq / Hkv;
-  const int Pb = min(pages_of(seq_lens[b], S), Pmax);
-  ScoreLanes<D> ql;
-  ql.load_query(q + ((size_t)b * Hq + (size_t)h * G) * D, G);
-  const int p0 = blockIdx.x * scan_pages, p1 = min(p0 + scan_pages, Pmax);
-  score_pages_slice<D>(ql, page_min + (size_t)u * Pmax * D, page_max + (size_t)u * Pmax * D, Pb, p0,
-                       p1, scores + (size_t)u * Pmax);
+  float* srow = scores + (size_t)u * Pmax;
+  score_pages_waves<D>(
+      page_min + (size_t)u * Pmax * D, page_max + (size_t)u * Pmax * D,
+      q + ((size_t)b * Hq + (size_t)h * G) * D, G, Pmax, blockIdx.x * kWaves + wave_id(),
+      gridDim.x * kWaves, [&] { return min(pages_of(seq_lens[b], S), Pmax); },
+      [&](int pg, float s) { srow[pg] = s; });
 }
 
 __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scores,
@@ -129,16 +115,21 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
                                                                int Hkv, int S, int Pmax, int Kmax) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int u = blockIdx.x, b = u / Hkv, h = u % Hkv;
-  const int Pb = min(pages_of(seq_lens[b], S), Pmax);
+  const int Pb = uniform(min(pages_of(seq_lens[b], S), Pmax));
   const int K = topk_per_seq ? topk_per_seq[b] : topk;
-  const int Kb = max(0, min(min(K, Pb), Kmax));
+  const int Kb = uniform(max(0, min(min(K, Pb), Kmax)));
   if (h == 0 && threadIdx.x == 0) sel_count[b] = Kb;
-  select_topk_unit(scores + (size_t)u * Pmax, Pb, Kb, Kmax, sel + (size_t)u * Kmax,
-                   carve_select(smem, Pmax));
+  const SelectLds L = carve_select(smem, Pmax);
+  const float* srow = scores + (size_t)u * Pmax;
+  int32_t* row = sel + (size_t)u * Kmax;
+  for (int i = Kb + threadIdx.x; i < Kmax; i += kThreads) row[i] = -1;
+  for (int j = threadIdx.x; j < Pb; j += kThreads) L.keys[j] = score_key(srow[j]);
+  __syncthreads();
+  select_topk_lds(L, Pb, Kb, [&](int rank, int page) { row[rank] = page; });
 }
 
-// grid (n_split, units).  The last workgroup of a unit to deposit its partial
-// merges them (unit_done counts arrivals and is left at zero again).
+// grid (g, units).  The last workgroup of a unit to deposit its partial merges
+// them (unit_done counts arrivals and is left at zero again).
 template <int D, int S>
 __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams p,
                                                                     const int32_t* sel,
@@ -146,128 +137,133 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
                                                                     int32_t* unit_done) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
-  const int u = blockIdx.y, b = u / p.Hkv, h = u % p.Hkv;
-  const int Kb = max(0, min(sel_count[b], p.Kmax));
-  attend_split<D, S>(p, b, h, blockIdx.x, sel + (size_t)u * p.Kmax, Kb,
-                     reinterpret_cast<float*>(smem));
+  const int u = blockIdx.y, b = u / p.Hkv, h = u % p.Hkv, split = blockIdx.x;
+  const int Kb = uniform(max(0, min(sel_count[b], p.Kmax)));
+  const int c0 = min(split * p.chunk, Kb), count = min(c0 + p.chunk, Kb) - c0;
+  const int32_t* sel_row = sel + (size_t)u * p.Kmax + c0;
+  const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
+  attend_split<D, S>(
+      p, b, h, split, count, p.seq_lens[b], [&](int i) { return sel_row[i]; },
+      [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
   if (p.n_split == 1) return;
-  fence_release_agent();
+  stores_complete();
   __syncthreads();
   if (threadIdx.x == 0) s_last = atomic_add_agent(&unit_done[u], 1) == p.n_split - 1;
   __syncthreads();
   if (!uniform(s_last)) return;
-  fence_acquire_agent();
   combine_splits<D>(p, b, h);
   if (threadIdx.x == 0) atomic_store_agent(&unit_done[u], 0);
 }
 
 // ---------------------------------------------------------------------------
-// Fused kernel: one launch, persistent workgroups pulling work items in ticket
-// order.  Items [0, units*scan_items) score a slice of one unit's pages; items
-// after that attend one split of one unit's selected pages.  The workgroup
-// that completes a unit's last slice runs the selection for that unit and
-// publishes it; attention items wait (bounded) for that publication.  Because
-// tickets are handed out in increasing order, every item an attention item can
-// wait for is already held by a running workgroup that itself never waits, so
-// the waits end whatever the number of resident workgroups.
+// Fused kernel (Algorithm 1 in one launch).
+//
+// Workgroup w belongs to cluster w / g as member w % g; a cluster takes units
+// cluster, cluster + n_clusters, ...  For each unit a member
+//   1. scores every g-th group of the unit's pages (metadata loads are issued
+//      before anything else; the unit's block-table row is copied to LDS
+//      meanwhile),
+//   2. g > 1: publishes its scores with agent-scope stores, bumps the unit's
+//      scan counter, waits (bounded) until all g members have, and reads the
+//      whole score row back;  g == 1: the scores never leave LDS,
+//   3. runs the top-K selection itself (every member computes the same list),
+//   4. attends its own 1/g of the selected pages,
+//   5. g > 1: publishes its partial softmax state, bumps the unit's attention
+//      counter; the member that arrives last merges the g partials.
+// Members only ever wait for members of their own cluster, all of which are
+// resident: the host launches at most as many workgroups as fit on the device
+// at once.  Every wait is bounded and raises the workspace's error word.
+//
+// Every thread-0-only block sits between two barriers and every value that
+// steers a branch around a barrier is pinned uniform.
 // ---------------------------------------------------------------------------
 template <int D, int S>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_ticket, s_flag;
+  __shared__ int s_flag;
   const AttendParams& at = p.at;
-  const int scan_total = p.units * p.scan_items;
-  const int total = scan_total + p.units * at.n_split;
-  const int G = at.G;
+  const int g = p.g, G = at.G, Pmax = at.Pmax;
+  const int member = blockIdx.x % g;
+  const int n_clusters = gridDim.x / g;
+  const SelectLds sl = carve_select(smem, Pmax);
+  const size_t sel_bytes = select_lds_bytes(Pmax);
+  const size_t att_bytes = (size_t)kWaves * G * (D + 2) * 4;
+  int32_t* bt_lds = reinterpret_cast<int32_t*>(smem + (sel_bytes > att_bytes ? sel_bytes : att_bytes));
+  int32_t* my_sel = bt_lds + Pmax;  // [chunk]
+  const bool exchange = g > 1;
 
-  // Every thread-0-only block below sits between two barriers, and every value
-  // that steers a branch is pinned uniform: the compiler must never be able to
-  // merge two thread-0 regions across the loop back-edge, which would let the
-  // other lanes run ahead to the next barrier.
-  if (threadIdx.x == 0) s_ticket = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
-  __syncthreads();
-  int t = uniform(s_ticket);
-  while (t < total) {
-    int done_unit = -1;  // unit whose last attention item this workgroup finished
-    if (t < scan_total) {
-      const int u = t / p.scan_items, it = t % p.scan_items;
-      const int b = u / at.Hkv, h = u % at.Hkv;
-      const int Pb = uniform(min(pages_of(at.seq_lens[b], p.S), at.Pmax));
-      ScoreLanes<D> ql;
-      ql.load_query(at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
-      const int p0 = it * p.scan_pages, p1 = min(p0 + p.scan_pages, at.Pmax);
-      float* srow = p.scores + (size_t)u * at.Pmax;
-      score_pages_slice<D>(ql, p.page_min + (size_t)u * at.Pmax * D,
-                           p.page_max + (size_t)u * at.Pmax * D, Pb, p0, p1, srow);
-      fence_release_agent();
+  for (int u = blockIdx.x / g; u < p.units; u += n_clusters) {
+    const int b = u / at.Hkv, h = u % at.Hkv;
+    const uint16_t* q_group = at.q + ((size_t)b * at.Hq + (size_t)h * G) * D;
+    const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
+    float* srow = p.scores + (size_t)u * Pmax;
+    float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
+
+    // 1. score my share of the pages
+    score_pages_waves<D>(
+        p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, q_group, G, Pmax,
+        member * kWaves + wave_id(), g * kWaves,
+        [&] {
+          // while the metadata is in flight: the block-table row goes to LDS
+          for (int j = threadIdx.x; j < Pmax; j += kThreads) bt_lds[j] = bt_row[j];
+          return min(pages_of(at.seq_lens[b], p.S), Pmax);
+        },
+        [&](int pg, float s) {
+          if (exchange) store_agent(srow + pg, s);
+          else sl.keys[pg] = score_key(s);
+          if (srow_out) srow_out[pg] = s;
+        });
+    const int L = uniform(at.seq_lens[b]);
+    const int Pb = uniform(min(pages_of(L, p.S), Pmax));
+    const int K = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
+    const int Kb = uniform(max(0, min(min(K, Pb), at.Kmax)));
+
+    // 2. exchange the scores inside the cluster
+    if (exchange) {
+      stores_complete();
       __syncthreads();
-      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.scan_done[u], 1) == p.scan_items - 1;
-      __syncthreads();
-      if (uniform(s_flag)) {  // this workgroup completed the unit's scores: select
-        fence_acquire_agent();
-        const int K = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
-        const int Kb = uniform(max(0, min(min(K, Pb), at.Kmax)));
-        select_topk_unit(srow, Pb, Kb, at.Kmax, p.sel + (size_t)u * at.Kmax,
-                         carve_select(smem, at.Pmax));
-        fence_release_agent();
-        __syncthreads();
-        if (threadIdx.x == 0) {
-          if (p.sel_count && h == 0) p.sel_count[b] = Kb;
-          atomic_store_agent(&p.sel_ready[u], 1);
-        }
-      }
-    } else {
-      const int a = t - scan_total;
-      const int u = a / at.n_split, split = a % at.n_split;
-      const int b = u / at.Hkv, h = u % at.Hkv;
       if (threadIdx.x == 0) {
-        int ok = 0;
-        for (int spin = 0; spin < kSpinLimit; ++spin) {
-          if (atomic_load_agent(&p.sel_ready[u]) != 0) { ok = 1; break; }
-          __builtin_amdgcn_s_sleep(2);
-        }
+        atomic_add_agent(&p.scan_done[u], 1);
+        const int ok = wait_at_least(&p.scan_done[u], g, kSpinLimit);
         if (!ok) atomic_store_agent(&p.ctrl[kCtrlError], 1);
         s_flag = ok;
       }
       __syncthreads();
-      const int ok = uniform(s_flag);
-      fence_acquire_agent();
-      const int Pb = uniform(min(pages_of(at.seq_lens[b], p.S), at.Pmax));
-      const int K = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
-      const int Kb = uniform(ok ? max(0, min(min(K, Pb), at.Kmax)) : 0);
-      attend_split<D, S>(at, b, h, split, p.sel + (size_t)u * at.Kmax, Kb,
-                         reinterpret_cast<float*>(smem));  // ends with a barrier
-      int last = 1;
-      if (at.n_split > 1) {
-        fence_release_agent();
-        __syncthreads();
-        if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u], 1) == at.n_split - 1;
-        __syncthreads();
-        last = uniform(s_flag);
-        if (last) {
-          fence_acquire_agent();
-          combine_splits<D>(at, b, h);
-        }
-      }
-      if (last) done_unit = u;
-    }
-    __syncthreads();  // the item is finished; s_ticket / s_flag are free again
-    if (threadIdx.x == 0) {
-      if (done_unit >= 0) {  // every item of this unit has passed its waits: re-arm it
-        atomic_store_agent(&p.scan_done[done_unit], 0);
-        atomic_store_agent(&p.sel_ready[done_unit], 0);
-        atomic_store_agent(&p.attend_done[done_unit], 0);
-      }
-      s_ticket = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
+      for (int j = threadIdx.x; j < Pb; j += kThreads) sl.keys[j] = score_key(load_agent(srow + j));
     }
     __syncthreads();
-    t = uniform(s_ticket);
-  }
-  // the last workgroup to leave re-arms the ticket counter for the next launch
-  if (threadIdx.x == 0) {
-    if (atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
-      atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
-      atomic_store_agent(&p.ctrl[kCtrlExit], 0);
+
+    // 3. select; keep my own chunk of the ascending list
+    const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
+    int32_t* sel_row = (p.sel_out && member == 0) ? p.sel_out + (size_t)u * at.Kmax : nullptr;
+    if (sel_row)
+      for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
+    if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
+    select_topk_lds(sl, Pb, Kb, [&](int rank, int page) {
+      if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
+      if (sel_row) sel_row[rank] = page;
+    });
+    __syncthreads();
+
+    // 4. attend my chunk (the wave-merge area reuses the select scratch)
+    attend_split<D, S>(
+        at, b, h, member, count, L, [&](int i) { return my_sel[i]; },
+        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
+
+    // 5. merge the cluster's partials
+    if (exchange) {
+      stores_complete();
+      __syncthreads();
+      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u], 1) == g - 1;
+      __syncthreads();
+      const int last = uniform(s_flag);
+      if (last) combine_splits<D>(at, b, h);
+      __syncthreads();
+      if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
+        atomic_store_agent(&p.scan_done[u], 0);
+        atomic_store_agent(&p.attend_done[u], 0);
+      }
+      __syncthreads();
     }
   }
 }
@@ -317,6 +313,15 @@ static int allow_lds(KernelT kernel, size_t bytes) {
              : TS_ERR_LAUNCH;
 }
 
+// Workgroups of `kernel` that can be resident on the whole device at once.
+template <typename KernelT>
+static int resident_capacity(KernelT kernel, size_t lds) {
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, lds) != hipSuccess)
+    return 0;
+  return per_cu * num_compute_units();
+}
+
 static MetaParams meta_params(const ts_layout* L) {
   MetaParams p;
   p.k_pool = static_cast<const uint16_t*>(L->k_pool);
@@ -350,7 +355,7 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.Pmax = L->max_pages_per_seq;
   a.Kmax = max_topk;
   a.n_phys = L->num_phys_pages;
-  a.n_split = pl.n_split;
+  a.n_split = pl.g;
   a.chunk = pl.chunk;
   a.scale_log2 = softmax_scale * 1.4426950408889634f;
   return a;
@@ -362,7 +367,7 @@ using namespace ts;
 
 extern "C" {
 
-int ts_version(void) { return 1; }
+int ts_version(void) { return 2; }
 
 const char* ts_strerror(int status) {
   switch (status) {
@@ -377,9 +382,9 @@ const char* ts_strerror(int status) {
   }
 }
 
-int ts_set_tuning(int32_t scan_pages_per_task, int32_t num_splits, int32_t workgroups_per_cu) {
-  if (scan_pages_per_task < 0 || num_splits < 0 || workgroups_per_cu < 0) return TS_ERR_SHAPE;
-  g_tune_scan_pages = scan_pages_per_task;
+int ts_set_tuning(int32_t reserved, int32_t num_splits, int32_t workgroups_per_cu) {
+  if (reserved < 0 || num_splits < 0 || workgroups_per_cu < 0) return TS_ERR_SHAPE;
+  g_tune_reserved = reserved;
   g_tune_splits = num_splits;
   g_tune_wg_per_cu = workgroups_per_cu;
   return TS_OK;
@@ -394,9 +399,9 @@ int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return TS_ERR_NULL;
   if (workspace_bytes < kCtrlWords * sizeof(int32_t)) return TS_ERR_WORKSPACE;
   // control words + per-unit counters live at the head; zeroing the first
-  // min(bytes, 1 MiB) covers them for every supported unit count (<= 65535)
+  // ~0.5 MiB covers them for every supported unit count (<= 65535)
   size_t n = workspace_bytes / sizeof(int32_t);
-  const size_t cap = (kCtrlWords + 3 * 65536) ;
+  const size_t cap = kCtrlWords + 2 * 65536;
   if (n > cap) n = cap;
   fill_zero_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
       static_cast<int32_t*>(workspace), n);
@@ -445,18 +450,24 @@ int ts_score_pages(const ts_layout* layout, const void* q, float* scores, void* 
   if (st != TS_OK) return st;
   if (!q || !scores || !layout->seq_lens || !layout->page_min || !layout->page_max)
     return TS_ERR_NULL;
-  Plan pl = make_plan(layout, 1);
-  dim3 grid(pl.scan_items, pl.units);
+  const int units = layout->num_seqs * layout->num_kv_heads;
+  const int Pmax = layout->max_pages_per_seq;
+  const int ppi_wg = (layout->head_dim == 64 ? 32 : 16) * kWaves;  // pages per workgroup pass
+  int gx = (2 * kTargetWorkgroups + units - 1) / units;
+  const int most = (Pmax + ppi_wg - 1) / ppi_wg;
+  if (gx > most) gx = most;
+  if (gx < 1) gx = 1;
+  dim3 grid(gx, units);
   const uint16_t* pmin = static_cast<const uint16_t*>(layout->page_min);
   const uint16_t* pmax = static_cast<const uint16_t*>(layout->page_max);
   if (layout->head_dim == 64)
     score_pages_kernel<64><<<grid, kThreads, 0, (hipStream_t)stream>>>(
         static_cast<const uint16_t*>(q), pmin, pmax, layout->seq_lens, scores, layout->num_q_heads,
-        layout->num_kv_heads, layout->page_size, layout->max_pages_per_seq, pl.scan_pages);
+        layout->num_kv_heads, layout->page_size, Pmax);
   else
     score_pages_kernel<128><<<grid, kThreads, 0, (hipStream_t)stream>>>(
         static_cast<const uint16_t*>(q), pmin, pmax, layout->seq_lens, scores, layout->num_q_heads,
-        layout->num_kv_heads, layout->page_size, layout->max_pages_per_seq, pl.scan_pages);
+        layout->num_kv_heads, layout->page_size, Pmax);
   return launch_status();
 }
 
@@ -467,10 +478,10 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
   if (st != TS_OK) return st;
   if (!scores || !sel || !sel_count || !layout->seq_lens) return TS_ERR_NULL;
   if (max_topk < 1 || (!topk_per_seq && (topk < 1 || max_topk < topk))) return TS_ERR_SHAPE;
-  Plan pl = make_plan(layout, max_topk);
-  const size_t lds = (size_t)layout->max_pages_per_seq * 4 + 256 * 4 + 16 * 4;
+  const int units = layout->num_seqs * layout->num_kv_heads;
+  const size_t lds = select_lds_bytes(layout->max_pages_per_seq);
   if ((st = allow_lds(select_topk_kernel, lds)) != TS_OK) return st;
-  select_topk_kernel<<<pl.units, kThreads, lds, (hipStream_t)stream>>>(
+  select_topk_kernel<<<units, kThreads, lds, (hipStream_t)stream>>>(
       scores, layout->seq_lens, topk, topk_per_seq, sel, sel_count, layout->num_kv_heads,
       layout->page_size, layout->max_pages_per_seq, max_topk);
   return launch_status();
@@ -490,9 +501,9 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
-  int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + 2 * (size_t)pl.units;
+  int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units;
   const size_t lds = (size_t)kWaves * a.G * (layout->head_dim + 2) * 4;
-  dim3 grid(pl.n_split, pl.units);
+  dim3 grid(pl.g, pl.units);
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
   if (D == 64 && S == 16)
@@ -526,30 +537,32 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
   p.at = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
   p.page_min = static_cast<const uint16_t*>(layout->page_min);
   p.page_max = static_cast<const uint16_t*>(layout->page_max);
-  p.scores = scores_out ? scores_out : reinterpret_cast<float*>(ws + pl.off_scores);
-  p.sel = sel_out ? sel_out : reinterpret_cast<int32_t*>(ws + pl.off_sel);
+  p.scores = reinterpret_cast<float*>(ws + pl.off_scores);
+  p.scores_out = scores_out;
+  p.sel_out = sel_out;
   p.sel_count = sel_count_out;
   p.topk_per_seq = topk_per_seq;
   p.ctrl = reinterpret_cast<int32_t*>(ws);
   p.scan_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
-  p.sel_ready = p.scan_done + pl.units;
-  p.attend_done = p.sel_ready + pl.units;
+  p.attend_done = p.scan_done + pl.units;
   p.topk = topk;
   p.S = layout->page_size;
   p.units = pl.units;
-  p.scan_pages = pl.scan_pages;
-  p.scan_items = pl.scan_items;
-  const long long items = (long long)pl.units * (pl.scan_items + pl.n_split);
-  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 4;
-  long long grid = (long long)cus * per_cu;
-  if (grid > items) grid = items;
+  p.g = pl.g;
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
-#define TS_LAUNCH_FUSED(DD, SS)                                                        \
-  do {                                                                                 \
-    if ((st = allow_lds(query_aware_decode_kernel<DD, SS>, pl.lds_bytes)) != TS_OK)    \
-      return st;                                                                       \
-    query_aware_decode_kernel<DD, SS><<<(unsigned)grid, kThreads, pl.lds_bytes, s>>>(p); \
+  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 2;
+#define TS_LAUNCH_FUSED(DD, SS)                                                          \
+  do {                                                                                   \
+    if ((st = allow_lds(query_aware_decode_kernel<DD, SS>, pl.lds_fused)) != TS_OK)      \
+      return st;                                                                         \
+    int cap = resident_capacity(query_aware_decode_kernel<DD, SS>, pl.lds_fused);        \
+    if (cap > cus * per_cu) cap = cus * per_cu;                                          \
+    int clusters = cap / pl.g;                                                           \
+    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */          \
+    if (clusters > pl.units) clusters = pl.units;                                        \
+    query_aware_decode_kernel<DD, SS>                                                    \
+        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                 \
   } while (0)
   if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16);
   else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32);

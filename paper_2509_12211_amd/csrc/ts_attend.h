@@ -184,36 +184,38 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
   }
 }
 
-// The workgroup attends the selected pages sel_row[c_begin .. c_end) of unit
-// (b, h); wave w takes entries c_begin + w, + kWaves, ...  The four wave states
-// are merged through LDS (lds: kWaves * G * (D + 2) floats).  With n_split == 1
-// the normalised result goes to `out`; otherwise the unnormalised partial
-// (o[D], m, l per head) goes to p.partials for combine_splits().
-template <int D, int S>
+// The workgroup attends `count` selected pages of unit (b, h): entry i of its
+// list is page sel_at(i), stored in physical page phys_at(page).  Wave w takes
+// entries w, w + kWaves, ...  The four wave states are merged through LDS
+// (lds: kWaves * G * (D + 2) floats).  With n_split == 1 the normalised result
+// goes to `out`; otherwise the unnormalised partial (o[D], m, l per head) is
+// handed to the combining workgroup through agent-scope stores.
+// Ends with a barrier after which `lds` may be reused; on return (n_split > 1)
+// the caller still has to wait for its stores and count its arrival.
+template <int D, int S, typename SelAt, typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
-                                             const int32_t* sel_row, int Kb, float* lds) {
+                                             int count, int L, SelAt sel_at, PhysAt phys_at,
+                                             float* lds) {
   const int lane = lane_id(), wave = wave_id();
   const int head = lane & 15, kb = lane >> 4;
   const int G = p.G;
-  const int L = uniform(p.seq_lens[b]);
-  Kb = uniform(Kb);
-  const int c_begin = min(split * p.chunk, Kb), c_end = min(c_begin + p.chunk, Kb);
-  const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
+  L = uniform(L);
+  count = uniform(count);
 
   short4_t qf[D / 16];
   load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
   WaveAcc<D> acc;
   acc.init();
 
-  for (int batch = c_begin + wave; batch < c_end; batch += kWave * kWaves) {
+  for (int batch = wave; batch < count; batch += kWave * kWaves) {
     // lane x holds the ids of this wave's x-th page of the batch
     const int my_i = batch + lane * kWaves;
     int my_j = -1, my_phys = -1;
-    if (my_i < c_end) {
-      my_j = sel_row[my_i];
-      if (my_j >= 0 && my_j < p.Pmax) my_phys = bt_row[my_j];
+    if (my_i < count) {
+      my_j = sel_at(my_i);
+      if (my_j >= 0 && my_j < p.Pmax) my_phys = phys_at(my_j);
     }
-    const int n = min(kWave, (c_end - batch + kWaves - 1) / kWaves);
+    const int n = min(kWave, (count - batch + kWaves - 1) / kWaves);
     PageFrag<D, S> fa, fb;
     auto issue = [&](PageFrag<D, S>& f, int x) -> int {
       const int j = __builtin_amdgcn_readlane(my_j, x);
@@ -252,8 +254,8 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   }
   __syncthreads();
   float* part = p.partials + (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
-  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-    const int g = idx / D, c = idx % D;
+  for (int idx = threadIdx.x; idx < G * RS; idx += kThreads) {
+    const int g = idx / RS, c = idx % RS;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) M = fmaxf(M, lds[((size_t)w * G + g) * RS + D]);
@@ -263,20 +265,20 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
       const float* row = lds + ((size_t)w * G + g) * RS;
       const float wgt = __builtin_amdgcn_exp2f(row[D] - M);
       Lsum += row[D + 1] * wgt;
-      O += row[c] * wgt;
+      O += row[c < D ? c : 0] * wgt;
     }
     if (p.n_split == 1) {
-      p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+      if (c < D) p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
     } else {
-      part[(size_t)g * RS + c] = O;
-      if (c == 0) { part[(size_t)g * RS + D] = M; part[(size_t)g * RS + D + 1] = Lsum; }
+      store_agent(part + idx, c < D ? O : (c == D ? M : Lsum));
     }
   }
-  __syncthreads();  // lds is reused by the caller's next work item
+  __syncthreads();
 }
 
 // Merge the n_split partials of unit (b, h) and write the normalised output.
-// The caller has established that all partials are visible.
+// The caller has observed every producer's arrival; the partials are read with
+// agent-scope loads.
 template <int D>
 __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int h) {
   constexpr int RS = D + 2;
@@ -285,13 +287,13 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
   for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
     const int g = idx / D, c = idx % D;
     float M = -INFINITY;
-    for (int s = 0; s < p.n_split; ++s) M = fmaxf(M, part[((size_t)s * G + g) * RS + D]);
+    for (int s = 0; s < p.n_split; ++s) M = fmaxf(M, load_agent(part + ((size_t)s * G + g) * RS + D));
     float Lsum = 0.f, O = 0.f;
     for (int s = 0; s < p.n_split; ++s) {
       const float* row = part + ((size_t)s * G + g) * RS;
-      const float wgt = __builtin_amdgcn_exp2f(row[D] - M);
-      Lsum += row[D + 1] * wgt;
-      O += row[c] * wgt;
+      const float wgt = __builtin_amdgcn_exp2f(load_agent(row + D) - M);
+      Lsum += load_agent(row + D + 1) * wgt;
+      O += load_agent(row + c) * wgt;
     }
     p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
   }

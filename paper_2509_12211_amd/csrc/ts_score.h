@@ -23,6 +23,8 @@ template <int D>
 struct ScoreLanes {
   static constexpr int LPR = D / 8;         // lanes per metadata row
   static constexpr int PPW = kWave / LPR;   // pages per wave-wide load
+  static constexpr int U = 4;               // wave-wide loads of min (and of max) in flight
+  static constexpr int PPI = PPW * U;       // pages one wave covers per iteration
   double qp[8], qn[8];
 
   __device__ __forceinline__ void load_query(const uint16_t* q_group, int G) {
@@ -53,24 +55,22 @@ struct ScoreLanes {
   }
 };
 
-// Scores pages [p_begin, p_end) of one (sequence, KV head) with the whole
-// workgroup; writes -inf for pages >= Pb.  pmin_u / pmax_u point at the unit's
-// first metadata row, srow at its score row.  U loads of min and of max are
-// issued before the first use to keep several KiB in flight per wave.
+// The metadata rows one wave has in flight: U wave-wide loads of min and of max
+// covering pages [base, base + PPI).  Rows up to Pmax are always readable
+// (whatever they hold), so the loads do not wait for the sequence length.
 template <int D>
-__device__ __forceinline__ void score_pages_slice(const ScoreLanes<D>& ql, const uint16_t* pmin_u,
-                                                  const uint16_t* pmax_u, int Pb, int p_begin,
-                                                  int p_end, float* srow) {
-  constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
-  constexpr int U = 4;
-  const int lane = lane_id();
-  const int cg = lane % LPR, prow = lane / LPR;
-  for (int base = p_begin + wave_id() * PPW * U; base < p_end; base += kWaves * PPW * U) {
-    uint4 mn[U], mx[U];
+struct MetaTile {
+  static constexpr int U = ScoreLanes<D>::U;
+  uint4 mn[U], mx[U];
+
+  __device__ __forceinline__ void load(const uint16_t* pmin_u, const uint16_t* pmax_u, int base,
+                                       int Pmax) {
+    constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
+    const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pg = base + u * PPW + prow;
-      if (pg < Pb && pg < p_end) {
+      if (pg < Pmax) {
         mn[u] = *reinterpret_cast<const uint4*>(pmin_u + (size_t)pg * D + cg * 8);
         mx[u] = *reinterpret_cast<const uint4*>(pmax_u + (size_t)pg * D + cg * 8);
       } else {
@@ -78,14 +78,49 @@ __device__ __forceinline__ void score_pages_slice(const ScoreLanes<D>& ql, const
         mx[u] = make_uint4(0, 0, 0, 0);
       }
     }
+  }
+
+  // sink(page, score) is called once per page < Pmax by one lane; pages >= Pb
+  // get -inf.
+  template <typename Sink>
+  __device__ __forceinline__ void reduce(const ScoreLanes<D>& ql, int base, int Pb, int Pmax,
+                                         Sink sink) const {
+    constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
+    const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pg = base + u * PPW + prow;
       double s = ql.row_partial(mn[u], mx[u]);
 #pragma unroll
       for (int m = 1; m < LPR; m <<= 1) s += __shfl_xor(s, m, kWave);
-      if (cg == 0 && pg < p_end) srow[pg] = pg < Pb ? static_cast<float>(s) : -INFINITY;
+      if (cg == 0 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
     }
+  }
+};
+
+// Scores the pages of one (sequence, KV head) that fall to this wave: wave
+// iterations it = first_iter, first_iter + iter_stride, ... each cover
+// ScoreLanes<D>::PPI consecutive pages.  The first metadata loads are issued
+// before the query is read.  Pb is passed as a callable so its (scalar) load
+// need not be waited for before the metadata loads go out.
+template <int D, typename PbFn, typename Sink>
+__device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const uint16_t* pmax_u,
+                                                  const uint16_t* q_group, int G, int Pmax,
+                                                  int first_iter, int iter_stride, PbFn pb_fn,
+                                                  Sink sink) {
+  constexpr int PPI = ScoreLanes<D>::PPI;
+  MetaTile<D> tile;
+  int base = first_iter * PPI;
+  if (base < Pmax) tile.load(pmin_u, pmax_u, base, Pmax);
+  ScoreLanes<D> ql;
+  ql.load_query(q_group, G);
+  const int Pb = pb_fn();
+  while (base < Pmax) {
+    const int next = base + iter_stride * PPI;
+    MetaTile<D> cur = tile;
+    if (next < Pmax) tile.load(pmin_u, pmax_u, next, Pmax);
+    cur.reduce(ql, base, Pb, Pmax, sink);
+    base = next;
   }
 }
 
