@@ -99,12 +99,13 @@ __global__ __launch_bounds__(kThreads) void score_pages_kernel(const uint16_t* q
                                                                const uint16_t* page_max,
                                                                const int32_t* seq_lens, float* scores,
                                                                int Hq, int Hkv, int S, int Pmax) {
+  __shared__ __align__(16) unsigned char q_stage[ScoreLanes<D>::query_stage_bytes(16)];
   const int u = blockIdx.y, b = u / Hkv, h = u % Hkv, G = Hq / Hkv;
   float* srow = scores + (size_t)u * Pmax;
   score_pages_waves<D>(
       page_min + (size_t)u * Pmax * D, page_max + (size_t)u * Pmax * D,
       q + ((size_t)b * Hq + (size_t)h * G) * D, G, Pmax, blockIdx.x * kWaves + wave_id(),
-      gridDim.x * kWaves, [&] { return min(pages_of(seq_lens[b], S), Pmax); },
+      gridDim.x * kWaves, q_stage, [] {}, [&] { return min(pages_of(seq_lens[b], S), Pmax); },
       [&](int pg, float s) { srow[pg] = s; });
 }
 
@@ -193,19 +194,36 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   const bool exchange = g > 1;
 
   for (int u = blockIdx.x / g; u < p.units; u += n_clusters) {
+    TS_MARK(0);
     const int b = u / at.Hkv, h = u % at.Hkv;
     const uint16_t* q_group = at.q + ((size_t)b * at.Hq + (size_t)h * G) * D;
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
     float* srow = p.scores + (size_t)u * Pmax;
     float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
 
-    // 1. score my share of the pages
+    // 1. score my share of the pages; the unit's block-table row is fetched
+    // alongside (first kBtRegs * 256 entries through registers, all in flight
+    // with the query and metadata loads) and parked in LDS
+    constexpr int kBtRegs = 8;
+    int bt_regs[kBtRegs];
     score_pages_waves<D>(
         p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, q_group, G, Pmax,
-        member * kWaves + wave_id(), g * kWaves,
+        member * kWaves + wave_id(), g * kWaves, reinterpret_cast<unsigned char*>(sl.hist),
         [&] {
-          // while the metadata is in flight: the block-table row goes to LDS
-          for (int j = threadIdx.x; j < Pmax; j += kThreads) bt_lds[j] = bt_row[j];
+#pragma unroll
+          for (int k = 0; k < kBtRegs; ++k) {
+            const int j = threadIdx.x + k * kThreads;
+            bt_regs[k] = j < Pmax ? bt_row[j] : -1;
+          }
+        },
+        [&] {
+#pragma unroll
+          for (int k = 0; k < kBtRegs; ++k) {
+            const int j = threadIdx.x + k * kThreads;
+            if (j < Pmax) bt_lds[j] = bt_regs[k];
+          }
+          for (int j = threadIdx.x + kBtRegs * kThreads; j < Pmax; j += kThreads)
+            bt_lds[j] = bt_row[j];
           return min(pages_of(at.seq_lens[b], p.S), Pmax);
         },
         [&](int pg, float s) {
@@ -219,9 +237,11 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     const int Kb = uniform(max(0, min(min(K, Pb), at.Kmax)));
 
     // 2. exchange the scores inside the cluster
+    TS_MARK(1);
     if (exchange) {
       stores_complete();
       __syncthreads();
+      TS_MARK(2);
       if (threadIdx.x == 0) {
         atomic_add_agent(&p.scan_done[u], 1);
         const int ok = wait_at_least(&p.scan_done[u], g, kSpinLimit);
@@ -229,9 +249,25 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
         s_flag = ok;
       }
       __syncthreads();
-      for (int j = threadIdx.x; j < Pb; j += kThreads) sl.keys[j] = score_key(load_agent(srow + j));
+      TS_MARK(3);
+      // all loads of a round in flight together (a plain loop would pay one
+      // memory round trip per iteration)
+      for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int j = j0 + i * kThreads;
+          v[i] = j < Pb ? load_agent(srow + j) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int j = j0 + i * kThreads;
+          if (j < Pb) sl.keys[j] = score_key(v[i]);
+        }
+      }
     }
     __syncthreads();
+    TS_MARK(4);
 
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
@@ -244,21 +280,26 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       if (sel_row) sel_row[rank] = page;
     });
     __syncthreads();
+    TS_MARK(5);
 
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     attend_split<D, S>(
         at, b, h, member, count, L, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
+    TS_MARK(6);
 
     // 5. merge the cluster's partials
     if (exchange) {
       stores_complete();
       __syncthreads();
+      TS_MARK(7);
       if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u], 1) == g - 1;
       __syncthreads();
       const int last = uniform(s_flag);
+      TS_MARK(8);
       if (last) combine_splits<D>(at, b, h);
       __syncthreads();
+      TS_MARK(9);
       if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
         atomic_store_agent(&p.scan_done[u], 0);
         atomic_store_agent(&p.attend_done[u], 0);
@@ -368,6 +409,13 @@ using namespace ts;
 extern "C" {
 
 int ts_version(void) { return 2; }
+
+#ifdef TS_PROFILE
+int ts_debug_set_profile_buffer(void* buf) {
+  return hipMemcpyToSymbol(HIP_SYMBOL(g_profile_buf), &buf, sizeof(buf)) == hipSuccess ? TS_OK
+                                                                                        : TS_ERR_LAUNCH;
+}
+#endif
 
 const char* ts_strerror(int status) {
   switch (status) {

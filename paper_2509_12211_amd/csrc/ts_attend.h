@@ -143,8 +143,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
       mx = fmaxf(mx, x);
     }
   }
-  mx = fmaxf(mx, shfl_xor_f(mx, 16));
-  mx = fmaxf(mx, shfl_xor_f(mx, 32));
+  mx = rows_max_f32(mx);
   const float m_new = fmaxf(a.m, mx);
   const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
   a.m = m_new;
@@ -216,33 +215,39 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
       if (my_j >= 0 && my_j < p.Pmax) my_phys = phys_at(my_j);
     }
     const int n = min(kWave, (count - batch + kWaves - 1) / kWaves);
-    PageFrag<D, S> fa, fb;
-    auto issue = [&](PageFrag<D, S>& f, int x) -> int {
+    // A ring of NBUF page buffers: up to NBUF pages of this wave are in flight
+    // (4 KiB - 8 KiB each) before the first is consumed.
+    constexpr int NBUF = (D * S <= 1024) ? 4 : (D * S <= 2048 ? 3 : 2);
+    PageFrag<D, S> f[NBUF];
+    int valid[NBUF];
+    auto issue = [&](PageFrag<D, S>& fr, int x) -> int {
       const int j = __builtin_amdgcn_readlane(my_j, x);
       const int phys = __builtin_amdgcn_readlane(my_phys, x);
       if (phys < 0 || phys >= p.n_phys) {
-        zero_page(f);
+        zero_page(fr);
         return 0;
       }
       const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)(S * D);
-      load_page<D, S>(f, p.k_pool + tile, p.v_pool + tile);
+      load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile);
       return max(0, min(S, L - j * S));
     };
-    int va = issue(fa, 0), vb = 0;
-    for (int x = 0; x < n; x += 2) {
-      if (x + 1 < n) vb = issue(fb, x + 1);
-      attend_page<D, S>(fa, qf, va, p.scale_log2, acc);
-      if (x + 1 < n) {
-        if (x + 2 < n) va = issue(fa, x + 2);
-        attend_page<D, S>(fb, qf, vb, p.scale_log2, acc);
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i)
+      if (i < n) valid[i] = issue(f[i], i);
+    for (int x0 = 0; x0 < n; x0 += NBUF) {
+#pragma unroll
+      for (int i = 0; i < NBUF; ++i) {
+        const int x = x0 + i;
+        if (x < n) {
+          attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
+          if (x + NBUF < n) valid[i] = issue(f[i], x + NBUF);
+        }
       }
     }
   }
 
   // merge the wave states
-  float l = acc.l;
-  l += shfl_xor_f(l, 16);
-  l += shfl_xor_f(l, 32);
+  const float l = rows_sum_f32(acc.l);
   constexpr int RS = D + 2;
   if (head < G) {
     float* row = lds + ((size_t)wave * G + head) * RS;
@@ -286,14 +291,31 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
   const float* part = p.partials + ((size_t)b * p.Hkv + h) * p.n_split * (size_t)G * RS;
   for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
     const int g = idx / D, c = idx % D;
-    float M = -INFINITY;
-    for (int s = 0; s < p.n_split; ++s) M = fmaxf(M, load_agent(part + ((size_t)s * G + g) * RS + D));
-    float Lsum = 0.f, O = 0.f;
-    for (int s = 0; s < p.n_split; ++s) {
-      const float* row = part + ((size_t)s * G + g) * RS;
-      const float wgt = __builtin_amdgcn_exp2f(load_agent(row + D) - M);
-      Lsum += load_agent(row + D + 1) * wgt;
-      O += load_agent(row + c) * wgt;
+    // online merge, 8 partials per round with all their loads in flight together
+    float M = -1e30f, Lsum = 0.f, O = 0.f;
+    for (int s0 = 0; s0 < p.n_split; s0 += 8) {
+      float o[8], m[8], l[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bool on = s0 + i < p.n_split;
+        const float* row = part + ((size_t)(on ? s0 + i : 0) * G + g) * RS;
+        o[i] = on ? load_agent(row + c) : 0.f;
+        m[i] = on ? load_agent(row + D) : -1e30f;
+        l[i] = on ? load_agent(row + D + 1) : 0.f;
+      }
+      float Mn = M;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) Mn = fmaxf(Mn, m[i]);
+      const float sc = __builtin_amdgcn_exp2f(M - Mn);
+      Lsum *= sc;
+      O *= sc;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float wgt = __builtin_amdgcn_exp2f(m[i] - Mn);
+        Lsum += l[i] * wgt;
+        O += o[i] * wgt;
+      }
+      M = Mn;
     }
     p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
   }

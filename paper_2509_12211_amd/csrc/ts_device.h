@@ -45,6 +45,82 @@ __device__ __forceinline__ int popc_below(uint64_t mask) {
 
 __device__ __forceinline__ float shfl_xor_f(float v, int m) { return __shfl_xor(v, m, kWave); }
 
+// Wave64 scans / reductions on the DPP data path (a few cycles per step; the
+// ds_bpermute route of __shfl_* costs an LDS round trip per step).  Lanes whose
+// DPP source does not exist, or whose row is masked off, receive `identity`.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_move(int identity, int src) {
+  return __builtin_amdgcn_update_dpp(identity, src, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+  v += dpp_move<kDppRowShr1>(0, v);
+  v += dpp_move<kDppRowShr2>(0, v);
+  v += dpp_move<kDppRowShr4>(0, v);
+  v += dpp_move<kDppRowShr8>(0, v);
+  v += dpp_move<kDppRowBcast15, 0xa>(0, v);
+  v += dpp_move<kDppRowBcast31, 0xc>(0, v);
+  return v;
+}
+// Sum over each aligned group of N (8 or 16) lanes, delivered to every lane of
+// the group: butterfly on quad permutes, then the half-row / row mirrors.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+template <int N>
+__device__ __forceinline__ double group_sum_f64(double v) {
+  static_assert(N == 8 || N == 16, "group of 8 or 16 lanes");
+  v += dpp_move_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move_f64<0x141>(v);   // row_half_mirror
+  if (N == 16) v += dpp_move_f64<0x140>(v);  // row_mirror
+  return v;
+}
+
+// Combine a value over the four lanes {l, l^16, l^32, l^48} (the four rows of a
+// wave) with the gfx950 row-swap instructions.
+typedef unsigned uint2s_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max_f32(float v) {
+  uint2s_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  const float m = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float rows_sum_f32(float v) {
+  uint2s_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  const float m = __uint_as_float(r.x) + __uint_as_float(r.y);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
+// Reductions over the wave; the result is returned as a scalar (lane 63 of the scan).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  int x = (int)v;
+  const int id = -1;  // 0xffffffff
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowShr1>(id, x));
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowShr2>(id, x));
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowShr4>(id, x));
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowShr8>(id, x));
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast15, 0xa>(id, x));
+  x = (int)min((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast31, 0xc>(id, x));
+  return (uint32_t)__builtin_amdgcn_readlane(x, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  int x = (int)v;
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowShr1>(0, x));
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowShr2>(0, x));
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowShr4>(0, x));
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowShr8>(0, x));
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast15, 0xa>(0, x));
+  x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast31, 0xc>(0, x));
+  return (uint32_t)__builtin_amdgcn_readlane(x, 63);
+}
+
 // Agent-scope (whole GPU, all XCDs) synchronisation words.
 __device__ __forceinline__ int atomic_add_agent(int* p, int v) {
   return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -83,5 +159,20 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
   }
   return 0;
 }
+
+
+// Phase timestamps for tuning builds (-DTS_PROFILE): thread 0 of every
+// workgroup records the constant-rate 100 MHz clock at numbered points.
+// Compiled out of the product library.
+#ifdef TS_PROFILE
+__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][16]
+#define TS_MARK(i)                                                                      \
+  do {                                                                                  \
+    if (threadIdx.x == 0 && ts::g_profile_buf)                                          \
+      ts::g_profile_buf[(size_t)blockIdx.x * 16 + (i)] = wall_clock64();                \
+  } while (0)
+#else
+#define TS_MARK(i) do { } while (0)
+#endif
 
 }  // namespace ts

@@ -27,20 +27,53 @@ struct ScoreLanes {
   static constexpr int PPI = PPW * U;       // pages one wave covers per iteration
   double qp[8], qn[8];
 
-  __device__ __forceinline__ void load_query(const uint16_t* q_group, int G) {
+  // Qp / Qn of the unit, computed once per workgroup through LDS: the G query
+  // rows arrive with a single round of 16-byte loads (a per-lane loop over the
+  // heads would pay one memory round trip per head), threads 0..D-1 reduce one
+  // channel each over the heads, and every lane picks up its 8 channels.
+  // Split in two so the caller can issue other loads between the query load
+  // and its first use (loads return in issue order: what is needed first is
+  // issued first).  stage: LDS scratch of query_stage_bytes(G) bytes.
+  static constexpr size_t query_stage_bytes(int G) { return (size_t)G * D * 2 + 2 * D * 8; }
+  static constexpr int kQueryLoads = 16 * D / 8 / kThreads > 0 ? 16 * D / 8 / kThreads : 1;
+
+  struct QueryRegs { uint4 w[kQueryLoads]; };
+
+  __device__ __forceinline__ static void issue_query(QueryRegs& r, const uint16_t* q_group, int G) {
+    const int n16 = G * D / 8;
+#pragma unroll
+    for (int k = 0; k < kQueryLoads; ++k) {
+      const int i = threadIdx.x + k * kThreads;
+      r.w[k] = i < n16 ? reinterpret_cast<const uint4*>(q_group)[i] : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  // Two barriers.
+  __device__ __forceinline__ void finish_query(const QueryRegs& r, int G, unsigned char* stage) {
+    uint4* raw = reinterpret_cast<uint4*>(stage);
+    double* red = reinterpret_cast<double*>(stage + (size_t)G * D * 2);   // [2][D]
+    const int n16 = G * D / 8;
+#pragma unroll
+    for (int k = 0; k < kQueryLoads; ++k) {
+      const int i = threadIdx.x + k * kThreads;
+      if (i < n16) raw[i] = r.w[k];
+    }
+    __syncthreads();
+    if (threadIdx.x < D) {
+      const uint16_t* col = reinterpret_cast<const uint16_t*>(stage) + threadIdx.x;
+      double p = 0.0, n = 0.0;
+      for (int g = 0; g < G; ++g) {
+        const float f = bf16_to_f32(col[g * D]);
+        p += static_cast<double>(fmaxf(f, 0.f));
+        n += static_cast<double>(fminf(f, 0.f));
+      }
+      red[threadIdx.x] = p;
+      red[D + threadIdx.x] = n;
+    }
+    __syncthreads();
     const int cg = lane_id() % LPR;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { qp[i] = 0.0; qn[i] = 0.0; }
-    for (int g = 0; g < G; ++g) {
-      const uint4 w = *reinterpret_cast<const uint4*>(q_group + (size_t)g * D + cg * 8);
-      float f[8];
-      unpack8(w, f);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        qp[i] += static_cast<double>(fmaxf(f[i], 0.f));
-        qn[i] += static_cast<double>(fminf(f[i], 0.f));
-      }
-    }
+    for (int i = 0; i < 8; ++i) { qp[i] = red[cg * 8 + i]; qn[i] = red[D + cg * 8 + i]; }
   }
 
   __device__ __forceinline__ double row_partial(const uint4& mn, const uint4& mx) const {
@@ -90,9 +123,7 @@ struct MetaTile {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pg = base + u * PPW + prow;
-      double s = ql.row_partial(mn[u], mx[u]);
-#pragma unroll
-      for (int m = 1; m < LPR; m <<= 1) s += __shfl_xor(s, m, kWave);
+      const double s = group_sum_f64<LPR>(ql.row_partial(mn[u], mx[u]));
       if (cg == 0 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
     }
   }
@@ -100,21 +131,28 @@ struct MetaTile {
 
 // Scores the pages of one (sequence, KV head) that fall to this wave: wave
 // iterations it = first_iter, first_iter + iter_stride, ... each cover
-// ScoreLanes<D>::PPI consecutive pages.  The first metadata loads are issued
-// before the query is read.  Pb is passed as a callable so its (scalar) load
-// need not be waited for before the metadata loads go out.
-template <int D, typename PbFn, typename Sink>
+// ScoreLanes<D>::PPI consecutive pages.  Loads go out in the order their data
+// is needed: the query rows, then whatever `issue_extra` loads, then the first
+// metadata tile; only then is anything waited for.  `after_query` runs once the
+// query is in registers (it consumes the extra loads and returns Pb).  Must be
+// called by the whole workgroup (the query goes through LDS, q_stage, with
+// barriers).
+template <int D, typename IssueExtra, typename AfterQuery, typename Sink>
 __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const uint16_t* pmax_u,
                                                   const uint16_t* q_group, int G, int Pmax,
-                                                  int first_iter, int iter_stride, PbFn pb_fn,
-                                                  Sink sink) {
+                                                  int first_iter, int iter_stride,
+                                                  unsigned char* q_stage, IssueExtra issue_extra,
+                                                  AfterQuery after_query, Sink sink) {
   constexpr int PPI = ScoreLanes<D>::PPI;
+  typename ScoreLanes<D>::QueryRegs qr;
+  ScoreLanes<D>::issue_query(qr, q_group, G);
+  issue_extra();
   MetaTile<D> tile;
   int base = first_iter * PPI;
   if (base < Pmax) tile.load(pmin_u, pmax_u, base, Pmax);
   ScoreLanes<D> ql;
-  ql.load_query(q_group, G);
-  const int Pb = pb_fn();
+  ql.finish_query(qr, G, q_stage);
+  const int Pb = after_query();
   while (base < Pmax) {
     const int next = base + iter_stride * PPI;
     MetaTile<D> cur = tile;

@@ -28,40 +28,29 @@ struct SelectLds {
   uint32_t* hist;  // [kRadixBins]
   int* red;        // [32]         small reductions / broadcasts
 };
+// keys padded to a multiple of 4 words: hist is accessed 16 bytes at a time
 constexpr size_t select_lds_bytes(int Pmax) {
-  return (size_t)Pmax * 4 + kRadixBins * 4 + 32 * 4;
+  return (size_t)((Pmax + 3) / 4 * 4) * 4 + kRadixBins * 4 + 32 * 4;
 }
 __device__ __forceinline__ SelectLds carve_select(unsigned char* smem, int Pmax) {
   SelectLds L;
   L.keys = reinterpret_cast<uint32_t*>(smem);
-  L.hist = L.keys + Pmax;
+  L.hist = L.keys + (Pmax + 3) / 4 * 4;
   L.red = reinterpret_cast<int*>(L.hist + kRadixBins);
   return L;
-}
-
-// Inclusive scan of one int per thread over the workgroup (thread order).
-// red: 4 ints of LDS scratch.  Contains two barriers.
-__device__ __forceinline__ int block_inclusive_scan(int v, int* red) {
-  const int lane = lane_id(), wave = wave_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int up = __shfl_up(v, d, kWave);
-    if (lane >= d) v += up;
-  }
-  __syncthreads();  // red free
-  if (lane == kWave - 1) red[wave] = v;
-  __syncthreads();
-  int off = 0;
-  for (int w = 0; w < wave; ++w) off += uniform(red[w]);
-  return v + off;
 }
 
 // Keeps the Kb largest of keys[0..Pb) (ties: lower index first) and calls
 // emit(rank, page) for every kept page, rank = its position in ascending page
 // order.  All kThreads threads must call; Pb, Kb workgroup-uniform.
+//
+// hist is stored top bin first (slot k holds bin 2047 - k), so that a thread
+// reads its 8 consecutive bins with two 16-byte LDS loads and a scan in thread
+// order accumulates from the top bin down.
 template <typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int Kb, Emit emit) {
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+  constexpr int BPT = kRadixBins / kThreads;  // 8 bins per thread
   Pb = uniform(Pb);
   Kb = uniform(Kb);
   if (Kb <= 0) return;
@@ -69,19 +58,21 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int 
     for (int j = tid; j < Pb; j += kThreads) emit(j, j);
     return;
   }
-  // range of the keys
+  // range of the keys (and the bins cleared for the first pass)
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int j = tid; j < Pb; j += kThreads) {
-    const uint32_t k = L.keys[j];
-    kmin = min(kmin, k);
-    kmax = max(kmax, k);
-  }
+  for (int j0 = tid; j0 < Pb; j0 += kThreads * 4) {
+    uint32_t k[4];
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, m, kWave));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, m, kWave));
+    for (int i = 0; i < 4; ++i) k[i] = j0 + i * kThreads < Pb ? L.keys[j0 + i * kThreads] : 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (j0 + i * kThreads < Pb) { kmin = min(kmin, k[i]); kmax = max(kmax, k[i]); }
   }
+  kmin = wave_min_u32(kmin);
+  kmax = wave_max_u32(kmax);
   if (lane == 0) { L.red[8 + wave] = (int)kmin; L.red[12 + wave] = (int)kmax; }
+  reinterpret_cast<uint4*>(L.hist)[tid * 2] = make_uint4(0, 0, 0, 0);
+  reinterpret_cast<uint4*>(L.hist)[tid * 2 + 1] = make_uint4(0, 0, 0, 0);
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
@@ -90,6 +81,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int 
   }
   kmin = (uint32_t)uniform((int)kmin);
   kmax = (uint32_t)uniform((int)kmax);
+  TS_MARK(10);
 
   // Candidates: normalised keys nk = key - kmin with nk in [base, base + 2^bits).
   // Everything above that interval is already known to be kept; `need` more are
@@ -97,25 +89,42 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int 
   uint32_t base = 0u;
   int bits = 32 - __clz((int)(kmax - kmin));  // 0 when all keys are equal
   int need = Kb;
+  bool first = true;
   while (bits > 0) {
     const int s = max(bits - kRadixBits, 0);
-    for (int i = tid; i < kRadixBins; i += kThreads) L.hist[i] = 0u;
-    __syncthreads();
-    for (int j = tid; j < Pb; j += kThreads) {
-      const uint32_t nk = L.keys[j] - kmin;
-      if (nk >= base) {
+    if (!first) {
+      reinterpret_cast<uint4*>(L.hist)[tid * 2] = make_uint4(0, 0, 0, 0);
+      reinterpret_cast<uint4*>(L.hist)[tid * 2 + 1] = make_uint4(0, 0, 0, 0);
+      __syncthreads();
+    }
+    first = false;
+    for (int j0 = tid; j0 < Pb; j0 += kThreads * 4) {
+      uint32_t k[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) k[i] = j0 + i * kThreads < Pb ? L.keys[j0 + i * kThreads] : 0u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t nk = k[i] - kmin;
         const uint32_t d = nk - base;
-        if (bits >= 32 || (d >> bits) == 0u) atomicAdd(&L.hist[d >> s], 1u);
+        const bool in = j0 + i * kThreads < Pb && nk >= base && (bits >= 32 || (d >> bits) == 0u);
+        if (in) atomicAdd(&L.hist[kRadixBins - 1 - (d >> s)], 1u);
       }
     }
     __syncthreads();
-    // thread t owns bins 2047-8t .. 2040-8t (descending), so a scan in thread
-    // order accumulates from the top bin down
-    constexpr int BPT = kRadixBins / kThreads;
-    int c[BPT], tot = 0;
+    TS_MARK(11);
+    // thread t owns slots 8t..8t+7 = bins 2047-8t .. 2040-8t
+    const uint4 h0 = reinterpret_cast<const uint4*>(L.hist)[tid * 2];
+    const uint4 h1 = reinterpret_cast<const uint4*>(L.hist)[tid * 2 + 1];
+    const int c[BPT] = {(int)h0.x, (int)h0.y, (int)h0.z, (int)h0.w,
+                        (int)h1.x, (int)h1.y, (int)h1.z, (int)h1.w};
+    int tot = 0;
 #pragma unroll
-    for (int i = 0; i < BPT; ++i) { c[i] = (int)L.hist[kRadixBins - 1 - (tid * BPT + i)]; tot += c[i]; }
-    const int incl = block_inclusive_scan(tot, L.red);
+    for (int i = 0; i < BPT; ++i) tot += c[i];
+    int incl = wave_inclusive_sum(tot);
+    if (lane == kWave - 1) L.red[wave] = incl;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) incl += uniform(L.red[w]);
+    TS_MARK(12);
     int run = incl - tot;
     if (run < need && need <= incl) {  // exactly one thread: the cut-off bin is one of its own
 #pragma unroll
@@ -135,6 +144,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int 
     bits = s;
     if (cnt == need) break;  // the whole cut-off bin is kept
   }
+  TS_MARK(13);
   // Kept: nk >= base + 2^bits, plus the first `need` (in page order) of the
   // pages with nk in [base, base + 2^bits).  (bits == 0: one exact value.)
   auto classify = [&](int j, bool& g, bool& e) {
@@ -158,6 +168,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, int Pb, int 
     ce += __popcll(__ballot(e));
   }
   __syncthreads();  // red[4..6] no longer read
+  TS_MARK(14);
   if (lane == 0) { L.red[16 + wave] = cg; L.red[20 + wave] = ce; }
   __syncthreads();
   int goff = 0, eoff = 0;
