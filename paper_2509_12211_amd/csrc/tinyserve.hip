@@ -22,6 +22,8 @@ namespace ts {
 // compute unit; with thousands of units g = 1 and nothing is exchanged
 // between workgroups at all.
 constexpr int kCtrlWords = 64;   // control words at the head of the workspace
+constexpr int kCtrlTicket = 0;   // next unit (fused kernel, g == 1, more units than workgroups)
+constexpr int kCtrlExit = 1;     // workgroups that have finished taking tickets
 constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
 constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
 constexpr int kTargetWorkgroups = 512;
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
                                                                int32_t* sel, int32_t* sel_count,
                                                                int Hkv, int S, int Pmax, int Kmax) {
   extern __shared__ __align__(16) unsigned char smem[];
+  TS_MARK(0);
   const int u = blockIdx.x, b = u / Hkv, h = u % Hkv;
   const int Pb = uniform(min(pages_of(seq_lens[b], S), Pmax));
   const int K = topk_per_seq ? topk_per_seq[b] : topk;
@@ -124,9 +127,29 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
   const float* srow = scores + (size_t)u * Pmax;
   int32_t* row = sel + (size_t)u * Kmax;
   for (int i = Kb + threadIdx.x; i < Kmax; i += kThreads) row[i] = -1;
-  for (int j = threadIdx.x; j < Pb; j += kThreads) L.keys[j] = score_key(srow[j]);
+  // eight loads per thread in flight per round (a plain loop would pay one
+  // memory round trip per iteration); the key range is gathered on the way
+  const KeyLayout kl = KeyLayout::make(Pb);
+  uint32_t tmin = 0xffffffffu, tmax = 0u;
+  for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = j0 + i * kThreads < Pb ? srow[j0 + i * kThreads] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = j0 + i * kThreads;
+      if (j < Pb) {
+        const uint32_t k = score_key(v[i]);
+        L.keys[kl.at(j)] = k;
+        tmin = min(tmin, k);
+        tmax = max(tmax, k);
+      }
+    }
+  }
   __syncthreads();
-  select_topk_lds(L, Pb, Kb, [&](int rank, int page) { row[rank] = page; });
+  TS_MARK(1);
+  select_topk_lds(L, kl, Pb, Kb, tmin, tmax, [&](int rank, int page) { row[rank] = page; });
+  TS_MARK(5);
 }
 
 // grid (g, units).  The last workgroup of a unit to deposit its partial merges
@@ -192,8 +215,21 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   int32_t* bt_lds = reinterpret_cast<int32_t*>(smem + (sel_bytes > att_bytes ? sel_bytes : att_bytes));
   int32_t* my_sel = bt_lds + Pmax;  // [chunk]
   const bool exchange = g > 1;
+  // With one workgroup per unit and more units than workgroups (long ragged
+  // batches) the units are handed out from a counter as workgroups become
+  // free: a unit then takes tens of microseconds, so the counter is not
+  // contended, and the spread of sequence lengths no longer decides the finish
+  // time.  Nothing ever waits on a ticket holder.
+  const bool dynamic = !exchange && p.units > (int)gridDim.x;
+  int u = blockIdx.x / g;
+  if (dynamic) {
+    if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
+    __syncthreads();
+    u = uniform(s_flag);
+    __syncthreads();
+  }
 
-  for (int u = blockIdx.x / g; u < p.units; u += n_clusters) {
+  while (u < p.units) {
     TS_MARK(0);
     const int b = u / at.Hkv, h = u % at.Hkv;
     const uint16_t* q_group = at.q + ((size_t)b * at.Hq + (size_t)h * G) * D;
@@ -206,6 +242,9 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // with the query and metadata loads) and parked in LDS
     constexpr int kBtRegs = 8;
     int bt_regs[kBtRegs];
+    KeyLayout kl;
+    int pb_scan = 0;                         // the unit's page count, known once the scan runs
+    uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
     score_pages_waves<D>(
         p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, q_group, G, Pmax,
         member * kWaves + wave_id(), g * kWaves, reinterpret_cast<unsigned char*>(sl.hist),
@@ -224,11 +263,19 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           for (int j = threadIdx.x + kBtRegs * kThreads; j < Pmax; j += kThreads)
             bt_lds[j] = bt_row[j];
-          return min(pages_of(at.seq_lens[b], p.S), Pmax);
+          pb_scan = min(pages_of(at.seq_lens[b], p.S), Pmax);
+          kl = KeyLayout::make(pb_scan);
+          return pb_scan;
         },
         [&](int pg, float s) {
-          if (exchange) store_agent(srow + pg, s);
-          else sl.keys[pg] = score_key(s);
+          if (exchange) {
+            store_agent(srow + pg, s);
+          } else if (pg < pb_scan) {
+            const uint32_t k = score_key(s);
+            sl.keys[kl.at(pg)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
+          }
           if (srow_out) srow_out[pg] = s;
         });
     const int L = uniform(at.seq_lens[b]);
@@ -262,7 +309,12 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int j = j0 + i * kThreads;
-          if (j < Pb) sl.keys[j] = score_key(v[i]);
+          if (j < Pb) {
+            const uint32_t k = score_key(v[i]);
+            sl.keys[kl.at(j)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
+          }
         }
       }
     }
@@ -275,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (sel_row)
       for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
     if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
-    select_topk_lds(sl, Pb, Kb, [&](int rank, int page) {
+    select_topk_lds(sl, kl, Pb, Kb, tmin, tmax, [&](int rank, int page) {
       if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
       if (sel_row) sel_row[rank] = page;
     });
@@ -305,6 +357,22 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
         atomic_store_agent(&p.attend_done[u], 0);
       }
       __syncthreads();
+    }
+    if (dynamic) {
+      __syncthreads();
+      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
+      __syncthreads();
+      u = uniform(s_flag);
+      __syncthreads();
+    } else {
+      u += n_clusters;
+    }
+  }
+  if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
+    __syncthreads();
+    if (threadIdx.x == 0 && atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
+      atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
+      atomic_store_agent(&p.ctrl[kCtrlExit], 0);
     }
   }
 }

@@ -217,7 +217,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     const int n = min(kWave, (count - batch + kWaves - 1) / kWaves);
     // A ring of NBUF page buffers: up to NBUF pages of this wave are in flight
     // (4 KiB - 8 KiB each) before the first is consumed.
-    constexpr int NBUF = (D * S <= 1024) ? 4 : (D * S <= 2048 ? 3 : 2);
+    constexpr int NBUF = (D * S <= 1024) ? 4 : ((D == 64 && D * S <= 2048) ? 3 : 2);
     PageFrag<D, S> f[NBUF];
     int valid[NBUF];
     auto issue = [&](PageFrag<D, S>& fr, int x) -> int {

@@ -153,10 +153,12 @@ __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const 
   ScoreLanes<D> ql;
   ql.finish_query(qr, G, q_stage);
   const int Pb = after_query();
+  // only the first tile is fetched blind; later ones stop at the sequence's
+  // last page (pages >= Pb still get their -inf through the sink)
   while (base < Pmax) {
     const int next = base + iter_stride * PPI;
     MetaTile<D> cur = tile;
-    if (next < Pmax) tile.load(pmin_u, pmax_u, next, Pmax);
+    if (next < Pb) tile.load(pmin_u, pmax_u, next, Pb);
     cur.reduce(ql, base, Pb, Pmax, sink);
     base = next;
   }
