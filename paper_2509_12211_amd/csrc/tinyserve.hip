@@ -18,15 +18,15 @@ namespace ts {
 // ---------------------------------------------------------------------------
 // A unit is one (sequence, KV head).  A unit is worked on by a cluster of g
 // workgroups: each scores 1/g of the unit's pages and attends 1/g of its
-// selected pages.  g is chosen so that units * g is about two workgroups per
-// compute unit; with thousands of units g = 1 and nothing is exchanged
+// selected pages.  g is chosen so that units * g is about one workgroup (eight
+// waves) per compute unit; with thousands of units g = 1 and nothing is exchanged
 // between workgroups at all.
 constexpr int kCtrlWords = 64;   // control words at the head of the workspace
 constexpr int kCtrlTicket = 0;   // next unit (fused kernel, g == 1, more units than workgroups)
 constexpr int kCtrlExit = 1;     // workgroups that have finished taking tickets
 constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
 constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
-constexpr int kTargetWorkgroups = 512;
+constexpr int kTargetWorkgroups = 256;
 constexpr int kMaxCluster = 64;
 
 struct Plan {
@@ -667,7 +667,7 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
   p.g = pl.g;
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
-  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 2;
+  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
 #define TS_LAUNCH_FUSED(DD, SS)                                                          \
   do {                                                                                   \
     if ((st = allow_lds(query_aware_decode_kernel<DD, SS>, pl.lds_fused)) != TS_OK)      \

@@ -7,7 +7,7 @@
 namespace ts {
 
 constexpr int kWave = 64;
-constexpr int kThreads = 256;            // every kernel here runs 4 wavefronts per workgroup
+constexpr int kThreads = 512;            // every kernel here runs 8 wavefronts per workgroup
 constexpr int kWaves = kThreads / kWave;
 
 typedef short short4_t __attribute__((ext_vector_type(4)));

@@ -51,14 +51,14 @@ struct KeyLayout {
 struct SelectLds {
   uint32_t* keys;  // [select_key_words(Pmax)]  filled by the caller through KeyLayout::at
   uint32_t* hist;  // [kRadixBins]
-  int* red;        // [32]   small reductions / broadcasts
+  int* red;        // [64]   [0..7] wave sums, [8..10] cut, [16..31] / [32..47] key ranges
 };
 constexpr size_t select_key_words(int Pmax) {
   // kThreads chunks of (C | 1) words, C = ceil(Pmax / kThreads), padded to 16 bytes
   return (size_t)((kThreads * ((((Pmax + kThreads - 1) / kThreads)) | 1) + 3) / 4 * 4);
 }
 constexpr size_t select_lds_bytes(int Pmax) {
-  return select_key_words(Pmax) * 4 + kRadixBins * 4 + 32 * 4;
+  return select_key_words(Pmax) * 4 + kRadixBins * 4 + 64 * 4;
 }
 __device__ __forceinline__ SelectLds carve_select(unsigned char* smem, int Pmax) {
   SelectLds L;
@@ -85,14 +85,15 @@ __device__ __forceinline__ SelectLds carve_select(unsigned char* smem, int Pmax)
 // minimum.
 //
 // hist is stored top bin first (slot k holds bin 2047 - k), so that a thread
-// reads its 8 consecutive bins with two 16-byte LDS loads and a scan in thread
+// reads its consecutive bins with 16-byte LDS loads and a scan in thread
 // order accumulates from the top bin down.
 template <typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLayout& kl, int Pb,
                                                 int Kb, uint32_t tmin, uint32_t tmax, Emit emit) {
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   constexpr int BPT = kRadixBins / kThreads;  // bins per thread
-  static_assert(BPT == 8, "bin scan written for 8 bins per thread");
+  static_assert(BPT == 4 || BPT == 8, "bin scan written for 4 or 8 bins per thread");
+  static_assert(kWaves <= 8, "red[] layout holds 8 wave slots");
   constexpr int kBatch = 8;  // LDS reads issued together
   Pb = uniform(Pb);
   Kb = uniform(Kb);
@@ -107,8 +108,9 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const uint32_t* my_keys = L.keys + tid * kl.stride;
 
   auto clear_bins = [&] {
-    reinterpret_cast<uint4*>(L.hist)[tid * 2] = make_uint4(0, 0, 0, 0);
-    reinterpret_cast<uint4*>(L.hist)[tid * 2 + 1] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < BPT / 4; ++i)
+      reinterpret_cast<uint4*>(L.hist)[tid * (BPT / 4) + i] = make_uint4(0, 0, 0, 0);
   };
   // Block-wide min / max from per-thread partials; one barrier.
   auto block_range = [&](uint32_t& lo, uint32_t& hi, int slot) {
@@ -137,10 +139,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   // Top-down scan of the bins: finds the bin in which the `need`-th largest
   // counted key falls.  Two barriers.  Returns bin, keys above it, keys in it.
   auto find_cut = [&](int need, int& bin, int& above, int& cnt) {
-    const uint4 h0 = reinterpret_cast<const uint4*>(L.hist)[tid * 2];
-    const uint4 h1 = reinterpret_cast<const uint4*>(L.hist)[tid * 2 + 1];
-    const int c[BPT] = {(int)h0.x, (int)h0.y, (int)h0.z, (int)h0.w,
-                        (int)h1.x, (int)h1.y, (int)h1.z, (int)h1.w};
+    int c[BPT];
+#pragma unroll
+    for (int i = 0; i < BPT / 4; ++i) {
+      const uint4 h = reinterpret_cast<const uint4*>(L.hist)[tid * (BPT / 4) + i];
+      c[4 * i] = (int)h.x; c[4 * i + 1] = (int)h.y; c[4 * i + 2] = (int)h.z; c[4 * i + 3] = (int)h.w;
+    }
     int tot = 0;
 #pragma unroll
     for (int i = 0; i < BPT; ++i) tot += c[i];
@@ -157,23 +161,23 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
 #pragma unroll
       for (int i = 0; i < BPT; ++i) {
         if (run < need && need <= run + c[i]) {
-          L.red[4] = kRadixBins - 1 - (tid * BPT + i);
-          L.red[5] = run;
-          L.red[6] = c[i];
+          L.red[8] = kRadixBins - 1 - (tid * BPT + i);
+          L.red[9] = run;
+          L.red[10] = c[i];
         }
         run += c[i];
       }
     }
     __syncthreads();
-    bin = uniform(L.red[4]);
-    above = uniform(L.red[5]);
-    cnt = uniform(L.red[6]);
+    bin = uniform(L.red[8]);
+    above = uniform(L.red[9]);
+    cnt = uniform(L.red[10]);
   };
 
   // ---- stage 1: linear bins over [s_min, s_max] ------------------------------
   uint32_t kmin = tmin, kmax = tmax;
   clear_bins();
-  block_range(kmin, kmax, 8);
+  block_range(kmin, kmax, 16);
   TS_MARK(10);
   const float smin = key_score(kmin);
   const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
@@ -201,7 +205,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
       for_my_keys([&](uint32_t k, int) {
         if (linear_bin(k) == cut_bin) { clo = min(clo, k); chi = max(chi, k); }
       });
-      block_range(clo, chi, 16);
+      block_range(clo, chi, 32);
       bits = 32 - __clz((int)(chi - clo));  // 0: all of the bin's keys are equal
       while (bits > 0) {
         const int s = max(bits - kRadixBits, 0);
@@ -253,7 +257,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const int cg = __popcll(gbits), ce = __popcll(ebits);
   const int packed = cg | (ce << 16);  // both sums stay below 2^15
   int incl = wave_inclusive_sum(packed);
-  __syncthreads();  // red[0..6] no longer read
+  __syncthreads();  // red[0..10] no longer read
   if (lane == kWave - 1) L.red[wave] = incl;
   __syncthreads();
 #pragma unroll
