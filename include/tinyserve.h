@@ -50,7 +50,8 @@ extern "C" {
 typedef enum ts_status {
   TS_OK = 0,
   TS_ERR_NULL = -1,        /* a required pointer is NULL                                   */
-  TS_ERR_SHAPE = -2,       /* non-positive dimension, Hq % Hkv != 0, topk < 1, max_topk < topk */
+  TS_ERR_SHAPE = -2,       /* non-positive dimension, Hq % Hkv != 0, topk < 1, max_topk < topk,
+                              0 < kv_tile_stride < S*d or not a multiple of 8 */
   TS_ERR_UNSUPPORTED = -3, /* head_dim / page_size / group size / page count outside the built set */
   TS_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than ts_workspace_bytes()             */
   TS_ERR_LAUNCH = -5,      /* the HIP runtime reported an error when enqueueing             */
@@ -61,6 +62,13 @@ typedef enum ts_status {
  *   k_pool      bf16 [num_phys_pages][Hkv][S][d]   a (page, head) K tile is S*d contiguous
  *   v_pool      bf16 [num_phys_pages][Hkv][d][S]   V tile stored channel-major (transposed),
  *                                                  so the token axis is contiguous
+ *   The tile of (physical page p, head h) starts kv_tile_stride elements after
+ *   the tile of (p, h-1) in both pools; 0 means S*d (two dense pools).  The
+ *   layout this library is tuned for interleaves the two: one allocation
+ *   [num_phys_pages][Hkv][2][S*d], k_pool = base, v_pool = base + S*d,
+ *   kv_tile_stride = 2*S*d, so the K and V tiles of a page form one contiguous
+ *   4-8 KiB block (random 4 KiB reads reach ~40 % more HBM bandwidth than
+ *   random 2 KiB reads on this part).
  *   block_table int32 [B][P_max]                   logical page -> physical page
  *   seq_lens    int32 [B]                          tokens currently cached per sequence
  *   page_min,
@@ -75,7 +83,7 @@ typedef struct ts_layout {
   int32_t page_size;         /* S                                   */
   int32_t max_pages_per_seq; /* P_max: row stride of block_table, page_min, page_max, scores */
   int32_t num_phys_pages;    /* pool capacity                       */
-  int32_t reserved;          /* must be 0                           */
+  int32_t kv_tile_stride;    /* elements between consecutive (page, head) tiles; 0 = S*d */
   void* k_pool;
   void* v_pool;
   const int32_t* block_table;
@@ -102,7 +110,7 @@ int ts_append_token_meta(const ts_layout* layout, const void* k_new, const void*
 
 /* Eq. 2, step 1 of Algorithm 1.  q: bf16 [B][Hq][d].  scores: fp32
  * [B][Hkv][P_max]; entry (b, h, j) is the group-summed bound for j < P_b and
- * -inf for j >= P_b.  fp32 accumulation. */
+ * -inf for j >= P_b.  Accumulated in fp64, rounded to fp32 once. */
 int ts_score_pages(const ts_layout* layout, const void* q, float* scores, void* stream);
 
 /* Section 3.5 (S_t = TopK_j r, |S_t| = K), step 2 of Algorithm 1.  For each
@@ -154,11 +162,12 @@ int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 int ts_workspace_status(const void* workspace, int32_t* status_host);
 
 /* Launch-shape overrides for tuning sweeps; 0 restores the built-in choice.
- *   scan_pages_per_task  pages one workgroup scores per work item (multiple of 32)
- *   num_splits           workgroups sharing the selected pages of one (b, h)
+ *   reserved             must be 0
+ *   num_splits           workgroups sharing one (b, h): each scores 1/n of its pages and
+ *                        attends 1/n of its selected pages
  *   workgroups_per_cu    resident workgroups per compute unit of the fused kernel
  * Process-wide; affects ts_workspace_bytes too, so set it before sizing. */
-int ts_set_tuning(int32_t scan_pages_per_task, int32_t num_splits, int32_t workgroups_per_cu);
+int ts_set_tuning(int32_t reserved, int32_t num_splits, int32_t workgroups_per_cu);
 
 const char* ts_strerror(int status);
 int ts_version(void);

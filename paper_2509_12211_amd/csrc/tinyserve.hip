@@ -391,12 +391,19 @@ static int check_layout(const ts_layout* L) {
       L->page_size <= 0 || L->max_pages_per_seq <= 0 || L->num_phys_pages <= 0)
     return TS_ERR_SHAPE;
   if (L->num_q_heads % L->num_kv_heads != 0) return TS_ERR_SHAPE;
+  if (L->kv_tile_stride != 0 &&
+      (L->kv_tile_stride < L->head_dim * L->page_size || L->kv_tile_stride % 8 != 0))
+    return TS_ERR_SHAPE;
   if (L->head_dim != 64 && L->head_dim != 128) return TS_ERR_UNSUPPORTED;
   if (L->page_size != 16 && L->page_size != 32) return TS_ERR_UNSUPPORTED;
   if (L->num_q_heads / L->num_kv_heads > 16) return TS_ERR_UNSUPPORTED;
   if (L->max_pages_per_seq > TS_MAX_PAGES_PER_SEQ) return TS_ERR_UNSUPPORTED;
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
   return TS_OK;
+}
+
+static int tile_stride_of(const ts_layout* L) {
+  return L->kv_tile_stride ? L->kv_tile_stride : L->head_dim * L->page_size;
 }
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? TS_OK : TS_ERR_LAUNCH; }
@@ -445,6 +452,7 @@ static MetaParams meta_params(const ts_layout* L) {
   p.S = L->page_size;
   p.Pmax = L->max_pages_per_seq;
   p.n_phys = L->num_phys_pages;
+  p.tile_stride = tile_stride_of(L);
   return p;
 }
 
@@ -464,6 +472,7 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.Pmax = L->max_pages_per_seq;
   a.Kmax = max_topk;
   a.n_phys = L->num_phys_pages;
+  a.tile_stride = tile_stride_of(L);
   a.n_split = pl.g;
   a.chunk = pl.chunk;
   a.scale_log2 = softmax_scale * 1.4426950408889634f;

@@ -29,13 +29,14 @@ __device__ __forceinline__ float4_t mfma16(short4_t a, short4_t b, float4_t c) {
 
 struct AttendParams {
   const uint16_t* q;           // [B][Hq][D]
-  const uint16_t* k_pool;      // [n_phys][Hkv][S][D]
-  const uint16_t* v_pool;      // [n_phys][Hkv][D][S]
+  const uint16_t* k_pool;      // [n_phys][Hkv] tiles of [S][D], tile_stride apart
+  const uint16_t* v_pool;      // [n_phys][Hkv] tiles of [D][S], tile_stride apart
   const int32_t* block_table;  // [B][Pmax]
   const int32_t* seq_lens;     // [B]
   float* out;                  // [B][Hq][D]
   float* partials;             // [B*Hkv][n_split][G][D+2]
   int Hq, Hkv, G, Pmax, Kmax, n_phys, n_split, chunk;
+  int tile_stride;             // elements between consecutive (page, head) tiles
   float scale_log2;            // softmax_scale * log2(e)
 };
 
@@ -227,7 +228,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
         zero_page(fr);
         return 0;
       }
-      const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)(S * D);
+      const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
       load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile);
       return max(0, min(S, L - j * S));
     };

@@ -12,7 +12,7 @@ struct MetaParams {
   int32_t* seq_lens;
   uint16_t* page_min;
   uint16_t* page_max;
-  int B, Hkv, S, Pmax, n_phys;
+  int B, Hkv, S, Pmax, n_phys, tile_stride;
 };
 
 // One wavefront summarises one (sequence, KV head, logical page): the S x D
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
   const int phys = p.block_table[(size_t)b * p.Pmax + j];
   if (phys < 0 || phys >= p.n_phys) return;
   const int valid = min(p.S, L - j * p.S);
-  const uint16_t* tile = p.k_pool + ((size_t)phys * p.Hkv + h) * (size_t)p.S * D;
+  const uint16_t* tile = p.k_pool + ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
   const int cg = lane % LPR;
   float lo[8], hi[8];
 #pragma unroll
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams 
         if (x > bf16_to_f32(p.page_max[m])) p.page_max[m] = kn;
       }
       if (v_new != nullptr) {
-        const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.S * D;
+        const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
         p.k_pool_w[tile + (size_t)slot * D + c] = kn;
         p.v_pool_w[tile + (size_t)c * p.S + slot] = v_new[((size_t)b * p.Hkv + h) * D + c];
       }

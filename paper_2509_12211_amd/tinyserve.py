@@ -35,7 +35,7 @@ class TsLayout(ctypes.Structure):
         ("num_seqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
         ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("page_size", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
-        ("num_phys_pages", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("num_phys_pages", ctypes.c_int32), ("kv_tile_stride", ctypes.c_int32),
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
         ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
         ("page_min", ctypes.c_void_p), ("page_max", ctypes.c_void_p),
@@ -101,7 +101,15 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                 page_max) -> TsLayout:
     """Fill the C struct; tensors must stay alive while calls using it are in flight."""
     n_phys = 0 if k_pool is None else k_pool.shape[0]
-    lay = TsLayout(B, Hq, Hkv, d, S, P_max, n_phys, 0,
+    tile_stride = 0
+    if k_pool is not None and Hkv > 1:
+        # [n_phys][Hkv][...]: distance between the tiles of two heads (S*d for dense pools,
+        # 2*S*d when the K and V tiles of a page are interleaved in one allocation)
+        tile_stride = int(k_pool.stride(1))
+        assert k_pool.stride(0) == Hkv * tile_stride and v_pool.stride(1) == tile_stride
+    elif k_pool is not None:
+        tile_stride = int(k_pool.stride(0))
+    lay = TsLayout(B, Hq, Hkv, d, S, P_max, n_phys, tile_stride,
                    None if k_pool is None else k_pool.data_ptr(),
                    None if v_pool is None else v_pool.data_ptr(),
                    None if block_table is None else block_table.data_ptr(),
@@ -173,6 +181,6 @@ def query_aware_decode(layout, q, topk, max_topk, softmax_scale, out, workspace,
         "ts_query_aware_decode")
 
 
-def set_tuning(scan_pages_per_task=0, num_splits=0, workgroups_per_cu=0):
-    _check(lib().ts_set_tuning(int(scan_pages_per_task), int(num_splits),
+def set_tuning(reserved=0, num_splits=0, workgroups_per_cu=0):
+    _check(lib().ts_set_tuning(int(reserved), int(num_splits),
                                int(workgroups_per_cu)), "ts_set_tuning")

@@ -10,6 +10,9 @@ Pool layout (shared with include/tinyserve.h):
     k_pool  bf16 [num_phys_pages][Hkv][S][d]     one (page, head) K tile is S*d contiguous
     v_pool  bf16 [num_phys_pages][Hkv][d][S]     V tile stored channel-major (transposed)
     block_table int32 [B][P_max]                 logical page -> physical page
+By default the two pools are strided views of ONE allocation
+[num_phys_pages][Hkv][2][S*d], so the K and V tiles of a page are adjacent
+(interleave=False gives two dense pools instead).
 The five named workloads follow the shapes of the paper's small-model decoding
 (GPT2-345M and TinyLLaMA head geometry, contexts 4K-128K, page size 16/32,
 token budgets of 1/8 .. 1/4 of the pages); values are synthetic.
@@ -108,7 +111,7 @@ def _draw_keys(spec, g, Hkv, L, d, device, offset):
 
 
 def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
-                  poison: float = float("nan")) -> Workload:
+                  poison: float = float("nan"), interleave: bool = True) -> Workload:
     """Generate a workload on `device`.  Slots that hold no token (the tail of a
     partly filled page, the append headroom) are filled with `poison`."""
     device = torch.device(device)
@@ -135,8 +138,13 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
         block_table[b, :n] = perm[start:start + n].to(torch.int32)
         start += n
 
-    k_pool = torch.full((n_phys, Hkv, S, d), poison, dtype=torch.bfloat16, device=device)
-    v_pool = torch.full((n_phys, Hkv, d, S), poison, dtype=torch.bfloat16, device=device)
+    if interleave:
+        kv = torch.full((n_phys, Hkv, 2, S * d), poison, dtype=torch.bfloat16, device=device)
+        k_pool = kv[:, :, 0].view(n_phys, Hkv, S, d)
+        v_pool = kv[:, :, 1].view(n_phys, Hkv, d, S)
+    else:
+        k_pool = torch.full((n_phys, Hkv, S, d), poison, dtype=torch.bfloat16, device=device)
+        v_pool = torch.full((n_phys, Hkv, d, S), poison, dtype=torch.bfloat16, device=device)
     g = _gen(device, seed)
     offset = torch.randn((Hkv, d), generator=g, device=device, dtype=torch.float32) * 2.0
     bt_dev = block_table.to(device)

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 
 def _layout(**kw):
     base = dict(num_seqs=2, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16,
-                max_pages_per_seq=64, num_phys_pages=128, reserved=0,
+                max_pages_per_seq=64, num_phys_pages=128, kv_tile_stride=0,
                 k_pool=0x1000, v_pool=0x1000, block_table=0x1000, seq_lens=0x1000,
                 page_min=0x1000, page_max=0x1000)
     base.update(kw)
@@ -52,6 +52,8 @@ def test_workspace_bytes_is_host_only_and_monotone():
     (dict(num_seqs=0), ts.TS_ERR_SHAPE),
     (dict(num_q_heads=7), ts.TS_ERR_SHAPE),
     (dict(max_pages_per_seq=-1), ts.TS_ERR_SHAPE),
+    (dict(kv_tile_stride=512), ts.TS_ERR_SHAPE),      # smaller than one S*d tile
+    (dict(kv_tile_stride=2052), ts.TS_ERR_SHAPE),     # tiles must stay 16-byte aligned
     (dict(head_dim=96), ts.TS_ERR_UNSUPPORTED),
     (dict(page_size=8), ts.TS_ERR_UNSUPPORTED),
     (dict(num_q_heads=64, num_kv_heads=2), ts.TS_ERR_UNSUPPORTED),

@@ -114,7 +114,9 @@ def built():
 def test_reduced_all_units(oracle, built, name, scale_mode):
     spec = REDUCED[name]
     print(f"[case] reduced {name} scale={scale_mode}", flush=True)
-    w = wl.make_workload(spec, DEV, seed=2000 + len(name), n_q=2)
+    # paper-literal scale runs on two dense pools, the usual one on the interleaved K|V pool
+    w = wl.make_workload(spec, DEV, seed=2000 + len(name), n_q=2,
+                         interleave=(scale_mode == "rsqrt_d"))
     scale = 1.0 / math.sqrt(spec.d) if scale_mode == "rsqrt_d" else 1.0
     if scale_mode == "one":      # paper-literal softmax(q.k): keep logits in a sane range
         w.q.mul_(0.25)
