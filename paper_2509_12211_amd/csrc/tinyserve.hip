@@ -28,12 +28,24 @@ constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
 constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
 constexpr int kTargetWorkgroups = 256;
 constexpr int kMaxCluster = 64;
+// Per-unit counters are polled and bumped by every member of a cluster at once.
+// Each gets a 256-byte slot of its own while that fits the zeroed head of the
+// workspace: sixteen units' counters packed into one 64-byte line made every
+// workgroup of the launch hammer the same line (measured: 6 us of waiting with
+// 16 x 16 workgroups).  Only clusters (g > 1, at most a few hundred units) use
+// the counters, so large batches keep them packed.
+constexpr int kCounterPadUnits = 512;
+constexpr int kCounterPadStride = 64;   // int32 words
+constexpr size_t kZeroedWords = kCtrlWords + 2 * 65536;
+static_assert(kCtrlWords + 2 * (size_t)kCounterPadUnits * kCounterPadStride <= kZeroedWords,
+              "padded counters must lie inside the zeroed head of the workspace");
 
 struct Plan {
   int units;          // B * Hkv
   int g;              // workgroups per unit (= attention splits = score slices)
   int chunk;          // selected pages per workgroup
-  size_t off_unit;    // int32 [2][units]: scan_done, attend_done
+  size_t off_unit;    // int32 [2][units * cstride]: scan_done, attend_done
+  int cstride;        // words between the counters of consecutive units
   size_t off_scores;  // fp32 [units][Pmax]
   size_t off_part;    // fp32 [units][g][G][d+2]
   size_t total;
@@ -60,7 +72,8 @@ static Plan make_plan(const ts_layout* L, int max_topk) {
   pl.g = (max_topk + pl.chunk - 1) / pl.chunk;
   size_t off = kCtrlWords * sizeof(int32_t);
   pl.off_unit = off;
-  off = align_up(off + 2 * (size_t)pl.units * sizeof(int32_t), 256);
+  pl.cstride = pl.units <= kCounterPadUnits ? kCounterPadStride : 1;
+  off = align_up(off + 2 * (size_t)pl.units * pl.cstride * sizeof(int32_t), 256);
   pl.off_scores = off;
   off = align_up(off + (size_t)pl.units * Pmax * sizeof(float), 256);
   pl.off_part = off;
@@ -84,9 +97,9 @@ struct FusedParams {
   int32_t* sel_count;   // nullable [B]
   const int32_t* topk_per_seq;
   int32_t* ctrl;        // control words
-  int32_t* scan_done;   // [units]
-  int32_t* attend_done; // [units]
-  int topk, S, units, g;
+  int32_t* scan_done;   // [units * cstride]
+  int32_t* attend_done; // [units * cstride]
+  int topk, S, units, g, cstride;
 };
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
@@ -158,7 +171,8 @@ template <int D, int S>
 __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams p,
                                                                     const int32_t* sel,
                                                                     const int32_t* sel_count,
-                                                                    int32_t* unit_done) {
+                                                                    int32_t* unit_done,
+                                                                    int cstride) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
   const int u = blockIdx.y, b = u / p.Hkv, h = u % p.Hkv, split = blockIdx.x;
@@ -172,11 +186,11 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   if (p.n_split == 1) return;
   stores_complete();
   __syncthreads();
-  if (threadIdx.x == 0) s_last = atomic_add_agent(&unit_done[u], 1) == p.n_split - 1;
+  if (threadIdx.x == 0) s_last = atomic_add_agent(&unit_done[u * cstride], 1) == p.n_split - 1;
   __syncthreads();
   if (!uniform(s_last)) return;
   combine_splits<D>(p, b, h);
-  if (threadIdx.x == 0) atomic_store_agent(&unit_done[u], 0);
+  if (threadIdx.x == 0) atomic_store_agent(&unit_done[u * cstride], 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -290,8 +304,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       __syncthreads();
       TS_MARK(2);
       if (threadIdx.x == 0) {
-        atomic_add_agent(&p.scan_done[u], 1);
-        const int ok = wait_at_least(&p.scan_done[u], g, kSpinLimit);
+        atomic_add_agent(&p.scan_done[u * p.cstride], 1);
+        const int ok = wait_at_least(&p.scan_done[u * p.cstride], g, kSpinLimit);
         if (!ok) atomic_store_agent(&p.ctrl[kCtrlError], 1);
         s_flag = ok;
       }
@@ -345,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       stores_complete();
       __syncthreads();
       TS_MARK(7);
-      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u], 1) == g - 1;
+      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u * p.cstride], 1) == g - 1;
       __syncthreads();
       const int last = uniform(s_flag);
       TS_MARK(8);
@@ -353,8 +367,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       __syncthreads();
       TS_MARK(9);
       if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
-        atomic_store_agent(&p.scan_done[u], 0);
-        atomic_store_agent(&p.attend_done[u], 0);
+        atomic_store_agent(&p.scan_done[u * p.cstride], 0);
+        atomic_store_agent(&p.attend_done[u * p.cstride], 0);
       }
       __syncthreads();
     }
@@ -524,10 +538,10 @@ int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return TS_ERR_NULL;
   if (workspace_bytes < kCtrlWords * sizeof(int32_t)) return TS_ERR_WORKSPACE;
   // control words + per-unit counters live at the head; zeroing the first
-  // ~0.5 MiB covers them for every supported unit count (<= 65535)
+  // ~0.5 MiB covers them for every supported unit count (<= 65535 packed,
+  // <= kCounterPadUnits padded)
   size_t n = workspace_bytes / sizeof(int32_t);
-  const size_t cap = kCtrlWords + 2 * 65536;
-  if (n > cap) n = cap;
+  if (n > kZeroedWords) n = kZeroedWords;
   fill_zero_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
       static_cast<int32_t*>(workspace), n);
   return launch_status();
@@ -626,19 +640,23 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
-  int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units;
+  int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units * pl.cstride;
   const size_t lds = (size_t)kWaves * a.G * (layout->head_dim + 2) * 4;
   dim3 grid(pl.g, pl.units);
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
   if (D == 64 && S == 16)
-    sparse_attention_kernel<64, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done);
+    sparse_attention_kernel<64, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
+                                                               pl.cstride);
   else if (D == 64 && S == 32)
-    sparse_attention_kernel<64, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done);
+    sparse_attention_kernel<64, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
+                                                               pl.cstride);
   else if (D == 128 && S == 16)
-    sparse_attention_kernel<128, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done);
+    sparse_attention_kernel<128, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
+                                                               pl.cstride);
   else
-    sparse_attention_kernel<128, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done);
+    sparse_attention_kernel<128, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
+                                                               pl.cstride);
   return launch_status();
 }
 
@@ -669,7 +687,8 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
   p.topk_per_seq = topk_per_seq;
   p.ctrl = reinterpret_cast<int32_t*>(ws);
   p.scan_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
-  p.attend_done = p.scan_done + pl.units;
+  p.attend_done = p.scan_done + (size_t)pl.units * pl.cstride;
+  p.cstride = pl.cstride;
   p.topk = topk;
   p.S = layout->page_size;
   p.units = pl.units;

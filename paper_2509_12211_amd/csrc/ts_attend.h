@@ -235,6 +235,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 #pragma unroll
     for (int i = 0; i < NBUF; ++i)
       if (i < n) valid[i] = issue(f[i], i);
+    TS_MARK(17);
     for (int x0 = 0; x0 < n; x0 += NBUF) {
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
@@ -248,6 +249,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   }
 
   // merge the wave states
+  TS_MARK(18);
   const float l = rows_sum_f32(acc.l);
   constexpr int RS = D + 2;
   if (head < G) {

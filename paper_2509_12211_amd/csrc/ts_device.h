@@ -165,11 +165,11 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
 // workgroup records the constant-rate 100 MHz clock at numbered points.
 // Compiled out of the product library.
 #ifdef TS_PROFILE
-__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][16]
+__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][32]
 #define TS_MARK(i)                                                                      \
   do {                                                                                  \
     if (threadIdx.x == 0 && ts::g_profile_buf)                                          \
-      ts::g_profile_buf[(size_t)blockIdx.x * 16 + (i)] = wall_clock64();                \
+      ts::g_profile_buf[(size_t)blockIdx.x * 32 + (i)] = wall_clock64();                \
   } while (0)
 #else
 #define TS_MARK(i) do { } while (0)

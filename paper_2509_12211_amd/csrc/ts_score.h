@@ -152,6 +152,7 @@ __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const 
   if (base < Pmax) tile.load(pmin_u, pmax_u, base, Pmax);
   ScoreLanes<D> ql;
   ql.finish_query(qr, G, q_stage);
+  TS_MARK(16);
   const int Pb = after_query();
   // only the first tile is fetched blind; later ones stop at the sequence's
   // last page (pages >= Pb still get their -inf through the sink)
