@@ -130,6 +130,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
                                                                int32_t* sel, int32_t* sel_count,
                                                                int Hkv, int S, int Pmax, int Kmax) {
   extern __shared__ __align__(16) unsigned char smem[];
+  TS_MARK_INIT();
   TS_MARK(0);
   const int u = blockIdx.x, b = u / Hkv, h = u % Hkv;
   const int Pb = uniform(min(pages_of(seq_lens[b], S), Pmax));
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
   for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
     float v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = j0 + i * kThreads < Pb ? srow[j0 + i * kThreads] : 0.f;
+    for (int i = 0; i < 8; ++i) v[i] = srow[min(j0 + i * kThreads, Pb - 1)];  // no branch around the load
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int j = j0 + i * kThreads;
@@ -215,10 +216,19 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 // Every thread-0-only block sits between two barriers and every value that
 // steers a branch around a barrier is pinned uniform.
 // ---------------------------------------------------------------------------
-template <int D, int S>
+//
+// kLoop = false is the build for launches in which every cluster has exactly one
+// unit (units * g workgroups all resident: every latency-bound shape).  Without
+// the loop around the body the compiler has nothing to hoist: with it, every
+// unit-independent value of the whole body (several hundred instructions, most
+// of them spilled at once) is computed ahead of the first unit, that is ahead of
+// the first load.
+template <int D, int S, bool kLoop>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_flag;
+  TS_MARK_INIT();
+  TS_MARK(22);
   const AttendParams& at = p.at;
   const int g = p.g, G = at.G, Pmax = at.Pmax;
   const int member = blockIdx.x % g;
@@ -234,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   // free: a unit then takes tens of microseconds, so the counter is not
   // contended, and the spread of sequence lengths no longer decides the finish
   // time.  Nothing ever waits on a ticket holder.
-  const bool dynamic = !exchange && p.units > (int)gridDim.x;
+  const bool dynamic = kLoop && !exchange && p.units > (int)gridDim.x;
   int u = blockIdx.x / g;
   if (dynamic) {
     if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
@@ -243,32 +253,42 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     __syncthreads();
   }
 
-  while (u < p.units) {
+  // The first loads of a unit (sequence length, K, query rows, block-table row,
+  // first metadata tile) are sent out ahead of everything else: for the first
+  // unit right here, before the set-up work that follows, for later units at the
+  // end of the unit before.  What they fetch is only looked at inside the loop.
+  constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
+  int L_raw, K_raw, bt_regs[kBtRegs];
+  ScanRegs<D> scan;
+  auto issue_unit = [&](int uu) {
+    const int b = uu / at.Hkv, h = uu % at.Hkv;
+    L_raw = at.seq_lens[b];
+    K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
+    scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
+    const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
+#pragma unroll
+    for (int k = 0; k < kBtRegs; ++k)   // no branch around the loads
+      bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
+    scan_issue_tile<D>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
+                       Pmax, member * kWaves + wave_id());
+  };
+  if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
+  TS_MARK(23);
+
+  while (kLoop ? u < p.units : true) {
     TS_MARK(0);
     const int b = u / at.Hkv, h = u % at.Hkv;
-    const uint16_t* q_group = at.q + ((size_t)b * at.Hq + (size_t)h * G) * D;
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
     float* srow = p.scores + (size_t)u * Pmax;
     float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
 
-    // 1. score my share of the pages; the unit's block-table row is fetched
-    // alongside (first kBtRegs * 256 entries through registers, all in flight
-    // with the query and metadata loads) and parked in LDS
-    constexpr int kBtRegs = 8;
-    int bt_regs[kBtRegs];
+    // 1. score my share of the pages; the unit's block-table row is parked in LDS
     KeyLayout kl;
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
-    score_pages_waves<D>(
-        p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, q_group, G, Pmax,
+    scan_finish<D>(
+        scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
         member * kWaves + wave_id(), g * kWaves, reinterpret_cast<unsigned char*>(sl.hist),
-        [&] {
-#pragma unroll
-          for (int k = 0; k < kBtRegs; ++k) {
-            const int j = threadIdx.x + k * kThreads;
-            bt_regs[k] = j < Pmax ? bt_row[j] : -1;
-          }
-        },
         [&] {
 #pragma unroll
           for (int k = 0; k < kBtRegs; ++k) {
@@ -277,7 +297,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           for (int j = threadIdx.x + kBtRegs * kThreads; j < Pmax; j += kThreads)
             bt_lds[j] = bt_row[j];
-          pb_scan = min(pages_of(at.seq_lens[b], p.S), Pmax);
+          // (the empty asm pins the first use of the two values to this point:
+          // using them earlier would put a memory round trip in front of the scan)
+          asm volatile("" : "+v"(L_raw), "+v"(K_raw));
+          pb_scan = uniform(min(pages_of(L_raw, S), Pmax));
           kl = KeyLayout::make(pb_scan);
           return pb_scan;
         },
@@ -292,10 +315,9 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           if (srow_out) srow_out[pg] = s;
         });
-    const int L = uniform(at.seq_lens[b]);
-    const int Pb = uniform(min(pages_of(L, p.S), Pmax));
-    const int K = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
-    const int Kb = uniform(max(0, min(min(K, Pb), at.Kmax)));
+    const int L = uniform(L_raw);
+    const int Pb = uniform(min(pages_of(L, S), Pmax));
+    const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
 
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
@@ -318,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int j = j0 + i * kThreads;
-          v[i] = j < Pb ? load_agent(srow + j) : 0.f;
+          v[i] = load_agent(srow + min(j, Pb - 1));  // no branch around the load
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -372,6 +394,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       }
       __syncthreads();
     }
+    if (!kLoop) break;
     if (dynamic) {
       __syncthreads();
       if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
@@ -381,6 +404,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     } else {
       u += n_clusters;
     }
+    if (u >= p.units) break;
+    issue_unit(u);
   }
   if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();
@@ -696,17 +721,25 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-#define TS_LAUNCH_FUSED(DD, SS)                                                          \
-  do {                                                                                   \
-    if ((st = allow_lds(query_aware_decode_kernel<DD, SS>, pl.lds_fused)) != TS_OK)      \
-      return st;                                                                         \
-    int cap = resident_capacity(query_aware_decode_kernel<DD, SS>, pl.lds_fused);        \
-    if (cap > cus * per_cu) cap = cus * per_cu;                                          \
-    int clusters = cap / pl.g;                                                           \
-    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */          \
-    if (clusters > pl.units) clusters = pl.units;                                        \
-    query_aware_decode_kernel<DD, SS>                                                    \
-        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                 \
+#define TS_LAUNCH_FUSED(DD, SS)                                                              \
+  do {                                                                                       \
+    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true>, pl.lds_fused)) != TS_OK ||  \
+        (st = allow_lds(query_aware_decode_kernel<DD, SS, false>, pl.lds_fused)) != TS_OK)   \
+      return st;                                                                             \
+    int cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false>, pl.lds_fused);    \
+    if (cap1 > cus * per_cu) cap1 = cus * per_cu;                                            \
+    if (pl.units * pl.g <= cap1) { /* one unit per cluster */                                \
+      query_aware_decode_kernel<DD, SS, false>                                               \
+          <<<(unsigned)(pl.units * pl.g), kThreads, pl.lds_fused, s>>>(p);                   \
+      break;                                                                                 \
+    }                                                                                        \
+    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true>, pl.lds_fused);      \
+    if (cap > cus * per_cu) cap = cus * per_cu;                                              \
+    int clusters = cap / pl.g;                                                               \
+    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */              \
+    if (clusters > pl.units) clusters = pl.units;                                            \
+    query_aware_decode_kernel<DD, SS, true>                                                  \
+        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                     \
   } while (0)
   if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16);
   else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32);

@@ -68,20 +68,23 @@ __device__ __forceinline__ void zero_page(PageFrag<D, S>& f) {
   }
 }
 
+// `spread` is 1 for a real page and 0 for a placeholder fetch: with 0 every
+// lane reads the first bytes of the tile, so the instruction touches one cache
+// line instead of the whole tile (the data is never used).
 template <int D, int S>
 __device__ __forceinline__ void load_page(PageFrag<D, S>& f, const uint16_t* ktile,
-                                          const uint16_t* vtile) {
-  const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
+                                          const uint16_t* vtile, int spread) {
+  const int lane = lane_id(), r = (lane & 15) * spread, kb = (lane >> 4) * spread;
 #pragma unroll
   for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
-    const uint16_t* krow = ktile + tile_token<S>(t, r) * D + kb * (D / 4);
+    const uint16_t* krow = ktile + tile_token<S>(t, r) * D * spread + kb * (D / 4);
 #pragma unroll
     for (int i = 0; i < PageFrag<D, S>::KQ; ++i)
-      f.k[t][i] = *reinterpret_cast<const uint4*>(krow + i * 8);
+      f.k[t][i] = *reinterpret_cast<const uint4*>(krow + i * 8 * spread);
   }
 #pragma unroll
   for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) {
-    const uint16_t* vrow = vtile + (16 * cb + r) * S;
+    const uint16_t* vrow = vtile + (16 * cb * spread + r) * S;
     if (S == 16) {
       f.v[0][cb] = *reinterpret_cast<const uint2*>(vrow + 4 * kb);
     } else {
@@ -111,9 +114,9 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
   const int lane = lane_id(), head = lane & 15, kb = lane >> 4;
 #pragma unroll
   for (int i = 0; i < D / 32; ++i) {
-    uint4 w = make_uint4(0, 0, 0, 0);
-    if (head < G)
-      w = *reinterpret_cast<const uint4*>(q_group + (size_t)head * D + kb * (D / 4) + i * 8);
+    // heads past G re-read head G - 1 (no branch around the load) and are zeroed
+    uint4 w = *reinterpret_cast<const uint4*>(q_group + (size_t)min(head, G - 1) * D + kb * (D / 4) + i * 8);
+    if (head >= G) w = make_uint4(0, 0, 0, 0);
     qf[2 * i] = as_short4(w.x, w.y);
     qf[2 * i + 1] = as_short4(w.z, w.w);
   }
@@ -221,35 +224,34 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     constexpr int NBUF = (D * S <= 1024) ? 4 : ((D == 64 && D * S <= 2048) ? 3 : 2);
     PageFrag<D, S> f[NBUF];
     int valid[NBUF];
+    // No branch around the loads (a load under a branch makes the compiler
+    // wait for ALL outstanding loads wherever it needs one of them, so the ring
+    // would drain before the first page is used): a slot past the end of the
+    // list, or one whose page id is out of range, re-reads a page that is
+    // certainly mapped (a single cache line of it) and counts zero valid tokens.
     auto issue = [&](PageFrag<D, S>& fr, int x) -> int {
-      const int j = __builtin_amdgcn_readlane(my_j, x);
-      const int phys = __builtin_amdgcn_readlane(my_phys, x);
-      if (phys < 0 || phys >= p.n_phys) {
-        zero_page(fr);
-        return 0;
-      }
-      const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
-      load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile);
-      return max(0, min(S, L - j * S));
+      const int xc = min(x, n - 1);
+      const int j = __builtin_amdgcn_readlane(my_j, xc);
+      const int phys = __builtin_amdgcn_readlane(my_phys, xc);
+      const bool good = x < n && phys >= 0 && phys < p.n_phys;
+      const size_t tile = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
+      load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile, good ? 1 : 0);
+      return good ? max(0, min(S, L - j * S)) : 0;
     };
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i)
-      if (i < n) valid[i] = issue(f[i], i);
+    for (int i = 0; i < NBUF; ++i) valid[i] = issue(f[i], i);
     TS_MARK(17);
     for (int x0 = 0; x0 < n; x0 += NBUF) {
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
-        const int x = x0 + i;
-        if (x < n) {
-          attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
-          if (x + NBUF < n) valid[i] = issue(f[i], x + NBUF);
-        }
+        if (x0 + i < n) attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
+        valid[i] = issue(f[i], x0 + i + NBUF);
       }
     }
   }
 
-  // merge the wave states
   TS_MARK(18);
+  // merge the wave states
   const float l = rows_sum_f32(acc.l);
   constexpr int RS = D + 2;
   if (head < G) {
@@ -300,11 +302,12 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
       float o[8], m[8], l[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const bool on = s0 + i < p.n_split;
+        const bool on = s0 + i < p.n_split;  // rows past the end re-read row 0, unused
         const float* row = part + ((size_t)(on ? s0 + i : 0) * G + g) * RS;
-        o[i] = on ? load_agent(row + c) : 0.f;
-        m[i] = on ? load_agent(row + D) : -1e30f;
-        l[i] = on ? load_agent(row + D + 1) : 0.f;
+        const float ov = load_agent(row + c), mv = load_agent(row + D), lv = load_agent(row + D + 1);
+        o[i] = on ? ov : 0.f;
+        m[i] = on ? mv : -1e30f;
+        l[i] = on ? lv : 0.f;
       }
       float Mn = M;
 #pragma unroll

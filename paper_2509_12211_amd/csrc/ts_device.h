@@ -162,16 +162,29 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
 
 
 // Phase timestamps for tuning builds (-DTS_PROFILE): thread 0 of every
-// workgroup records the constant-rate 100 MHz clock at numbered points.
+// workgroup records the constant-rate 100 MHz clock at numbered points.  The
+// buffer address is parked in LDS once (TS_MARK_INIT at kernel entry) so that a
+// mark costs an LDS read and a store, and waits for no memory load in flight.
 // Compiled out of the product library.
 #ifdef TS_PROFILE
 __device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][32]
+__device__ __forceinline__ unsigned long long** profile_slot() {
+  __shared__ unsigned long long* slot;
+  return &slot;
+}
+#define TS_MARK_INIT()                                                                  \
+  do {                                                                                  \
+    if (threadIdx.x == 0) *ts::profile_slot() = ts::g_profile_buf;                      \
+  } while (0)
 #define TS_MARK(i)                                                                      \
   do {                                                                                  \
-    if (threadIdx.x == 0 && ts::g_profile_buf)                                          \
-      ts::g_profile_buf[(size_t)blockIdx.x * 32 + (i)] = wall_clock64();                \
+    if (threadIdx.x == 0) {                                                             \
+      unsigned long long* ts_pb = *ts::profile_slot();                                  \
+      if (ts_pb) ts_pb[(size_t)blockIdx.x * 32 + (i)] = wall_clock64();                 \
+    }                                                                                   \
   } while (0)
 #else
+#define TS_MARK_INIT() do { } while (0)
 #define TS_MARK(i) do { } while (0)
 #endif
 

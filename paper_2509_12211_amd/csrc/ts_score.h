@@ -39,13 +39,16 @@ struct ScoreLanes {
 
   struct QueryRegs { uint4 w[kQueryLoads]; };
 
+  // Every thread loads and every thread stages what it loaded (thread i takes
+  // chunk i modulo the number of chunks; duplicates carry identical data): a
+  // load under a branch makes the compiler wait for ALL outstanding loads
+  // wherever it needs one of them, instead of counting, and a load whose only
+  // use sits under a branch is moved down into that branch.
   __device__ __forceinline__ static void issue_query(QueryRegs& r, const uint16_t* q_group, int G) {
     const int n16 = G * D / 8;
 #pragma unroll
-    for (int k = 0; k < kQueryLoads; ++k) {
-      const int i = threadIdx.x + k * kThreads;
-      r.w[k] = i < n16 ? reinterpret_cast<const uint4*>(q_group)[i] : make_uint4(0, 0, 0, 0);
-    }
+    for (int k = 0; k < kQueryLoads; ++k)
+      r.w[k] = reinterpret_cast<const uint4*>(q_group)[(threadIdx.x + k * kThreads) % n16];
   }
 
   // Two barriers.
@@ -55,10 +58,11 @@ struct ScoreLanes {
     const int n16 = G * D / 8;
 #pragma unroll
     for (int k = 0; k < kQueryLoads; ++k) {
-      const int i = threadIdx.x + k * kThreads;
-      if (i < n16) raw[i] = r.w[k];
+      raw[(threadIdx.x + k * kThreads) % n16] = r.w[k];
     }
+    TS_MARK(20);
     __syncthreads();
+    TS_MARK(21);
     if (threadIdx.x < D) {
       const uint16_t* col = reinterpret_cast<const uint16_t*>(stage) + threadIdx.x;
       double p = 0.0, n = 0.0;
@@ -96,20 +100,17 @@ struct MetaTile {
   static constexpr int U = ScoreLanes<D>::U;
   uint4 mn[U], mx[U];
 
+  // Plimit >= 1.  Pages at or past Plimit read row Plimit - 1 instead (no branch
+  // around the loads); reduce() never reports them.
   __device__ __forceinline__ void load(const uint16_t* pmin_u, const uint16_t* pmax_u, int base,
-                                       int Pmax) {
+                                       int Plimit) {
     constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int pg = base + u * PPW + prow;
-      if (pg < Pmax) {
-        mn[u] = *reinterpret_cast<const uint4*>(pmin_u + (size_t)pg * D + cg * 8);
-        mx[u] = *reinterpret_cast<const uint4*>(pmax_u + (size_t)pg * D + cg * 8);
-      } else {
-        mn[u] = make_uint4(0, 0, 0, 0);
-        mx[u] = make_uint4(0, 0, 0, 0);
-      }
+      const int pg = min(base + u * PPW + prow, Plimit - 1);
+      mn[u] = *reinterpret_cast<const uint4*>(pmin_u + (size_t)pg * D + cg * 8);
+      mx[u] = *reinterpret_cast<const uint4*>(pmax_u + (size_t)pg * D + cg * 8);
     }
   }
 
@@ -129,40 +130,68 @@ struct MetaTile {
   }
 };
 
-// Scores the pages of one (sequence, KV head) that fall to this wave: wave
-// iterations it = first_iter, first_iter + iter_stride, ... each cover
-// ScoreLanes<D>::PPI consecutive pages.  Loads go out in the order their data
-// is needed: the query rows, then whatever `issue_extra` loads, then the first
-// metadata tile; only then is anything waited for.  `after_query` runs once the
-// query is in registers (it consumes the extra loads and returns Pb).  Must be
+// Scoring one (sequence, KV head) is split in two so that a kernel can put the
+// first loads of a unit as early as it likes (before unrelated set-up work):
+// scan_issue sends out the query rows and the wave's first metadata tile,
+// scan_finish does everything else.  A wave's iterations are it = first_iter,
+// first_iter + iter_stride, ..., each covering ScoreLanes<D>::PPI consecutive
+// pages.
+template <int D>
+struct ScanRegs {
+  typename ScoreLanes<D>::QueryRegs q;
+  MetaTile<D> tile;
+};
+
+template <int D>
+__device__ __forceinline__ void scan_issue_query(ScanRegs<D>& r, const uint16_t* q_group, int G) {
+  ScoreLanes<D>::issue_query(r.q, q_group, G);
+}
+template <int D>
+__device__ __forceinline__ void scan_issue_tile(ScanRegs<D>& r, const uint16_t* pmin_u,
+                                                const uint16_t* pmax_u, int Pmax, int first_iter) {
+  r.tile.load(pmin_u, pmax_u, first_iter * ScoreLanes<D>::PPI, Pmax);
+}
+
+// `after_query` runs once the query is in registers and returns Pb.  Must be
 // called by the whole workgroup (the query goes through LDS, q_stage, with
 // barriers).
+template <int D, typename AfterQuery, typename Sink>
+__device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin_u,
+                                            const uint16_t* pmax_u, int G, int Pmax, int first_iter,
+                                            int iter_stride, unsigned char* q_stage,
+                                            AfterQuery after_query, Sink sink) {
+  constexpr int PPI = ScoreLanes<D>::PPI;
+  TS_MARK(19);
+  ScoreLanes<D> ql;
+  ql.finish_query(r.q, G, q_stage);
+  TS_MARK(16);
+  const int Pb = after_query();
+  // only the first tile is fetched blind; later ones stop at the sequence's
+  // last page (pages >= Pb still get their -inf through the sink)
+  int base = first_iter * PPI;
+  while (base < Pmax) {
+    const int next = base + iter_stride * PPI;
+    MetaTile<D> cur = r.tile;
+    r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
+    cur.reduce(ql, base, Pb, Pmax, sink);
+    base = next;
+  }
+}
+
+// Both halves back to back.  Loads go out in the order their data is needed:
+// the query rows, then whatever `issue_extra` loads, then the first metadata
+// tile; only then is anything waited for.
 template <int D, typename IssueExtra, typename AfterQuery, typename Sink>
 __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const uint16_t* pmax_u,
                                                   const uint16_t* q_group, int G, int Pmax,
                                                   int first_iter, int iter_stride,
                                                   unsigned char* q_stage, IssueExtra issue_extra,
                                                   AfterQuery after_query, Sink sink) {
-  constexpr int PPI = ScoreLanes<D>::PPI;
-  typename ScoreLanes<D>::QueryRegs qr;
-  ScoreLanes<D>::issue_query(qr, q_group, G);
+  ScanRegs<D> r;
+  scan_issue_query<D>(r, q_group, G);
   issue_extra();
-  MetaTile<D> tile;
-  int base = first_iter * PPI;
-  if (base < Pmax) tile.load(pmin_u, pmax_u, base, Pmax);
-  ScoreLanes<D> ql;
-  ql.finish_query(qr, G, q_stage);
-  TS_MARK(16);
-  const int Pb = after_query();
-  // only the first tile is fetched blind; later ones stop at the sequence's
-  // last page (pages >= Pb still get their -inf through the sink)
-  while (base < Pmax) {
-    const int next = base + iter_stride * PPI;
-    MetaTile<D> cur = tile;
-    if (next < Pb) tile.load(pmin_u, pmax_u, next, Pb);
-    cur.reduce(ql, base, Pb, Pmax, sink);
-    base = next;
-  }
+  scan_issue_tile<D>(r, pmin_u, pmax_u, Pmax, first_iter);
+  scan_finish<D>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query, sink);
 }
 
 }  // namespace ts
