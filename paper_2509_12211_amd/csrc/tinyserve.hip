@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   const int c0 = min(split * p.chunk, Kb), count = min(c0 + p.chunk, Kb) - c0;
   const int32_t* sel_row = sel + (size_t)u * p.Kmax + c0;
   const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
-  attend_split<D, S>(
+  attend_split<D, S, true>(
       p, b, h, split, count, p.seq_lens[b], [&](int i) { return sel_row[i]; },
       [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
   if (p.n_split == 1) return;
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     KeyLayout kl;
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
-    scan_finish<D>(
+    scan_finish<D, !kLoop>(
         scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
         member * kWaves + wave_id(), g * kWaves, reinterpret_cast<unsigned char*>(sl.hist),
         [&] {
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     TS_MARK(5);
 
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
-    attend_split<D, S>(
+    attend_split<D, S, !kLoop>(
         at, b, h, member, count, L, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
     TS_MARK(6);

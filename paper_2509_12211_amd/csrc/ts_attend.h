@@ -195,7 +195,10 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
 // handed to the combining workgroup through agent-scope stores.
 // Ends with a barrier after which `lds` may be reused; on return (n_split > 1)
 // the caller still has to wait for its stores and count its arrival.
-template <int D, int S, typename SelAt, typename PhysAt>
+// kBranchless: the ring is refilled without a branch around the loads (see
+// below); with false the refill past the end of the list is skipped instead,
+// which suits bandwidth-bound launches with thousands of units.
+template <int D, int S, bool kBranchless, typename SelAt, typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, SelAt sel_at, PhysAt phys_at,
                                              float* lds) {
@@ -245,7 +248,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
         if (x0 + i < n) attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
-        valid[i] = issue(f[i], x0 + i + NBUF);
+        if (kBranchless || x0 + i + NBUF < n) valid[i] = issue(f[i], x0 + i + NBUF);
       }
     }
   }

@@ -155,7 +155,14 @@ __device__ __forceinline__ void scan_issue_tile(ScanRegs<D>& r, const uint16_t* 
 // `after_query` runs once the query is in registers and returns Pb.  Must be
 // called by the whole workgroup (the query goes through LDS, q_stage, with
 // barriers).
-template <int D, typename AfterQuery, typename Sink>
+//
+// kBranchless: the next tile is fetched without a branch around the loads even
+// when there is none (the clamped loads then cost a cache line or two), so the
+// compiler can count outstanding loads and overlap the fetch with the reduction
+// of the current tile.  That is what a latency-bound launch wants; a launch with
+// thousands of units is bound by bandwidth and overlaps across workgroups, and
+// there the plain branch is a little cheaper.
+template <int D, bool kBranchless, typename AfterQuery, typename Sink>
 __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin_u,
                                             const uint16_t* pmax_u, int G, int Pmax, int first_iter,
                                             int iter_stride, unsigned char* q_stage,
@@ -172,7 +179,8 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin
   while (base < Pmax) {
     const int next = base + iter_stride * PPI;
     MetaTile<D> cur = r.tile;
-    r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
+    if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
+    else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb);
     cur.reduce(ql, base, Pb, Pmax, sink);
     base = next;
   }
@@ -191,7 +199,8 @@ __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const 
   scan_issue_query<D>(r, q_group, G);
   issue_extra();
   scan_issue_tile<D>(r, pmin_u, pmax_u, Pmax, first_iter);
-  scan_finish<D>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query, sink);
+  scan_finish<D, true>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query,
+                       sink);
 }
 
 }  // namespace ts
