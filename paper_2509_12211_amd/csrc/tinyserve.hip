@@ -25,28 +25,27 @@ constexpr int kCtrlWords = 64;   // control words at the head of the workspace
 constexpr int kCtrlTicket = 0;   // next unit (fused kernel, g == 1, more units than workgroups)
 constexpr int kCtrlExit = 1;     // workgroups that have finished taking tickets
 constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
+constexpr int kCtrlEpoch = 16;   // launches of the fused kernel with clusters so far (own 64-byte line)
+constexpr int kCtrlArrive = 32;  // workgroups of the current launch that have read the epoch (own line)
 constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
 constexpr int kTargetWorkgroups = 256;
 constexpr int kMaxCluster = 64;
-// Per-unit counters are polled and bumped by every member of a cluster at once.
-// Each gets a 256-byte slot of its own while that fits the zeroed head of the
-// workspace: sixteen units' counters packed into one 64-byte line made every
-// workgroup of the launch hammer the same line (measured: 6 us of waiting with
-// 16 x 16 workgroups).  Only clusters (g > 1, at most a few hundred units) use
-// the counters, so large batches keep them packed.
+// Per-unit counters are bumped by every member of a cluster at about the same
+// time.  Each gets a 256-byte slot of its own while the batch is small: sixteen
+// units' counters packed into one 64-byte line made every workgroup of the
+// launch hammer the same line (measured: 6 us of waiting with 16 x 16
+// workgroups).  Only clusters (g > 1, at most a few hundred units) use the
+// counters, so large batches keep them packed.
 constexpr int kCounterPadUnits = 512;
 constexpr int kCounterPadStride = 64;   // int32 words
-constexpr size_t kZeroedWords = kCtrlWords + 2 * 65536;
-static_assert(kCtrlWords + 2 * (size_t)kCounterPadUnits * kCounterPadStride <= kZeroedWords,
-              "padded counters must lie inside the zeroed head of the workspace");
 
 struct Plan {
   int units;          // B * Hkv
   int g;              // workgroups per unit (= attention splits = score slices)
   int chunk;          // selected pages per workgroup
-  size_t off_unit;    // int32 [2][units * cstride]: scan_done, attend_done
+  size_t off_unit;    // int32 [2][units * cstride]: arrival counters of the fused / the staged attention
   int cstride;        // words between the counters of consecutive units
-  size_t off_scores;  // fp32 [units][Pmax]
+  size_t off_scores;  // {fp32 score, uint32 launch tag} [units][Pmax]
   size_t off_part;    // fp32 [units][g][G][d+2]
   size_t total;
   size_t lds_fused;   // dynamic LDS of the fused kernel
@@ -75,7 +74,7 @@ static Plan make_plan(const ts_layout* L, int max_topk) {
   pl.cstride = pl.units <= kCounterPadUnits ? kCounterPadStride : 1;
   off = align_up(off + 2 * (size_t)pl.units * pl.cstride * sizeof(int32_t), 256);
   pl.off_scores = off;
-  off = align_up(off + (size_t)pl.units * Pmax * sizeof(float), 256);
+  off = align_up(off + (size_t)pl.units * Pmax * sizeof(uint64_t), 256);
   pl.off_part = off;
   off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(float), 256);
   pl.total = off;
@@ -91,13 +90,12 @@ struct FusedParams {
   AttendParams at;
   const uint16_t* page_min;
   const uint16_t* page_max;
-  float* scores;        // [units][Pmax] exchange buffer (workspace)
+  uint64_t* scores;     // [units][Pmax] exchange buffer (workspace): score | launch tag << 32
   float* scores_out;    // nullable, caller's
   int32_t* sel_out;     // nullable [units][Kmax]
   int32_t* sel_count;   // nullable [B]
   const int32_t* topk_per_seq;
   int32_t* ctrl;        // control words
-  int32_t* scan_done;   // [units * cstride]
   int32_t* attend_done; // [units * cstride]
   int topk, S, units, g, cstride;
 };
@@ -160,9 +158,10 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
       }
     }
   }
+  select_begin(L, tmin, tmax);
   __syncthreads();
   TS_MARK(1);
-  select_topk_lds(L, kl, Pb, Kb, tmin, tmax, [&](int rank, int page) { row[rank] = page; });
+  select_topk_lds(L, kl, Pb, Kb, [&](int rank, int page) { row[rank] = page; });
   TS_MARK(5);
 }
 
@@ -258,10 +257,11 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   // unit right here, before the set-up work that follows, for later units at the
   // end of the unit before.  What they fetch is only looked at inside the loop.
   constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
-  int L_raw, K_raw, bt_regs[kBtRegs];
+  int L_raw, K_raw, epoch_raw, bt_regs[kBtRegs];
   ScanRegs<D> scan;
   auto issue_unit = [&](int uu) {
     const int b = uu / at.Hkv, h = uu % at.Hkv;
+    epoch_raw = p.ctrl[kCtrlEpoch];
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
     scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
@@ -275,11 +275,17 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
   TS_MARK(23);
 
+  // Launch tag of the score exchange.  The epoch word is read by every
+  // workgroup before it counts itself in; the workgroup that counts in last
+  // (every other one has read the word by then) advances it for the next launch
+  // on its way out.
+  uint32_t tag = 0;
+  int arrived = -1;
   while (kLoop ? u < p.units : true) {
     TS_MARK(0);
     const int b = u / at.Hkv, h = u % at.Hkv;
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
-    float* srow = p.scores + (size_t)u * Pmax;
+    uint64_t* srow = p.scores + (size_t)u * Pmax;
     float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
 
     // 1. score my share of the pages; the unit's block-table row is parked in LDS
@@ -299,14 +305,15 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
             bt_lds[j] = bt_row[j];
           // (the empty asm pins the first use of the two values to this point:
           // using them earlier would put a memory round trip in front of the scan)
-          asm volatile("" : "+v"(L_raw), "+v"(K_raw));
+          asm volatile("" : "+v"(L_raw), "+v"(K_raw), "+v"(epoch_raw));
+          tag = (uint32_t)uniform(epoch_raw) + 1u;
           pb_scan = uniform(min(pages_of(L_raw, S), Pmax));
           kl = KeyLayout::make(pb_scan);
           return pb_scan;
         },
         [&](int pg, float s) {
           if (exchange) {
-            store_agent(srow + pg, s);
+            store_agent_tagged(srow + pg, s, tag);
           } else if (pg < pb_scan) {
             const uint32_t k = score_key(s);
             sl.keys[kl.at(pg)] = k;
@@ -322,38 +329,39 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
     if (exchange) {
-      stores_complete();
-      __syncthreads();
-      TS_MARK(2);
-      if (threadIdx.x == 0) {
-        atomic_add_agent(&p.scan_done[u * p.cstride], 1);
-        const int ok = wait_at_least(&p.scan_done[u * p.cstride], g, kSpinLimit);
-        if (!ok) atomic_store_agent(&p.ctrl[kCtrlError], 1);
-        s_flag = ok;
-      }
-      __syncthreads();
-      TS_MARK(3);
-      // all loads of a round in flight together (a plain loop would pay one
-      // memory round trip per iteration)
+      if (arrived < 0 && threadIdx.x == 0) arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
+      // every thread polls its own entries of the row until all carry this
+      // launch's tag (all loads of a round in flight together; bounded)
+      bool expired = false;
+      int spins = 0;
       for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
-        float v[8];
+        uint64_t v[8];
+        for (;;) {
+          bool all = true;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int j = j0 + i * kThreads;
-          v[i] = load_agent(srow + min(j, Pb - 1));  // no branch around the load
+          for (int i = 0; i < 8; ++i) {
+            v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
+            all = all && (uint32_t)(v[i] >> 32) == tag;
+          }
+          if (all) break;
+          if (++spins > kSpinLimit) { expired = true; break; }
+          __builtin_amdgcn_s_sleep(1);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int j = j0 + i * kThreads;
           if (j < Pb) {
-            const uint32_t k = score_key(v[i]);
+            const uint32_t k = score_key(__uint_as_float((uint32_t)v[i]));
             sl.keys[kl.at(j)] = k;
             tmin = min(tmin, k);
             tmax = max(tmax, k);
           }
         }
       }
+      if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
+      TS_MARK(3);
     }
+    select_begin(sl, tmin, tmax);
     __syncthreads();
     TS_MARK(4);
 
@@ -363,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (sel_row)
       for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
     if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
-    select_topk_lds(sl, kl, Pb, Kb, tmin, tmax, [&](int rank, int page) {
+    select_topk_lds(sl, kl, Pb, Kb, [&](int rank, int page) {
       if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
       if (sel_row) sel_row[rank] = page;
     });
@@ -389,7 +397,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       __syncthreads();
       TS_MARK(9);
       if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
-        atomic_store_agent(&p.scan_done[u * p.cstride], 0);
         atomic_store_agent(&p.attend_done[u * p.cstride], 0);
       }
       __syncthreads();
@@ -407,6 +414,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (u >= p.units) break;
     issue_unit(u);
   }
+  if (exchange && threadIdx.x == 0 && arrived == (int)gridDim.x - 1) {
+    atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
+    atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+  }
   if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();
     if (threadIdx.x == 0 && atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
@@ -417,8 +428,9 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 }
 
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -562,12 +574,12 @@ size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk) {
 int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return TS_ERR_NULL;
   if (workspace_bytes < kCtrlWords * sizeof(int32_t)) return TS_ERR_WORKSPACE;
-  // control words + per-unit counters live at the head; zeroing the first
-  // ~0.5 MiB covers them for every supported unit count (<= 65535 packed,
-  // <= kCounterPadUnits padded)
-  size_t n = workspace_bytes / sizeof(int32_t);
-  if (n > kZeroedWords) n = kZeroedWords;
-  fill_zero_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+  // Everything is zeroed: the control words and counters must start at zero,
+  // and no word of the exchange areas may carry a launch tag from an earlier
+  // life of the memory (tags start at 1 and only grow).
+  const size_t n = workspace_bytes / sizeof(int32_t);
+  const unsigned blocks = (unsigned)((n + 256 * 64 - 1) / (256 * 64));
+  fill_zero_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
       static_cast<int32_t*>(workspace), n);
   return launch_status();
 }
@@ -705,14 +717,13 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
   p.at = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
   p.page_min = static_cast<const uint16_t*>(layout->page_min);
   p.page_max = static_cast<const uint16_t*>(layout->page_max);
-  p.scores = reinterpret_cast<float*>(ws + pl.off_scores);
+  p.scores = reinterpret_cast<uint64_t*>(ws + pl.off_scores);
   p.scores_out = scores_out;
   p.sel_out = sel_out;
   p.sel_count = sel_count_out;
   p.topk_per_seq = topk_per_seq;
   p.ctrl = reinterpret_cast<int32_t*>(ws);
-  p.scan_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
-  p.attend_done = p.scan_done + (size_t)pl.units * pl.cstride;
+  p.attend_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
   p.cstride = pl.cstride;
   p.topk = topk;
   p.S = layout->page_size;

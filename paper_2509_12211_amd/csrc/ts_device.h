@@ -148,6 +148,17 @@ __device__ __forceinline__ float load_agent(const float* p) {
   return __int_as_float(__hip_atomic_load(reinterpret_cast<const int*>(p), __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_AGENT));
 }
+// A value handed over together with the tag that says which launch wrote it:
+// one aligned 8-byte store, so a reader sees both or neither.  The reader polls
+// the word itself until the tag is the current one; no counter, no wait for
+// the store's acknowledgement, one trip through the memory system in all.
+__device__ __forceinline__ void store_agent_tagged(uint64_t* p, float v, uint32_t tag) {
+  __hip_atomic_store(p, ((uint64_t)tag << 32) | (uint64_t)__float_as_uint(v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_agent_u64(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 // All of this wave's outstanding memory operations have been acknowledged.
 __device__ __forceinline__ void stores_complete() { __builtin_amdgcn_s_waitcnt(0); }
 
@@ -176,9 +187,12 @@ __device__ __forceinline__ unsigned long long** profile_slot() {
   do {                                                                                  \
     if (threadIdx.x == 0) *ts::profile_slot() = ts::g_profile_buf;                      \
   } while (0)
+#ifndef TS_PROFILE_MASK
+#define TS_PROFILE_MASK 0xffffffffu   // which of the numbered marks are compiled in
+#endif
 #define TS_MARK(i)                                                                      \
   do {                                                                                  \
-    if (threadIdx.x == 0) {                                                             \
+    if (((TS_PROFILE_MASK >> (i)) & 1u) && threadIdx.x == 0) {                          \
       unsigned long long* ts_pb = *ts::profile_slot();                                  \
       if (ts_pb) ts_pb[(size_t)blockIdx.x * 32 + (i)] = wall_clock64();                 \
     }                                                                                   \

@@ -50,49 +50,71 @@ struct KeyLayout {
 
 struct SelectLds {
   uint32_t* keys;  // [select_key_words(Pmax)]  filled by the caller through KeyLayout::at
-  uint32_t* hist;  // [kRadixBins]
-  int* red;        // [64]   [0..7] wave sums, [8..10] cut, [16..31] / [32..47] key ranges
+  uint32_t* hist;  // [kRadixBins]  bin counts, see bin_slot_index
+  int* red;        // [64]   [0..7] wave sums, [16..31] key range of the waves, [40] candidate count
+  uint32_t* cand;  // [2 * kMaxCandidates]  (key, page) of the pages in the cut-off bin
 };
+constexpr int kMaxCandidates = 32;
 constexpr size_t select_key_words(int Pmax) {
   // kThreads chunks of (C | 1) words, C = ceil(Pmax / kThreads), padded to 16 bytes
   return (size_t)((kThreads * ((((Pmax + kThreads - 1) / kThreads)) | 1) + 3) / 4 * 4);
 }
 constexpr size_t select_lds_bytes(int Pmax) {
-  return select_key_words(Pmax) * 4 + kRadixBins * 4 + 64 * 4;
+  return select_key_words(Pmax) * 4 + kRadixBins * 4 + 64 * 4 + 2 * kMaxCandidates * 4;
 }
 __device__ __forceinline__ SelectLds carve_select(unsigned char* smem, int Pmax) {
   SelectLds L;
   L.keys = reinterpret_cast<uint32_t*>(smem);
   L.hist = L.keys + select_key_words(Pmax);
   L.red = reinterpret_cast<int*>(L.hist + kRadixBins);
+  L.cand = reinterpret_cast<uint32_t*>(L.red + 64);
   return L;
 }
 
-// Keeps the Kb largest of the Pb keys in L.keys (ties: lower page first) and
-// calls emit(rank, page) for every kept page, rank = its position in ascending
-// page order.  tmin / tmax: this thread's share of the min / max over ALL keys
-// (any partition over the threads; 0xffffffff / 0 if it saw none).  All
-// kThreads threads must call; Pb, Kb workgroup-uniform; the keys must be
-// visible (barrier) before the call.
+// Bins are counted top bin first: slot k holds bin kRadixBins - 1 - k, so a scan
+// in slot order accumulates from the highest scores down.  Lane l of a wave
+// scans slots 32 l .. 32 l + 31; they are laid out so that the lanes' 16-byte
+// reads of a round fall on consecutive addresses.
+__device__ __forceinline__ int bin_slot_index(int k) {
+  const int l = k >> 5, j = k & 31;
+  return (j >> 2) * 256 + l * 4 + (j & 3);
+}
+static_assert(kRadixBins == 64 * 32, "slot layout written for 64 lanes x 32 slots");
+
+// First half of the selection, to be called by all threads BEFORE the barrier
+// that makes the keys visible: clears the bins and deposits each wave's share
+// of the key range.  tmin / tmax: this thread's share of the min / max over ALL
+// keys (any partition over the threads; 0xffffffff / 0 if it saw none).
+__device__ __forceinline__ void select_begin(const SelectLds& L, uint32_t tmin, uint32_t tmax) {
+  reinterpret_cast<uint4*>(L.hist)[threadIdx.x] = make_uint4(0, 0, 0, 0);
+  static_assert(kRadixBins == 4 * kThreads, "one 16-byte store per thread clears the bins");
+  const uint32_t a = wave_min_u32(tmin), b = wave_max_u32(tmax);
+  if (lane_id() == 0) {
+    L.red[16 + wave_id()] = (int)a;
+    L.red[24 + wave_id()] = (int)b;
+    if (wave_id() == 0) L.red[40] = 0;
+  }
+}
+
+// Second half: keeps the Kb largest of the Pb keys in L.keys (ties: lower page
+// first) and calls emit(rank, page) for every kept page, rank = its position in
+// ascending page order.  All kThreads threads must call; Pb, Kb
+// workgroup-uniform; select_begin and a barrier must precede the call.
 //
 // Stage 1 spreads the pages over the 2048 bins LINEARLY in score,
 // bin = floor((s - s_min) * 2047 / (s_max - s_min)): a monotone map, so bins
 // respect the order of the keys, and one that spreads the scores of a unit
 // evenly whatever their sign or exponent range (the raw float bit patterns
 // would put a whole binade, or everything on one side of zero, into a handful
-// of bins).  If the cut-off bin has to be split, stage 2 runs exact radix
-// passes on the integer keys of that bin's pages only, normalised by their own
-// minimum.
-//
-// hist is stored top bin first (slot k holds bin 2047 - k), so that a thread
-// reads its consecutive bins with 16-byte LDS loads and a scan in thread
-// order accumulates from the top bin down.
+// of bins).  Every wave then finds the cut-off bin for itself (no exchange
+// between waves, no barrier).  If that bin has to be split, its few pages are
+// listed in LDS and every wave ranks them directly; only a cut-off bin with
+// more than kMaxCandidates pages (heavy ties) goes through exact radix passes
+// on the integer keys instead.
 template <typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLayout& kl, int Pb,
-                                                int Kb, uint32_t tmin, uint32_t tmax, Emit emit) {
+                                                int Kb, Emit emit) {
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
-  constexpr int BPT = kRadixBins / kThreads;  // bins per thread
-  static_assert(BPT == 4 || BPT == 8, "bin scan written for 4 or 8 bins per thread");
   static_assert(kWaves <= 8, "red[] layout holds 8 wave slots");
   constexpr int kBatch = 8;  // LDS reads issued together
   Pb = uniform(Pb);
@@ -108,19 +130,18 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const uint32_t* my_keys = L.keys + tid * kl.stride;
 
   auto clear_bins = [&] {
-#pragma unroll
-    for (int i = 0; i < BPT / 4; ++i)
-      reinterpret_cast<uint4*>(L.hist)[tid * (BPT / 4) + i] = make_uint4(0, 0, 0, 0);
+    reinterpret_cast<uint4*>(L.hist)[tid] = make_uint4(0, 0, 0, 0);
   };
   // Block-wide min / max from per-thread partials; one barrier.
-  auto block_range = [&](uint32_t& lo, uint32_t& hi, int slot) {
+  auto block_range = [&](uint32_t& lo, uint32_t& hi) {
     uint32_t a = wave_min_u32(lo), b = wave_max_u32(hi);
-    if (lane == 0) { L.red[slot + wave] = (int)a; L.red[slot + kWaves + wave] = (int)b; }
+    __syncthreads();  // earlier readers of the slots are done
+    if (lane == 0) { L.red[16 + wave] = (int)a; L.red[24 + wave] = (int)b; }
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      a = min(a, (uint32_t)L.red[slot + w]);
-      b = max(b, (uint32_t)L.red[slot + kWaves + w]);
+      a = min(a, (uint32_t)L.red[16 + w]);
+      b = max(b, (uint32_t)L.red[24 + w]);
     }
     lo = (uint32_t)uniform((int)a);
     hi = (uint32_t)uniform((int)b);
@@ -136,129 +157,146 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
         if (i0 + i < my_n) fn(k[i], i0 + i);
     }
   };
-  // Top-down scan of the bins: finds the bin in which the `need`-th largest
-  // counted key falls.  Two barriers.  Returns bin, keys above it, keys in it.
-  auto find_cut = [&](int need, int& bin, int& above, int& cnt) {
-    int c[BPT];
-#pragma unroll
-    for (int i = 0; i < BPT / 4; ++i) {
-      const uint4 h = reinterpret_cast<const uint4*>(L.hist)[tid * (BPT / 4) + i];
-      c[4 * i] = (int)h.x; c[4 * i + 1] = (int)h.y; c[4 * i + 2] = (int)h.z; c[4 * i + 3] = (int)h.w;
-    }
+  // Top-down scan of the bins by ONE wave (every wave does it for itself): the
+  // slot in which the `need`-th largest counted key falls, the keys above it,
+  // the keys in it.  The counts must be visible (barrier) before the call.
+  auto find_cut = [&](int need, int& slot, int& above, int& cnt) {
     int tot = 0;
 #pragma unroll
-    for (int i = 0; i < BPT; ++i) tot += c[i];
-    int incl = wave_inclusive_sum(tot);
-    if (lane == kWave - 1) L.red[wave] = incl;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const int t = uniform(L.red[w]);
-      if (w < wave) incl += t;
+    for (int r = 0; r < 8; ++r) {
+      const uint4 h = reinterpret_cast<const uint4*>(L.hist)[r * 64 + lane];
+      tot += (int)(h.x + h.y + h.z + h.w);
     }
-    int run = incl - tot;
-    if (run < need && need <= incl) {  // exactly one thread: the cut-off bin is one of its own
-#pragma unroll
-      for (int i = 0; i < BPT; ++i) {
-        if (run < need && need <= run + c[i]) {
-          L.red[8] = kRadixBins - 1 - (tid * BPT + i);
-          L.red[9] = run;
-          L.red[10] = c[i];
-        }
-        run += c[i];
-      }
-    }
-    __syncthreads();
-    bin = uniform(L.red[8]);
-    above = uniform(L.red[9]);
-    cnt = uniform(L.red[10]);
+    const int incl = wave_inclusive_sum(tot), excl = incl - tot;
+    const uint64_t m = __ballot(excl < need && need <= incl);
+    const int cl = m ? __builtin_ctzll(m) : kWave - 1;  // lane holding the cut-off slot
+    const int base = __builtin_amdgcn_readlane(excl, cl);
+    // second level: the 32 slots of that lane, one per lane
+    const int v = lane < 32 ? (int)L.hist[bin_slot_index(32 * cl + lane)] : 0;
+    const int incl2 = wave_inclusive_sum(v), excl2 = incl2 - v;
+    const uint64_t m2 = __ballot(lane < 32 && base + excl2 < need && need <= base + incl2);
+    const int j = m2 ? __builtin_ctzll(m2) : 31;
+    slot = 32 * cl + j;
+    above = base + __builtin_amdgcn_readlane(excl2, j);
+    cnt = __builtin_amdgcn_readlane(v, j);
   };
 
   // ---- stage 1: linear bins over [s_min, s_max] ------------------------------
-  uint32_t kmin = tmin, kmax = tmax;
-  clear_bins();
-  block_range(kmin, kmax, 16);
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    kmin = min(kmin, (uint32_t)L.red[16 + w]);
+    kmax = max(kmax, (uint32_t)L.red[24 + w]);
+  }
+  kmin = (uint32_t)uniform((int)kmin);
+  kmax = (uint32_t)uniform((int)kmax);
   TS_MARK(10);
   const float smin = key_score(kmin);
   const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
-  auto linear_bin = [&](uint32_t k) {
-    return (int)fminf((key_score(k) - smin) * scale, 2047.0f);
+  auto linear_slot = [&](uint32_t k) {   // 0 = highest scores
+    return kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
   };
-  int need = Kb, cut_bin = 0;
-  bool by_bin = false;        // true: the cut-off bin is kept whole
-  uint32_t clo = kmin, chi = kmax, base = 0u;
+  int need = Kb, cut_slot = 0;
+  // how the pages at the cut are told apart from those above it
+  enum { kWholeSlot, kThreshold, kRadix } mode = kWholeSlot;
+  uint32_t key_t = 0u;        // kThreshold: kept iff (key, -page) >= (key_t, -page_t)
+  int page_t = 0;
+  uint32_t clo = kmin, chi = kmax, base = 0u;  // kRadix
   int bits = 0;
   if (kmax > kmin) {
-    for_my_keys([&](uint32_t k, int) { atomicAdd(&L.hist[kRadixBins - 1 - linear_bin(k)], 1u); });
+    for_my_keys([&](uint32_t k, int) { atomicAdd(&L.hist[bin_slot_index(linear_slot(k))], 1u); });
     __syncthreads();
     TS_MARK(11);
     int above, cnt;
-    find_cut(need, cut_bin, above, cnt);
+    find_cut(need, cut_slot, above, cnt);
     TS_MARK(12);
     need -= above;
-    by_bin = cnt == need;
-    if (!by_bin) {
-      // ---- stage 2: exact radix passes on the keys of the cut-off bin ------------
+    if (cnt == need) {
+      mode = kWholeSlot;
+    } else if (cnt <= kMaxCandidates) {
+      // ---- stage 2a: list the cut-off bin's pages, every wave ranks them -------
+      mode = kThreshold;
+      for_my_keys([&](uint32_t k, int i) {
+        if (linear_slot(k) == cut_slot) {
+          const int at = atomicAdd(&L.red[40], 1);
+          L.cand[2 * at] = k;
+          L.cand[2 * at + 1] = (uint32_t)(my_first + i);
+        }
+      });
+      __syncthreads();
+      const uint32_t ck = lane < cnt ? L.cand[2 * lane] : 0u;
+      const int cp = lane < cnt ? (int)L.cand[2 * lane + 1] : 0x7fffffff;
+      int rank = 0;  // candidates that come before mine (higher key, or equal key and lower page)
+      for (int t = 0; t < cnt; ++t) {
+        const uint32_t ok = (uint32_t)__builtin_amdgcn_readlane((int)ck, t);
+        const int op = __builtin_amdgcn_readlane(cp, t);
+        rank += (ok > ck || (ok == ck && op < cp)) ? 1 : 0;
+      }
+      const uint64_t mt = __ballot(lane < cnt && rank == need - 1);
+      const int tl = mt ? __builtin_ctzll(mt) : 0;
+      key_t = (uint32_t)__builtin_amdgcn_readlane((int)ck, tl);
+      page_t = __builtin_amdgcn_readlane(cp, tl);
+    } else {
+      // ---- stage 2b: exact radix passes on the keys of the cut-off bin ----------
+      mode = kRadix;
+      __syncthreads();  // every wave has read the stage-1 counts
       clear_bins();
       clo = 0xffffffffu;
       chi = 0u;
       for_my_keys([&](uint32_t k, int) {
-        if (linear_bin(k) == cut_bin) { clo = min(clo, k); chi = max(chi, k); }
+        if (linear_slot(k) == cut_slot) { clo = min(clo, k); chi = max(chi, k); }
       });
-      block_range(clo, chi, 32);
+      block_range(clo, chi);
       bits = 32 - __clz((int)(chi - clo));  // 0: all of the bin's keys are equal
       while (bits > 0) {
         const int s = max(bits - kRadixBits, 0);
         for_my_keys([&](uint32_t k, int) {
           const uint32_t nk = k - clo, d = nk - base;
           if (k >= clo && k <= chi && nk >= base && (bits >= 32 || (d >> bits) == 0u))
-            atomicAdd(&L.hist[kRadixBins - 1 - (d >> s)], 1u);
+            atomicAdd(&L.hist[bin_slot_index(kRadixBins - 1 - (int)(d >> s))], 1u);
         });
         __syncthreads();
-        int bsel, above2, cnt2;
-        find_cut(need, bsel, above2, cnt2);
-        base += (uint32_t)bsel << s;
+        int ssel, above2, cnt2;
+        find_cut(need, ssel, above2, cnt2);
+        base += (uint32_t)(kRadixBins - 1 - ssel) << s;
         need -= above2;
         bits = s;
         if (cnt2 == need || bits == 0) break;
+        __syncthreads();  // every wave has read the counts
         clear_bins();
         __syncthreads();
       }
     }
   }
   TS_MARK(13);
-  // Kept: everything above the cut, plus the first `need` (in page order) of
-  // the pages at the cut (by_bin: the whole cut-off bin, and need == its size;
-  // otherwise keys k with k - clo in [base, base + 2^bits), one exact value
-  // when bits == 0).
-  auto classify = [&](uint32_t k, bool& g, bool& e) {
-    if (by_bin) {
-      const int b = linear_bin(k);
-      g = b > cut_bin;
-      e = b == cut_bin;
-    } else {
-      const uint32_t nk = k - clo, d = nk - base;
-      const bool inside = bits >= 32 || (d >> bits) == 0u;
-      const bool in = k >= clo && k <= chi && nk >= base;
-      g = k > chi || (in && !inside);
-      e = in && inside;
-    }
+  // Kept for certain (g) / kept while the quota `need` lasts, in page order (e):
+  //   kWholeSlot  g: slot at or above the cut-off slot (need == its size)
+  //   kThreshold  g: (key, page) at or before the threshold in the order above
+  //   kRadix      g: above the cut;  e: keys k with k - clo in [base, base + 2^bits),
+  //               one exact value when bits == 0
+  // (all keys equal: kRadix with bits == 0, every page is e)
+  if (!(kmax > kmin)) mode = kRadix;
+  auto classify = [&](uint32_t k, int page) -> int {   // bit 0: g, bit 1: e
+    if (mode == kWholeSlot) return linear_slot(k) <= cut_slot ? 1 : 0;
+    if (mode == kThreshold) return (k > key_t || (k == key_t && page <= page_t)) ? 1 : 0;
+    const uint32_t nk = k - clo, d = nk - base;
+    const bool inside = bits >= 32 || (d >> bits) == 0u;
+    const bool in = k >= clo && k <= chi && nk >= base;
+    return ((k > chi || (in && !inside)) ? 1 : 0) | ((in && inside) ? 2 : 0);
   };
   // Ordered compaction in one pass: every thread classifies its own chunk of
   // consecutive pages (bit masks in registers), a workgroup scan of the packed
   // counts gives its starting offsets, and it emits its kept pages in order.
   uint64_t gbits = 0, ebits = 0;  // chunk masks (C <= 64)
   for_my_keys([&](uint32_t k, int i) {
-    bool g, e;
-    classify(k, g, e);
-    gbits |= (uint64_t)g << i;
-    ebits |= (uint64_t)e << i;
+    const int c = classify(k, my_first + i);
+    gbits |= (uint64_t)(c & 1) << i;
+    ebits |= (uint64_t)(c >> 1) << i;
   });
   const int cg = __popcll(gbits), ce = __popcll(ebits);
   const int packed = cg | (ce << 16);  // both sums stay below 2^15
   int incl = wave_inclusive_sum(packed);
-  __syncthreads();  // red[0..10] no longer read
-  if (lane == kWave - 1) L.red[wave] = incl;
+  if (lane == kWave - 1) L.red[wave] = incl;   // slots 0..7 are used by nothing else
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {

@@ -150,16 +150,19 @@ def test_select_on_given_scores_is_exact(oracle, built):
     """ts_select_topk_pages on fp32 scores the oracle also sees: bit-exact sets,
     including heavy ties (quantised scores), -0/+0, and K >= P."""
     print("[case] select exact", flush=True)
-    B, Hkv, S, Pmax, Kmax = 5, 3, 16, 1500, 300
+    B, Hkv, S, Pmax, Kmax = 6, 3, 16, 1500, 300
     rng = np.random.default_rng(77)
-    lens = np.array([1500 * 16, 777 * 16 + 3, 16, 0, 299 * 16], dtype=np.int32)
+    lens = np.array([1500 * 16, 777 * 16 + 3, 16, 0, 299 * 16, 1200 * 16], dtype=np.int32)
     sc = rng.standard_normal((B, Hkv, Pmax)).astype(np.float32)
     sc[0, 1] = np.round(sc[0, 1] * 2) / 2                 # many exact ties
     sc[0, 2] = 0.0
     sc[0, 2, ::3] = -0.0                                   # signed zeros rank equal
     sc[1, 0] = np.float32(1e-30) * sc[1, 0]                # tiny magnitudes
     sc[1, 1] = -np.abs(sc[1, 1]) * 1e20                    # all negative, large
-    topk_ps = np.array([300, 100, 5, 7, 299], dtype=np.int32)
+    sc[5, 0] = np.round(sc[5, 0] * 64) / 64               # small tie groups at the cut
+    sc[5, 1] = np.round(sc[5, 1] * 8) / 8                 # tie groups of a few dozen
+    sc[5, 2] = np.round(sc[5, 2] * 512) / 512             # mostly pairs
+    topk_ps = np.array([300, 100, 5, 7, 299, 200], dtype=np.int32)
     lens_d = torch.from_numpy(lens).to(DEV)
     for per_seq in (False, True):
         lay = ts.make_layout(B, Hkv, Hkv, 64, S, Pmax, None, None, None, lens_d, None, None)
