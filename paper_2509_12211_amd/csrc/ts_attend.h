@@ -267,23 +267,32 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   }
   __syncthreads();
   float* part = p.partials + (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
-  for (int idx = threadIdx.x; idx < G * RS; idx += kThreads) {
-    const int g = idx / RS, c = idx % RS;
-    float M = -INFINITY;
+  // one thread per (head, channel); the thread of channel 0 also hands on the
+  // head's running max and sum
+  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    const int g = idx / D, c = idx % D;
+    float mw[kWaves], M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, lds[((size_t)w * G + g) * RS + D]);
+    for (int w = 0; w < kWaves; ++w) {
+      mw[w] = lds[((size_t)w * G + g) * RS + D];
+      M = fmaxf(M, mw[w]);
+    }
     float Lsum = 0.f, O = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
       const float* row = lds + ((size_t)w * G + g) * RS;
-      const float wgt = __builtin_amdgcn_exp2f(row[D] - M);
+      const float wgt = __builtin_amdgcn_exp2f(mw[w] - M);
       Lsum += row[D + 1] * wgt;
-      O += row[c < D ? c : 0] * wgt;
+      O += row[c] * wgt;
     }
     if (p.n_split == 1) {
-      if (c < D) p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+      p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
     } else {
-      store_agent(part + idx, c < D ? O : (c == D ? M : Lsum));
+      store_agent(part + g * RS + c, O);
+      if (c == 0) {
+        store_agent(part + g * RS + D, M);
+        store_agent(part + g * RS + D + 1, Lsum);
+      }
     }
   }
   __syncthreads();

@@ -70,38 +70,48 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
 
 // One workgroup per sequence: every (KV head, channel) of the new token widens
 // (or opens) the box of page seq_len / S and, when v_new is given, lands in its
-// pool slot.  All threads read seq_lens[b] before the barrier; thread 0
+// pool slot.  The kernel is a chain of dependent memory round trips, so it is
+// arranged to need only two: the token's values (which do not depend on the
+// length) go out together with the length, then the block-table entry and the
+// old box together.  All threads read seq_lens[b] before the barrier; thread 0
 // advances it after.
 __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams p, int D,
                                                                       const uint16_t* k_new,
                                                                       const uint16_t* v_new,
                                                                       int advance) {
-  const int b = blockIdx.x;
+  const int b = blockIdx.x, n = p.Hkv * D;
+  const size_t row = (size_t)b * n;  // [Hkv][D] values of this sequence's token
+  const int first = min((int)threadIdx.x, n - 1);
+  uint16_t kn = k_new[row + first];
+  uint16_t vn = v_new ? v_new[row + first] : (uint16_t)0;
   const int L = p.seq_lens[b];
-  const int j = L / p.S, slot = L % p.S;
-  int phys = -1;
-  if (j < p.Pmax) phys = p.block_table[(size_t)b * p.Pmax + j];
-  const bool ok = j < p.Pmax && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
-  if (ok) {
-    for (int idx = threadIdx.x; idx < p.Hkv * D; idx += kThreads) {
-      const int h = idx / D, c = idx % D;
-      const uint16_t kn = k_new[((size_t)b * p.Hkv + h) * D + c];
-      const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + c;
-      if (slot == 0) {
-        p.page_min[m] = kn;
-        p.page_max[m] = kn;
-      } else {
-        const float x = bf16_to_f32(kn);
-        if (x < bf16_to_f32(p.page_min[m])) p.page_min[m] = kn;
-        if (x > bf16_to_f32(p.page_max[m])) p.page_max[m] = kn;
-      }
+  const int sh = __builtin_ctz(p.S);  // page sizes are powers of two
+  const int j = L >> sh, slot = L & (p.S - 1);
+  const bool fits = j < p.Pmax;
+  const int jc = fits ? j : 0;
+  const int phys = p.block_table[(size_t)b * p.Pmax + jc];
+  bool ok = fits;
+  for (int idx = threadIdx.x; idx < n; idx += kThreads) {
+    if (idx != (int)threadIdx.x) {
+      kn = k_new[row + idx];
+      vn = v_new ? v_new[row + idx] : (uint16_t)0;
+    }
+    const int h = idx / D, c = idx % D;
+    const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + jc) * D + c;
+    const uint16_t lo = p.page_min[m], hi = p.page_max[m];  // fetched before phys is looked at
+    ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
+    if (ok) {
+      const float x = bf16_to_f32(kn);
+      if (slot == 0 || x < bf16_to_f32(lo)) p.page_min[m] = kn;
+      if (slot == 0 || x > bf16_to_f32(hi)) p.page_max[m] = kn;
       if (v_new != nullptr) {
         const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
         p.k_pool_w[tile + (size_t)slot * D + c] = kn;
-        p.v_pool_w[tile + (size_t)c * p.S + slot] = v_new[((size_t)b * p.Hkv + h) * D + c];
+        p.v_pool_w[tile + (size_t)c * p.S + slot] = vn;
       }
     }
   }
+  ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
   __syncthreads();
   if (ok && advance && threadIdx.x == 0) p.seq_lens[b] = L + 1;
 }
