@@ -146,14 +146,29 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream);
 
-/* Host-only: bytes of workspace the two calls above need for this layout and
+/* Section 3.4 + Algorithm 1: one decode step of a layer in ONE launch.  Exactly
+ * equivalent to ts_append_token_meta(layout, k_new, v_new, 1, stream) followed
+ * by ts_query_aware_decode(...) with the same remaining arguments: the new
+ * token of every sequence (k_new, v_new: bf16 [B][Hkv][d], both required) is
+ * stored in its pool slot, widens (or opens) the box of its page, takes part in
+ * the scoring, selection and attention of this same call, and seq_lens[b] is
+ * advanced by one before the call completes.  A sequence whose new page would
+ * be >= P_max is left unchanged.  The block-table entry of the page that
+ * receives the token must be valid. */
+int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,
+                         const void* q, int32_t topk, const int32_t* topk_per_seq,
+                         int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                         int32_t* sel_out, int32_t* sel_count_out, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/* Host-only: bytes of workspace the three calls above need for this layout and
  * max_topk (0 on invalid arguments).  Reads only the scalar fields. */
 size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk);
 
-/* Zeroes the workspace's control words.  Required once after allocation (and
- * after a launch that was aborted); every call leaves them zero again, so
- * repeated calls need no re-initialisation.  Calls sharing one workspace must
- * be ordered on one stream. */
+/* Zeroes the whole workspace.  Required once after allocation (and after a
+ * launch that was aborted); every call leaves the workspace ready for the
+ * next, so repeated calls need no re-initialisation.  Calls sharing one
+ * workspace must be ordered on one stream. */
 int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Blocking: copies the workspace's sticky error word to *status_host (host

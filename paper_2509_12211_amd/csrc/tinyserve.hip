@@ -82,7 +82,12 @@ static Plan make_plan(const ts_layout* L, int max_topk) {
   // this workgroup's selected pages; the wave-merge area aliases the keys
   const size_t lds_sel = select_lds_bytes(Pmax);
   const size_t lds_att = (size_t)kWaves * G * (L->head_dim + 2) * 4;
-  pl.lds_fused = (lds_sel > lds_att ? lds_sel : lds_att) + (size_t)Pmax * 4 + (size_t)pl.chunk * 4;
+  // ... and, in an area of its own, the query staging: a wave that is done
+  // scoring starts the selection (which clears the bins) while another may not
+  // have picked up its query sums yet, so the two must not share memory
+  const size_t lds_query = (size_t)G * L->head_dim * 2 + 2 * (size_t)L->head_dim * 8;
+  pl.lds_fused = (lds_sel > lds_att ? lds_sel : lds_att) +
+                 align_up((size_t)Pmax * 4 + (size_t)pl.chunk * 4, 16) + lds_query;
   return pl;
 }
 
@@ -97,8 +102,28 @@ struct FusedParams {
   const int32_t* topk_per_seq;
   int32_t* ctrl;        // control words
   int32_t* attend_done; // [units * cstride]
-  int topk, S, units, g, cstride;
+  // One token per sequence appended by the same launch (k_new == nullptr: none).
+  const uint16_t* k_new;   // [B][Hkv][D]
+  const uint16_t* v_new;
+  uint16_t* k_pool_w;
+  uint16_t* v_pool_w;
+  uint16_t* page_min_w;
+  uint16_t* page_max_w;
+  int32_t* seq_lens_w;
+  int topk, S, units, g, cstride, B;
 };
+
+// Element-wise box update of eight packed bf16: lo = k where k < lo, hi = k
+// where k > hi (strict, as the stand-alone append kernel does it).
+__device__ __forceinline__ uint32_t widen_pair(uint32_t box, uint32_t k, bool is_min) {
+  const float bl = bf16_lo(box), bh = bf16_hi(box), kl = bf16_lo(k), kh = bf16_hi(k);
+  const bool tl = is_min ? kl < bl : kl > bl, th = is_min ? kh < bh : kh > bh;
+  return ((tl ? k : box) & 0x0000ffffu) | ((th ? k : box) & 0xffff0000u);
+}
+__device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, bool is_min) {
+  return make_uint4(widen_pair(box.x, k.x, is_min), widen_pair(box.y, k.y, is_min),
+                    widen_pair(box.z, k.z, is_min), widen_pair(box.w, k.w, is_min));
+}
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
 
@@ -180,8 +205,9 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   const int c0 = min(split * p.chunk, Kb), count = min(c0 + p.chunk, Kb) - c0;
   const int32_t* sel_row = sel + (size_t)u * p.Kmax + c0;
   const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
-  attend_split<D, S, true>(
-      p, b, h, split, count, p.seq_lens[b], [&](int i) { return sel_row[i]; },
+  const NewToken none{-1, 0, p.q, p.q};
+  attend_split<D, S, true, false>(
+      p, b, h, split, count, p.seq_lens[b], none, [&](int i) { return sel_row[i]; },
       [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
   if (p.n_split == 1) return;
   stores_complete();
@@ -222,7 +248,10 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 // unit-independent value of the whole body (several hundred instructions, most
 // of them spilled at once) is computed ahead of the first unit, that is ahead of
 // the first load.
-template <int D, int S, bool kLoop>
+//
+// kApp = true is the build that first appends one token per sequence
+// (ts_append_and_decode); the plain build carries none of its registers.
+template <int D, int S, bool kLoop, bool kApp>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_flag;
@@ -237,6 +266,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   const size_t att_bytes = (size_t)kWaves * G * (D + 2) * 4;
   int32_t* bt_lds = reinterpret_cast<int32_t*>(smem + (sel_bytes > att_bytes ? sel_bytes : att_bytes));
   int32_t* my_sel = bt_lds + Pmax;  // [chunk]
+  unsigned char* q_stage = reinterpret_cast<unsigned char*>(bt_lds) +
+                           ((size_t)Pmax * 4 + (size_t)at.chunk * 4 + 15) / 16 * 16;
   const bool exchange = g > 1;
   // With one workgroup per unit and more units than workgroups (long ragged
   // batches) the units are handed out from a counter as workgroups become
@@ -259,11 +290,22 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
   int L_raw, K_raw, epoch_raw, bt_regs[kBtRegs];
   ScanRegs<D> scan;
+  // Append mode: the new token's key / value rows of this unit, as the 16-byte
+  // chunk (channels 8 * (lane % (D/8)) .. + 7) every lane needs for the box update
+  // and the pool write.
+  constexpr bool app = kApp;
+  constexpr int LPR = ScoreLanes<D>::LPR;
+  uint4 kn16 = make_uint4(0, 0, 0, 0), vn16 = make_uint4(0, 0, 0, 0);
   auto issue_unit = [&](int uu) {
     const int b = uu / at.Hkv, h = uu % at.Hkv;
     epoch_raw = p.ctrl[kCtrlEpoch];
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
+    if (app) {
+      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
+      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
+      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
+    }
     scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
 #pragma unroll
@@ -290,11 +332,12 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 
     // 1. score my share of the pages; the unit's block-table row is parked in LDS
     KeyLayout kl;
+    int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
     scan_finish<D, !kLoop>(
         scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
-        member * kWaves + wave_id(), g * kWaves, reinterpret_cast<unsigned char*>(sl.hist),
+        member * kWaves + wave_id(), g * kWaves, q_stage,
         [&] {
 #pragma unroll
           for (int k = 0; k < kBtRegs; ++k) {
@@ -307,9 +350,26 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           // using them earlier would put a memory round trip in front of the scan)
           asm volatile("" : "+v"(L_raw), "+v"(K_raw), "+v"(epoch_raw));
           tag = (uint32_t)uniform(epoch_raw) + 1u;
-          pb_scan = uniform(min(pages_of(L_raw, S), Pmax));
+          L_unit = uniform(L_raw);
+          if (app && L_unit / S < Pmax) {  // a sequence with no room left is not extended
+            j_new = L_unit / S;
+            slot_new = L_unit % S;
+            L_unit += 1;
+          }
+          pb_scan = uniform(min(pages_of(L_unit, S), Pmax));
           kl = KeyLayout::make(pb_scan);
           return pb_scan;
+        },
+        [&](uint4& mn, uint4& mx, int pg) {
+          // the wave that scores the new token's page first widens (or opens)
+          // its box, in registers and in memory
+          if (pg == j_new) {
+            mn = slot_new == 0 ? kn16 : widen_box(mn, kn16, true);
+            mx = slot_new == 0 ? kn16 : widen_box(mx, kn16, false);
+            const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
+            *reinterpret_cast<uint4*>(p.page_min_w + row) = mn;
+            *reinterpret_cast<uint4*>(p.page_max_w + row) = mx;
+          }
         },
         [&](int pg, float s) {
           if (exchange) {
@@ -322,14 +382,20 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           if (srow_out) srow_out[pg] = s;
         });
-    const int L = uniform(L_raw);
+    const int L = uniform(L_unit);
     const int Pb = uniform(min(pages_of(L, S), Pmax));
     const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
+
+    // count this workgroup in (once): it has read the epoch and, in append mode,
+    // the sequence length
+    if (!kLoop || exchange) {
+      if (arrived < 0 && threadIdx.x == 0 && (exchange || app))
+        arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
+    }
 
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
     if (exchange) {
-      if (arrived < 0 && threadIdx.x == 0) arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
       // every thread polls its own entries of the row until all carry this
       // launch's tag (all loads of a round in flight together; bounded)
       bool expired = false;
@@ -364,6 +430,21 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     select_begin(sl, tmin, tmax);
     __syncthreads();
     TS_MARK(4);
+    // the new token lands in its pool slot (one member's first lanes; the
+    // block-table row is complete in LDS by now).  Nothing in this launch reads
+    // it from there: the attention splices it in from the caller's arrays.
+    if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
+      const int phys = bt_lds[j_new];
+      if (phys >= 0 && phys < at.n_phys) {
+        const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
+        *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
+        const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
+              (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
+      }
+    }
 
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
@@ -379,8 +460,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     TS_MARK(5);
 
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
-    attend_split<D, S, !kLoop>(
-        at, b, h, member, count, L, [&](int i) { return my_sel[i]; },
+    const size_t new_row = ((size_t)b * at.Hkv + h) * D;
+    const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
+    attend_split<D, S, !kLoop, kApp>(
+        at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
     TS_MARK(6);
 
@@ -414,15 +497,37 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (u >= p.units) break;
     issue_unit(u);
   }
-  if (exchange && threadIdx.x == 0 && arrived == (int)gridDim.x - 1) {
-    atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
-    atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+  // Append mode: the sequence lengths advance once every workgroup is past its
+  // last read of them.  With one unit per workgroup that is known to the
+  // workgroup that counted itself in last (all the others had read theirs by
+  // then); with several units per workgroup, to the last workgroup to finish.
+  auto advance_lengths = [&] {
+    for (int i = threadIdx.x; i < p.B; i += kThreads) {
+      const int len = p.seq_lens_w[i];
+      if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
+    }
+  };
+  __syncthreads();
+  if (threadIdx.x == 0) s_flag = arrived == (int)gridDim.x - 1;
+  __syncthreads();
+  const bool counted_in_last = uniform(s_flag) != 0;
+  if (counted_in_last) {
+    if (threadIdx.x == 0) {
+      atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
+      if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+    }
+    if (app && !kLoop) advance_lengths();
   }
-  if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
+  if (dynamic || (kLoop && app)) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();
-    if (threadIdx.x == 0 && atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
-      atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
-      atomic_store_agent(&p.ctrl[kCtrlExit], 0);
+    if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1;
+    __syncthreads();
+    if (uniform(s_flag)) {
+      if (threadIdx.x == 0) {
+        atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
+        atomic_store_agent(&p.ctrl[kCtrlExit], 0);
+      }
+      if (app) advance_lengths();
     }
   }
 }
@@ -533,6 +638,85 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
 }  // namespace ts
 
 using namespace ts;
+
+static int launch_fused(const ts_layout* layout, const void* k_new, const void* v_new,
+                        const void* q, int32_t topk, const int32_t* topk_per_seq,
+                        int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                        int32_t* sel_out, int32_t* sel_count_out, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  int st = check_layout(layout);
+  if (st != TS_OK) return st;
+  if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
+      !layout->seq_lens || !layout->page_min || !layout->page_max)
+    return TS_ERR_NULL;
+  if (max_topk < 1 || (!topk_per_seq && (topk < 1 || max_topk < topk))) return TS_ERR_SHAPE;
+  Plan pl = make_plan(layout, max_topk);
+  if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
+  const int cus = num_compute_units();
+  if (cus <= 0) return TS_ERR_DEVICE;
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  FusedParams p;
+  p.at = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
+  p.page_min = static_cast<const uint16_t*>(layout->page_min);
+  p.page_max = static_cast<const uint16_t*>(layout->page_max);
+  p.scores = reinterpret_cast<uint64_t*>(ws + pl.off_scores);
+  p.scores_out = scores_out;
+  p.sel_out = sel_out;
+  p.sel_count = sel_count_out;
+  p.topk_per_seq = topk_per_seq;
+  p.ctrl = reinterpret_cast<int32_t*>(ws);
+  p.attend_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
+  p.cstride = pl.cstride;
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.k_pool_w = static_cast<uint16_t*>(layout->k_pool);
+  p.v_pool_w = static_cast<uint16_t*>(layout->v_pool);
+  p.page_min_w = static_cast<uint16_t*>(layout->page_min);
+  p.page_max_w = static_cast<uint16_t*>(layout->page_max);
+  p.seq_lens_w = layout->seq_lens;
+  p.B = layout->num_seqs;
+  p.topk = topk;
+  p.S = layout->page_size;
+  p.units = pl.units;
+  p.g = pl.g;
+  hipStream_t s = (hipStream_t)stream;
+  const int D = layout->head_dim, S = layout->page_size;
+  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
+#define TS_LAUNCH_FUSED(DD, SS, APP)                                                          \
+  do {                                                                                        \
+    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true, APP>, pl.lds_fused)) !=       \
+            TS_OK ||                                                                          \
+        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, APP>, pl.lds_fused)) != TS_OK) \
+      return st;                                                                              \
+    int cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false, APP>, pl.lds_fused); \
+    if (cap1 > cus * per_cu) cap1 = cus * per_cu;                                             \
+    if (pl.units * pl.g <= cap1) { /* one unit per cluster */                                 \
+      query_aware_decode_kernel<DD, SS, false, APP>                                           \
+          <<<(unsigned)(pl.units * pl.g), kThreads, pl.lds_fused, s>>>(p);                    \
+      break;                                                                                  \
+    }                                                                                         \
+    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true, APP>, pl.lds_fused);  \
+    if (cap > cus * per_cu) cap = cus * per_cu;                                               \
+    int clusters = cap / pl.g;                                                                \
+    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */               \
+    if (clusters > pl.units) clusters = pl.units;                                             \
+    query_aware_decode_kernel<DD, SS, true, APP>                                              \
+        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                      \
+  } while (0)
+#define TS_LAUNCH_FUSED_DS(APP)                            \
+  do {                                                     \
+    if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16, APP);  \
+    else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32, APP);   \
+    else if (D == 128 && S == 16) TS_LAUNCH_FUSED(128, 16, APP); \
+    else TS_LAUNCH_FUSED(128, 32, APP);                    \
+  } while (0)
+  if (k_new) TS_LAUNCH_FUSED_DS(true);
+  else TS_LAUNCH_FUSED_DS(false);
+#undef TS_LAUNCH_FUSED_DS
+#undef TS_LAUNCH_FUSED
+  return launch_status();
+}
+
 
 extern "C" {
 
@@ -702,62 +886,20 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           float* out, float* scores_out, int32_t* sel_out,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream) {
-  int st = check_layout(layout);
+  return launch_fused(layout, nullptr, nullptr, q, topk, topk_per_seq, max_topk, softmax_scale, out,
+                      scores_out, sel_out, sel_count_out, workspace, workspace_bytes, stream);
+}
+
+int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,
+                         const void* q, int32_t topk, const int32_t* topk_per_seq,
+                         int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                         int32_t* sel_out, int32_t* sel_count_out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  const int st = check_layout(layout);
   if (st != TS_OK) return st;
-  if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
-      !layout->seq_lens || !layout->page_min || !layout->page_max)
-    return TS_ERR_NULL;
-  if (max_topk < 1 || (!topk_per_seq && (topk < 1 || max_topk < topk))) return TS_ERR_SHAPE;
-  Plan pl = make_plan(layout, max_topk);
-  if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
-  const int cus = num_compute_units();
-  if (cus <= 0) return TS_ERR_DEVICE;
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  FusedParams p;
-  p.at = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
-  p.page_min = static_cast<const uint16_t*>(layout->page_min);
-  p.page_max = static_cast<const uint16_t*>(layout->page_max);
-  p.scores = reinterpret_cast<uint64_t*>(ws + pl.off_scores);
-  p.scores_out = scores_out;
-  p.sel_out = sel_out;
-  p.sel_count = sel_count_out;
-  p.topk_per_seq = topk_per_seq;
-  p.ctrl = reinterpret_cast<int32_t*>(ws);
-  p.attend_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
-  p.cstride = pl.cstride;
-  p.topk = topk;
-  p.S = layout->page_size;
-  p.units = pl.units;
-  p.g = pl.g;
-  hipStream_t s = (hipStream_t)stream;
-  const int D = layout->head_dim, S = layout->page_size;
-  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-#define TS_LAUNCH_FUSED(DD, SS)                                                              \
-  do {                                                                                       \
-    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true>, pl.lds_fused)) != TS_OK ||  \
-        (st = allow_lds(query_aware_decode_kernel<DD, SS, false>, pl.lds_fused)) != TS_OK)   \
-      return st;                                                                             \
-    int cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false>, pl.lds_fused);    \
-    if (cap1 > cus * per_cu) cap1 = cus * per_cu;                                            \
-    if (pl.units * pl.g <= cap1) { /* one unit per cluster */                                \
-      query_aware_decode_kernel<DD, SS, false>                                               \
-          <<<(unsigned)(pl.units * pl.g), kThreads, pl.lds_fused, s>>>(p);                   \
-      break;                                                                                 \
-    }                                                                                        \
-    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true>, pl.lds_fused);      \
-    if (cap > cus * per_cu) cap = cus * per_cu;                                              \
-    int clusters = cap / pl.g;                                                               \
-    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */              \
-    if (clusters > pl.units) clusters = pl.units;                                            \
-    query_aware_decode_kernel<DD, SS, true>                                                  \
-        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                     \
-  } while (0)
-  if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16);
-  else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32);
-  else if (D == 128 && S == 16) TS_LAUNCH_FUSED(128, 16);
-  else TS_LAUNCH_FUSED(128, 32);
-#undef TS_LAUNCH_FUSED
-  return launch_status();
+  if (!k_new || !v_new) return TS_ERR_NULL;
+  return launch_fused(layout, k_new, v_new, q, topk, topk_per_seq, max_topk, softmax_scale, out,
+                      scores_out, sel_out, sel_count_out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -95,6 +95,53 @@ __device__ __forceinline__ void load_page(PageFrag<D, S>& f, const uint16_t* kti
   }
 }
 
+// A token appended in the same launch: it belongs to page j (-1: none), slot
+// `slot` of that page; its key / value rows (D bf16 each) are read from the
+// caller's arrays and spliced into the page's operands in registers, so the
+// attention does not depend on when the pool itself receives them.  Without a
+// token the two pointers must still be readable (D bf16; the data is not used).
+struct NewToken {
+  int j, slot;
+  const uint16_t* k_row;
+  const uint16_t* v_row;
+};
+
+template <int D, int S>
+struct TokenPatch {
+  uint4 k[PageFrag<D, S>::KQ];       // this lane's D/4 channels of the key
+  uint32_t v[PageFrag<D, S>::NCB];   // value of channel 16 * cb + lane % 16
+  __device__ __forceinline__ void load(const NewToken& nt) {
+    const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, S>::KQ; ++i)
+      k[i] = *reinterpret_cast<const uint4*>(nt.k_row + kb * (D / 4) + i * 8);
+#pragma unroll
+    for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) v[cb] = nt.v_row[16 * cb + r];
+  }
+  // Splice into a page fetched from the pool (registers only).
+  __device__ __forceinline__ void apply(PageFrag<D, S>& f, int slot) const {
+    const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
+      if (tile_token<S>(t, r) == slot) {
+#pragma unroll
+        for (int i = 0; i < PageFrag<D, S>::KQ; ++i) f.k[t][i] = k[i];
+      }
+      // V words of tile t hold tokens tile_token<S>(t, 4 * kb) .. + 3
+      const int e = slot - tile_token<S>(t, 4 * kb);
+      if (e >= 0 && e < 4) {
+#pragma unroll
+        for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) {
+          const uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
+          const uint32_t put = (e & 1) ? (v[cb] << 16) : v[cb];
+          if (e < 2) f.v[t][cb].x = (f.v[t][cb].x & keep) | put;
+          else f.v[t][cb].y = (f.v[t][cb].y & keep) | put;
+        }
+      }
+    }
+  }
+};
+
 template <int D>
 struct WaveAcc {
   float m, l;  // running max (log2 domain) and this lane's share of the running sum
@@ -198,10 +245,11 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
 // kBranchless: the ring is refilled without a branch around the loads (see
 // below); with false the refill past the end of the list is skipped instead,
 // which suits bandwidth-bound launches with thousands of units.
-template <int D, int S, bool kBranchless, typename SelAt, typename PhysAt>
+// kPatch: a token appended in the same launch may have to be spliced in (nt).
+template <int D, int S, bool kBranchless, bool kPatch, typename SelAt, typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
-                                             int count, int L, SelAt sel_at, PhysAt phys_at,
-                                             float* lds) {
+                                             int count, int L, const NewToken& nt, SelAt sel_at,
+                                             PhysAt phys_at, float* lds) {
   const int lane = lane_id(), wave = wave_id();
   const int head = lane & 15, kb = lane >> 4;
   const int G = p.G;
@@ -210,6 +258,8 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 
   short4_t qf[D / 16];
   load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  TokenPatch<D, S> patch;
+  if (kPatch) patch.load(nt);
   WaveAcc<D> acc;
   acc.init();
 
@@ -226,15 +276,16 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     // (4 KiB - 8 KiB each) before the first is consumed.
     constexpr int NBUF = (D * S <= 1024) ? 4 : ((D == 64 && D * S <= 2048) ? 3 : 2);
     PageFrag<D, S> f[NBUF];
-    int valid[NBUF];
+    int valid[NBUF], page[NBUF];
     // No branch around the loads (a load under a branch makes the compiler
     // wait for ALL outstanding loads wherever it needs one of them, so the ring
     // would drain before the first page is used): a slot past the end of the
     // list, or one whose page id is out of range, re-reads a page that is
     // certainly mapped (a single cache line of it) and counts zero valid tokens.
-    auto issue = [&](PageFrag<D, S>& fr, int x) -> int {
+    auto issue = [&](PageFrag<D, S>& fr, int& jp, int x) -> int {
       const int xc = min(x, n - 1);
       const int j = __builtin_amdgcn_readlane(my_j, xc);
+      jp = j;
       const int phys = __builtin_amdgcn_readlane(my_phys, xc);
       const bool good = x < n && phys >= 0 && phys < p.n_phys;
       const size_t tile = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
@@ -242,13 +293,16 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
       return good ? max(0, min(S, L - j * S)) : 0;
     };
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i) valid[i] = issue(f[i], i);
+    for (int i = 0; i < NBUF; ++i) valid[i] = issue(f[i], page[i], i);
     TS_MARK(17);
     for (int x0 = 0; x0 < n; x0 += NBUF) {
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
-        if (x0 + i < n) attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
-        if (kBranchless || x0 + i + NBUF < n) valid[i] = issue(f[i], x0 + i + NBUF);
+        if (x0 + i < n) {
+          if (kPatch && nt.j >= 0 && page[i] == nt.j) patch.apply(f[i], nt.slot);
+          attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
+        }
+        if (kBranchless || x0 + i + NBUF < n) valid[i] = issue(f[i], page[i], x0 + i + NBUF);
       }
     }
   }

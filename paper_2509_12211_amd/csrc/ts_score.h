@@ -115,15 +115,17 @@ struct MetaTile {
   }
 
   // sink(page, score) is called once per page < Pmax by one lane; pages >= Pb
-  // get -inf.
-  template <typename Sink>
+  // get -inf.  patch(min_row, max_row, page) may first amend the row chunks this
+  // lane holds (a token appended in the same launch).
+  template <typename Patch, typename Sink>
   __device__ __forceinline__ void reduce(const ScoreLanes<D>& ql, int base, int Pb, int Pmax,
-                                         Sink sink) const {
+                                         Patch patch, Sink sink) {
     constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pg = base + u * PPW + prow;
+      patch(mn[u], mx[u], pg);
       const double s = group_sum_f64<LPR>(ql.row_partial(mn[u], mx[u]));
       if (cg == 0 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
     }
@@ -162,11 +164,11 @@ __device__ __forceinline__ void scan_issue_tile(ScanRegs<D>& r, const uint16_t* 
 // of the current tile.  That is what a latency-bound launch wants; a launch with
 // thousands of units is bound by bandwidth and overlaps across workgroups, and
 // there the plain branch is a little cheaper.
-template <int D, bool kBranchless, typename AfterQuery, typename Sink>
+template <int D, bool kBranchless, typename AfterQuery, typename Patch, typename Sink>
 __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin_u,
                                             const uint16_t* pmax_u, int G, int Pmax, int first_iter,
                                             int iter_stride, unsigned char* q_stage,
-                                            AfterQuery after_query, Sink sink) {
+                                            AfterQuery after_query, Patch patch, Sink sink) {
   constexpr int PPI = ScoreLanes<D>::PPI;
   TS_MARK(19);
   ScoreLanes<D> ql;
@@ -181,7 +183,7 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin
     MetaTile<D> cur = r.tile;
     if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
     else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb);
-    cur.reduce(ql, base, Pb, Pmax, sink);
+    cur.reduce(ql, base, Pb, Pmax, patch, sink);
     base = next;
   }
 }
@@ -200,7 +202,7 @@ __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const 
   issue_extra();
   scan_issue_tile<D>(r, pmin_u, pmax_u, Pmax, first_iter);
   scan_finish<D, true>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query,
-                       sink);
+                       [](uint4&, uint4&, int) {}, sink);
 }
 
 }  // namespace ts

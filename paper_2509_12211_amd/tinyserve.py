@@ -25,7 +25,8 @@ TS_ERR_DEVICE = -6
 
 EXPORTS = [
     "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
-    "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_workspace_bytes",
+    "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_append_and_decode",
+    "ts_workspace_bytes",
     "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
 ]
 
@@ -68,6 +69,7 @@ def lib():
         L.ts_select_topk_pages.argtypes = [lp, vp, i32, vp, i32, vp, vp, vp]
         L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_append_and_decode.argtypes = [lp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_workspace_bytes.argtypes = [lp, i32]
         L.ts_workspace_bytes.restype = sz
         L.ts_workspace_init.argtypes = [vp, sz, vp]
@@ -179,6 +181,15 @@ def query_aware_decode(layout, q, topk, max_topk, softmax_scale, out, workspace,
         float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out), _ptr(sel_count_out),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
         "ts_query_aware_decode")
+
+
+def append_and_decode(layout, k_new, v_new, q, topk, max_topk, softmax_scale, out, workspace,
+                      topk_per_seq=None, scores_out=None, sel_out=None, sel_count_out=None):
+    _check(lib().ts_append_and_decode(
+        ctypes.byref(layout), _ptr(k_new), _ptr(v_new), _ptr(q), int(topk), _ptr(topk_per_seq),
+        int(max_topk), float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out),
+        _ptr(sel_count_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream()), "ts_append_and_decode")
 
 
 def set_tuning(reserved=0, num_splits=0, workgroups_per_cu=0):

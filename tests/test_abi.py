@@ -92,6 +92,10 @@ def test_argument_validation():
                                      big, None) == ts.TS_ERR_SHAPE
     assert lib.ts_query_aware_decode(ctypes.byref(lay), p, 9, None, 8, 1.0, p, None, None, None, p,
                                      big, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_append_and_decode(ctypes.byref(lay), None, p, p, 4, None, 8, 1.0, p, None, None,
+                                    None, p, big, None) == ts.TS_ERR_NULL
+    assert lib.ts_append_and_decode(ctypes.byref(lay), p, p, p, 4, None, 8, 1.0, p, None, None,
+                                    None, p, 16, None) == ts.TS_ERR_WORKSPACE
     assert lib.ts_workspace_init(None, 1024, None) == ts.TS_ERR_NULL
     assert lib.ts_workspace_init(p, 8, None) == ts.TS_ERR_WORKSPACE
     assert lib.ts_workspace_status(None, None) == ts.TS_ERR_NULL

@@ -224,6 +224,92 @@ def test_append_matches_oracle_and_rebuild(oracle, built):
         assert np.array_equal(a, o)
 
 
+APPEND_FUSED = {
+    # clusters of two workgroups per unit
+    "gqa4_d64_s16": wl.WorkloadSpec("af1", 4, 8, 2, 64, 16, 200, 6, L_min=1, headroom=48),
+    # more units than workgroups: one workgroup per unit, units handed out by ticket
+    "mha_d128_s16_many": wl.WorkloadSpec("af2", 72, 4, 4, 128, 16, 300, 5, L_min=1, headroom=48),
+    "gqa8_d64_s32": wl.WorkloadSpec("af3", 3, 16, 2, 64, 32, 700, 7, keys="walk", headroom=80),
+    "gqa2_d128_s32": wl.WorkloadSpec("af4", 2, 4, 2, 128, 32, 500, 4, headroom=80),
+}
+
+
+def _bits_equal(a, b):
+    return torch.equal(a.contiguous().view(torch.int16), b.contiguous().view(torch.int16))
+
+
+@pytest.mark.parametrize("name", list(APPEND_FUSED))
+def test_append_and_decode_equals_separate_calls(oracle, built, name):
+    """ts_append_and_decode == ts_append_token_meta followed by ts_query_aware_decode:
+    same outputs, same metadata, same pool contents, same lengths, step after step
+    across page boundaries, including a sequence that runs out of room."""
+    spec = APPEND_FUSED[name]
+    print(f"[case] append+decode {name}", flush=True)
+    n_new = 36
+    scale = 1.0 / math.sqrt(spec.d)
+    sessions = []
+    for _ in range(2):
+        w = wl.make_workload(spec, DEV, seed=77, n_q=n_new, n_new=n_new, poison=0.0)
+        sess = Session(w, poison_meta=False)
+        if not spec.L_min:
+            # every sequence owns all P_max pages here: sequence 0 is put two tokens
+            # short of its capacity, so the third append must be refused
+            sess.seq_lens[0] = w.P_max * spec.S - 2
+        ts.build_page_meta(sess.layout)
+        sessions.append(sess)
+    a, f = sessions
+    units = [(b, h) for b in range(min(spec.B, 6)) for h in range(spec.Hkv)]
+    for i in range(n_new):
+        ts.append_token_meta(a.layout, a.w.k_new[i], a.w.v_new[i], advance_seq_lens=True)
+        a.fused(scale, q_idx=i)
+        w = f.w
+        ts.append_and_decode(f.layout, w.k_new[i], w.v_new[i], w.q[i], w.topk, w.K_max, scale, f.out,
+                             f.ws, topk_per_seq=w.topk_per_seq, scores_out=f.scores,
+                             sel_out=f.sel, sel_count_out=f.sel_count)
+        torch.cuda.synchronize()
+        assert ts.workspace_status(f.ws) == 0 and ts.workspace_status(a.ws) == 0
+        what = f"{name} step {i}"
+        assert torch.equal(a.seq_lens, f.seq_lens), what
+        assert torch.equal(a.sel_count, f.sel_count) and torch.equal(a.sel, f.sel), what
+        assert _bits_equal(a.page_min, f.page_min) and _bits_equal(a.page_max, f.page_max), what
+        assert _bits_equal(a.w.k_pool, f.w.k_pool) and _bits_equal(a.w.v_pool, f.w.v_pool), what
+        assert torch.equal(a.scores, f.scores), what
+        assert (a.out - f.out).abs().max().item() <= 1e-6, what
+        if i in (0, 17, n_new - 1):
+            compare_units(oracle, f, units, scale, q_idx=i, what=what)
+    if not spec.L_min:
+        assert int(f.seq_lens[0]) == f.w.P_max * spec.S      # stopped at capacity
+
+
+def test_query_sums_read_back_through_one_hot_boxes(built):
+    """Boxes are overwritten so that page c has max = unit vector c and min = 0: the
+    score of page c then equals Qp_c = sum over the group's heads of max(q_c, 0), read
+    back exactly.  More units than workgroups, many launches: every workgroup scores
+    several units in a row, and any mix-up of one unit's query staging with the
+    next phase of another wave shows as a wrong or zero channel."""
+    print("[case] one-hot probe", flush=True)
+    spec = wl.WorkloadSpec("probe", 72, 8, 4, 128, 16, 2100, 8, headroom=64)
+    n = 12
+    w = wl.make_workload(spec, DEV, seed=5, n_q=n, n_new=n, poison=0.0)
+    sess = Session(w, poison_meta=False)
+    ts.build_page_meta(sess.layout)
+    sess.page_min[:, :, :128] = 0
+    sess.page_max[:, :, :128] = torch.eye(128, dtype=torch.bfloat16, device=DEV)[None, None]
+    G = spec.Hq // spec.Hkv
+    scale = 1.0 / math.sqrt(spec.d)
+    for i in range(n):
+        if i % 2:
+            sess.fused(scale, q_idx=i)
+        else:
+            ts.append_and_decode(sess.layout, w.k_new[i], w.v_new[i], w.q[i], w.topk, w.K_max, scale,
+                                 sess.out, sess.ws, scores_out=sess.scores, sel_out=sess.sel,
+                                 sel_count_out=sess.sel_count)
+        torch.cuda.synchronize()
+        assert ts.workspace_status(sess.ws) == 0
+        qp = w.q[i].float().clamp(min=0).view(spec.B, spec.Hkv, G, spec.d).sum(2)
+        assert torch.equal(sess.scores[:, :, :128], qp), f"launch {i}"
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
