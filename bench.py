@@ -1,9 +1,10 @@
 """Benchmark of the query-aware decode hot path on one MI355X.
 
-A step = one decode step of one attention layer over one synthetic batch:
-ts_append_token_meta (one new token per sequence: K/V slot write + incremental
-min/max) followed by the fused single-launch ts_query_aware_decode (score all
-pages, top-K, sparse attention).  Consecutive steps rotate over several
+A step = one decode step of one attention layer over one synthetic batch: one
+new token per sequence is appended (K/V slot write + incremental min/max), then
+all pages are scored, the top-K selected and sparse attention run over them.  By
+default that is ONE launch of ts_append_and_decode; --step separate times the
+two-call form (ts_append_token_meta, then ts_query_aware_decode) instead.  Consecutive steps rotate over several
 independent layers (own KV pool, metadata and query), as a model's decode step
 does, so each step finds its metadata and KV pages in HBM rather than in the
 256 MB memory-side cache left warm by the previous step.
@@ -68,6 +69,11 @@ class Layer:
         tps = None if w.topk_per_seq is None else vp(w.topk_per_seq.data_ptr())
         self._append = (lib.ts_append_token_meta, (lay, vp(w.k_new[0].data_ptr()),
                                                    vp(w.v_new[0].data_ptr()), 1))
+        self._both = [(lib.ts_append_and_decode,
+                       (lay, vp(w.k_new[0].data_ptr()), vp(w.v_new[0].data_ptr()),
+                        vp(w.q[i].data_ptr()), w.topk, tps, w.K_max, scale,
+                        vp(self.out.data_ptr()), None, None, None, vp(self.ws.data_ptr()),
+                        self.ws.numel())) for i in range(n_q)]
         self._fused = [(lib.ts_query_aware_decode,
                         (lay, vp(w.q[i].data_ptr()), w.topk, tps, w.K_max, scale,
                          vp(self.out.data_ptr()), None, None, None, vp(self.ws.data_ptr()),
@@ -84,6 +90,12 @@ class Layer:
         st = f(*a, stream)
         if st != 0:
             raise RuntimeError(f"ts_query_aware_decode -> {st}")
+
+    def both(self, stream, qi=0):
+        f, a = self._both[qi % len(self._both)]
+        st = f(*a, stream)
+        if st != 0:
+            raise RuntimeError(f"ts_append_and_decode -> {st}")
 
     def reset_lengths(self):
         self.seq_lens.copy_(self.w.seq_lens)
@@ -148,6 +160,9 @@ def main():
     ap.add_argument("--workload", default="tinyllama", choices=list(WORKLOAD_DESC))
     ap.add_argument("--layers", type=int, default=0, help="independent layers rotated (0 = auto)")
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--step", default="one_launch", choices=["one_launch", "separate"],
+                    help="one_launch: ts_append_and_decode; separate: ts_append_token_meta + "
+                         "ts_query_aware_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -190,13 +205,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    one_launch = args.step == "one_launch"
+
     def step(i):
         ly = layers[i % n_layers]
-        ly.append(stream)
-        ly.fused(stream, i // n_layers)
+        if one_launch:
+            ly.both(stream, i // n_layers)
+        else:
+            ly.append(stream)
+            ly.fused(stream, i // n_layers)
 
-    def fused_only(i):
-        layers[i % n_layers].fused(stream, i // n_layers)
+    def fused_only(i):   # the dominant kernel alone: in one-launch mode it IS the step
+        if one_launch:
+            layers[i % n_layers].both(stream, i // n_layers)
+        else:
+            layers[i % n_layers].fused(stream, i // n_layers)
 
     launch = args.launch
 
@@ -218,11 +241,17 @@ def main():
         return g
 
     def body_step(ly, st):
-        ly.append(st)
-        ly.fused(st, 0)
+        if one_launch:
+            ly.both(st, 0)
+        else:
+            ly.append(st)
+            ly.fused(st, 0)
 
     def body_fused(ly, st):
-        ly.fused(st, 0)
+        if one_launch:
+            ly.both(st, 0)
+        else:
+            ly.fused(st, 0)
 
     graph = graph_fused = None
     if launch == "graph":
@@ -289,7 +318,9 @@ def main():
         "pct_of_hbm_peak": round(100.0 * by["total"] / (us_step * 1e-6) / HBM_PEAK, 2),
         "config": {
             "workload": WORKLOAD_DESC[args.workload],
-            "step": "ts_append_token_meta + fused ts_query_aware_decode, one layer",
+            "step": ("ts_append_and_decode (append + score + select + attend in one launch), one layer"
+                     if one_launch else
+                     "ts_append_token_meta + fused ts_query_aware_decode, one layer"),
             "layers_rotated": n_layers,
             "launch": launch,
             "softmax_scale": "1/sqrt(d)",
