@@ -281,6 +281,41 @@ def test_append_and_decode_equals_separate_calls(oracle, built, name):
         assert int(f.seq_lens[0]) == f.w.P_max * spec.S      # stopped at capacity
 
 
+MANY_UNITS = {
+    # more units than resident workgroups: the build of the fused kernel that loops over
+    # units (one workgroup per unit, units handed out by ticket), every (d, S) instance
+    "d64_s16": wl.WorkloadSpec("mu1", 80, 4, 4, 64, 16, 700, 9, L_min=1, headroom=32),
+    "d64_s32": wl.WorkloadSpec("mu2", 40, 16, 8, 64, 32, 900, 6, L_min=1, headroom=64),
+    "d128_s16": wl.WorkloadSpec("mu3", 70, 4, 4, 128, 16, 500, 0, L_min=1, budget_frac=0.3,
+                                headroom=32),
+    "d128_s32": wl.WorkloadSpec("mu4", 36, 16, 8, 128, 32, 800, 5, L_min=1, headroom=64),
+}
+
+
+@pytest.mark.parametrize("name", list(MANY_UNITS))
+def test_many_units_loop_build(oracle, built, name):
+    spec = MANY_UNITS[name]
+    print(f"[case] many units {name}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=404, n_q=3, n_new=3)
+    sess = Session(w)
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    n_units = spec.B * spec.Hkv
+    assert n_units > 256
+    rng = np.random.default_rng(9)
+    picks = sorted(set(rng.integers(0, n_units, 10).tolist()) | {0, 255, 256, n_units - 1})
+    units = [(u // spec.Hkv, u % spec.Hkv) for u in picks]
+    for i in range(3):
+        if i == 1:      # one step through the launch that also appends
+            ts.append_and_decode(sess.layout, w.k_new[i], w.v_new[i], w.q[i], w.topk, w.K_max, scale,
+                                 sess.out, sess.ws, topk_per_seq=w.topk_per_seq,
+                                 scores_out=sess.scores, sel_out=sess.sel,
+                                 sel_count_out=sess.sel_count)
+        else:
+            sess.fused(scale, q_idx=i)
+        compare_units(oracle, sess, units, scale, q_idx=i, what=f"{name} launch {i}")
+
+
 def test_query_sums_read_back_through_one_hot_boxes(built):
     """Boxes are overwritten so that page c has max = unit vector c and min = 0: the
     score of page c then equals Qp_c = sum over the group's heads of max(q_c, 0), read
