@@ -30,11 +30,11 @@ HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
 
 # HBM bytes per fused launch from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, one run each,
 # eager launches over cold data, each scaled by what the same counter reads for a plain
-# 256 MiB copy: x1.9996 and x1.0000).  Counters cannot be read from inside this process, so the
+# 256 MiB copy: x1.9997 and x1.0000).  Counters cannot be read from inside this process, so the
 # figures are carried here from the committed summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "tinyllama": int((26024.2 * 1.9996 + 1126.0) * 1024),
-    "longctx": int((18247.2 * 1.9996 + 1057.5) * 1024),
+    "tinyllama": int((26843.2 * 1.9997 + 1628.1) * 1024),
+    "longctx": int((19741.0 * 1.9997 + 1479.1) * 1024),
 }
 
 WORKLOAD_DESC = {
