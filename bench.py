@@ -9,7 +9,7 @@ independent layers (own KV pool, metadata and query), as a model's decode step
 does, so each step finds its metadata and KV pages in HBM rather than in the
 256 MB memory-side cache left warm by the previous step.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric, value (us/step), roofline of the dominant kernel, CPU-oracle baseline.
 """
 from __future__ import annotations
 
@@ -164,6 +164,8 @@ def main():
                     help="one_launch: ts_append_and_decode; separate: ts_append_token_meta + "
                          "ts_query_aware_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip timing the dense (whole-cache) attention beside the step")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known size against which "
@@ -301,6 +303,27 @@ def main():
     _, ev_a = time_region(torch, lambda i: layers[i % n_layers].append(stream), 2 * n_layers)
     append_us = ev_a / (2 * n_layers) * 1e6
 
+    # ---- the comparison the paper reports: attention over the whole cache ---------
+    dense = None
+    if not args.no_dense:
+        dws = [ts.new_dense_workspace(ly.layout, dev) for ly in layers]
+        scale = 1.0 / math.sqrt(spec.d)
+
+        def dense_call(i):
+            ly = layers[i % n_layers]
+            ts.dense_decode_attention(ly.layout, ly.w.q[0], scale, ly.out, dws[i % n_layers])
+
+        for i in range(n_layers):
+            dense_call(i)
+        n_dense = max(2 * n_layers, 4)
+        _, ev_d = time_region(torch, dense_call, n_dense)
+        dense_us = ev_d / n_dense * 1e6
+        dense = {"kernel": "ts_dense_decode_attention (every cached token, same pool and block table)",
+                 "us_per_launch": round(dense_us, 2),
+                 "GBps": round(by["dense"] / (dense_us * 1e-6) / 1e9, 1),
+                 "speedup_of_step_over_dense": round(dense_us / us_step, 2),
+                 "bytes_fraction_of_dense": round(by["total"] / by["dense"], 4)}
+
     result = {
         "metric": METRIC,
         "value": round(us_step, 3),
@@ -341,6 +364,8 @@ def main():
         "other_kernels_us": {"ts_build_page_meta": round(build_us, 2),
                              "ts_append_token_meta": round(append_us, 2)},
     }
+    if dense is not None:
+        result["dense_baseline"] = dense
     if not args.no_cpu_baseline:
         layers[0].reset_lengths()
         ts.build_page_meta(layers[0].layout)

@@ -165,6 +165,16 @@ int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void*
  * max_topk (0 on invalid arguments).  Reads only the scalar fields. */
 size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk);
 
+/* The comparison the paper measures against (the FullCache rows of its latency
+ * tables; Section 3.5 opens with this Attn(q_t, K, V) over the whole cache):
+ * single-query softmax attention over EVERY cached token of every sequence,
+ * through the same block table and pool layout, fp32 out [B][Hq][d].  Needs a
+ * workspace of its own size, ts_dense_workspace_bytes(layout) (host-only, 0 on
+ * an invalid layout), initialised with ts_workspace_init. */
+size_t ts_dense_workspace_bytes(const ts_layout* layout);
+int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Zeroes the whole workspace.  Required once after allocation (and after a
  * launch that was aborted); every call leaves the workspace ready for the
  * next, so repeated calls need no re-initialisation.  Calls sharing one

@@ -55,16 +55,22 @@ static int g_tune_splits = 0, g_tune_wg_per_cu = 0, g_tune_reserved = 0;
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-static Plan make_plan(const ts_layout* L, int max_topk) {
+// target_workgroups: about how many workgroups a launch should have.  The
+// query-aware path is latency-bound and wants one per compute unit; the dense
+// baseline streams the whole cache and wants several.
+constexpr int kDenseTargetWorkgroups = 1024;
+
+static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = kTargetWorkgroups) {
   Plan pl;
   const int G = L->num_q_heads / L->num_kv_heads;
   const int Pmax = L->max_pages_per_seq;
   pl.units = L->num_seqs * L->num_kv_heads;
-  int g = (kTargetWorkgroups + pl.units - 1) / pl.units;
+  int g = (target_workgroups + pl.units - 1) / pl.units;
   const int cap = (max_topk + 3) / 4;  // at least one page per wave
   if (g > cap) g = cap;
   if (g > kMaxCluster) g = kMaxCluster;
-  if (g_tune_splits > 0) g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
+  if (g_tune_splits > 0 && target_workgroups == kTargetWorkgroups)
+    g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
   if (g > max_topk) g = max_topk;
   if (g < 1) g = 1;
   pl.chunk = (max_topk + g - 1) / g;
@@ -201,13 +207,16 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
   const int u = blockIdx.y, b = u / p.Hkv, h = u % p.Hkv, split = blockIdx.x;
-  const int Kb = uniform(max(0, min(sel_count[b], p.Kmax)));
+  // sel == nullptr: the dense baseline, every page of the sequence in order
+  const int all = sel ? 0 : min((p.seq_lens[b] + S - 1) / S, p.Kmax);
+  const int Kb = uniform(sel ? max(0, min(sel_count[b], p.Kmax)) : all);
   const int c0 = min(split * p.chunk, Kb), count = min(c0 + p.chunk, Kb) - c0;
-  const int32_t* sel_row = sel + (size_t)u * p.Kmax + c0;
+  const int32_t* sel_row = sel ? sel + (size_t)u * p.Kmax + c0 : nullptr;
   const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
   const NewToken none{-1, 0, p.q, p.q};
   attend_split<D, S, true, false>(
-      p, b, h, split, count, p.seq_lens[b], none, [&](int i) { return sel_row[i]; },
+      p, b, h, split, count, p.seq_lens[b], none,
+      [&](int i) { return sel_row ? sel_row[i] : c0 + i; },
       [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
   if (p.n_split == 1) return;
   stores_complete();
@@ -847,18 +856,9 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
   return launch_status();
 }
 
-int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
-                               const int32_t* sel_count, int32_t max_topk, float softmax_scale,
-                               float* out, void* workspace, size_t workspace_bytes,
-                               void* stream) {
-  int st = check_layout(layout);
-  if (st != TS_OK) return st;
-  if (!q || !sel || !sel_count || !out || !workspace || !layout->k_pool || !layout->v_pool ||
-      !layout->block_table || !layout->seq_lens)
-    return TS_ERR_NULL;
-  if (max_topk < 1) return TS_ERR_SHAPE;
-  Plan pl = make_plan(layout, max_topk);
-  if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
+static int launch_attention(const ts_layout* layout, const Plan& pl, const void* q,
+                            const int32_t* sel, const int32_t* sel_count, int32_t max_topk,
+                            float softmax_scale, float* out, void* workspace, void* stream) {
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
   int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units * pl.cstride;
@@ -879,6 +879,40 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
     sparse_attention_kernel<128, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
                                                                pl.cstride);
   return launch_status();
+}
+
+int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
+                               const int32_t* sel_count, int32_t max_topk, float softmax_scale,
+                               float* out, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  int st = check_layout(layout);
+  if (st != TS_OK) return st;
+  if (!q || !sel || !sel_count || !out || !workspace || !layout->k_pool || !layout->v_pool ||
+      !layout->block_table || !layout->seq_lens)
+    return TS_ERR_NULL;
+  if (max_topk < 1) return TS_ERR_SHAPE;
+  const Plan pl = make_plan(layout, max_topk);
+  if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
+  return launch_attention(layout, pl, q, sel, sel_count, max_topk, softmax_scale, out, workspace,
+                          stream);
+}
+
+size_t ts_dense_workspace_bytes(const ts_layout* layout) {
+  if (check_layout(layout) != TS_OK) return 0;
+  return make_plan(layout, layout->max_pages_per_seq, kDenseTargetWorkgroups).total;
+}
+
+int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_layout(layout);
+  if (st != TS_OK) return st;
+  if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
+      !layout->seq_lens)
+    return TS_ERR_NULL;
+  const Plan pl = make_plan(layout, layout->max_pages_per_seq, kDenseTargetWorkgroups);
+  if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
+  return launch_attention(layout, pl, q, nullptr, nullptr, layout->max_pages_per_seq, softmax_scale,
+                          out, workspace, stream);
 }
 
 int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,

@@ -26,7 +26,7 @@ TS_ERR_DEVICE = -6
 EXPORTS = [
     "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
     "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_append_and_decode",
-    "ts_workspace_bytes",
+    "ts_dense_workspace_bytes", "ts_dense_decode_attention", "ts_workspace_bytes",
     "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
 ]
 
@@ -70,6 +70,9 @@ def lib():
         L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_append_and_decode.argtypes = [lp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_dense_workspace_bytes.argtypes = [lp]
+        L.ts_dense_workspace_bytes.restype = sz
+        L.ts_dense_decode_attention.argtypes = [lp, vp, f32, vp, vp, sz, vp]
         L.ts_workspace_bytes.argtypes = [lp, i32]
         L.ts_workspace_bytes.restype = sz
         L.ts_workspace_init.argtypes = [vp, sz, vp]
@@ -190,6 +193,21 @@ def append_and_decode(layout, k_new, v_new, q, topk, max_topk, softmax_scale, ou
         int(max_topk), float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out),
         _ptr(sel_count_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream()), "ts_append_and_decode")
+
+
+def new_dense_workspace(layout, device) -> torch.Tensor:
+    n = int(lib().ts_dense_workspace_bytes(ctypes.byref(layout)))
+    if n == 0:
+        raise TinyServeError(TS_ERR_SHAPE, "ts_dense_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    workspace_init(ws)
+    return ws
+
+
+def dense_decode_attention(layout, q, softmax_scale, out, workspace):
+    _check(lib().ts_dense_decode_attention(
+        ctypes.byref(layout), _ptr(q), float(softmax_scale), _ptr(out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream()), "ts_dense_decode_attention")
 
 
 def set_tuning(reserved=0, num_splits=0, workgroups_per_cu=0):

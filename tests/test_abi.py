@@ -96,6 +96,10 @@ def test_argument_validation():
                                     None, p, big, None) == ts.TS_ERR_NULL
     assert lib.ts_append_and_decode(ctypes.byref(lay), p, p, p, 4, None, 8, 1.0, p, None, None,
                                     None, p, 16, None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_dense_decode_attention(ctypes.byref(lay), p, 1.0, p, p, 16, None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_dense_decode_attention(ctypes.byref(lay), None, 1.0, p, p, big, None) == ts.TS_ERR_NULL
+    assert lib.ts_dense_workspace_bytes(ctypes.byref(lay)) > 0
+    assert lib.ts_dense_workspace_bytes(ctypes.byref(_layout(head_dim=96))) == 0
     assert lib.ts_workspace_init(None, 1024, None) == ts.TS_ERR_NULL
     assert lib.ts_workspace_init(p, 8, None) == ts.TS_ERR_WORKSPACE
     assert lib.ts_workspace_status(None, None) == ts.TS_ERR_NULL

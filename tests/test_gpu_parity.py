@@ -345,6 +345,31 @@ def test_query_sums_read_back_through_one_hot_boxes(built):
         assert torch.equal(sess.scores[:, :, :128], qp), f"launch {i}"
 
 
+@pytest.mark.parametrize("name", ["mha_d64_s16", "gqa8_d64_s32_walk", "mha_d128_s16_ragged",
+                                  "gqa4_d128_s32", "k_exceeds_p"])
+def test_dense_baseline_matches_oracle(oracle, built, name):
+    """ts_dense_decode_attention (attention over the whole cache, the comparison the
+    paper measures against) against the oracle's dense softmax attention."""
+    spec = REDUCED[name]
+    print(f"[case] dense {name}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=11, n_q=1)
+    sess = Session(w)
+    scale = 1.0 / math.sqrt(spec.d)
+    ws = ts.new_dense_workspace(sess.layout, DEV)
+    ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws)
+    torch.cuda.synchronize()
+    K, V = wl.logical_kv(w)
+    ref = oracle.dense_decode_attention(wl.bits(w.q[0]), wl.bits(K), wl.bits(V),
+                                        w.seq_lens.cpu().numpy(), scale)
+    err = np.abs(sess.out.cpu().numpy().astype(np.float64) - ref).max()
+    assert err <= 2e-3, f"dense attention off by {err}"
+    # a second call on the same workspace (counters left re-armed)
+    first = sess.out.clone()
+    ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, sess.out)
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
@@ -366,7 +391,7 @@ FULL = ["tiny", "gpt2_345m", "tinyllama", "longctx", "ragged"]
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_sampled(oracle, built, name):
-    """BASELINE workloads at full size, default launch shapes, sampled units."""
+    """The five benchmark workloads at full size, default launch shapes, sampled units."""
     spec = wl.SPECS[name]
     print(f"[case] full {name}", flush=True)
     w = wl.make_workload(spec, DEV, seed=1000 + FULL.index(name), n_q=2, n_new=1)
