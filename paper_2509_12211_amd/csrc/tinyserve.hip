@@ -5,6 +5,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "ts_attend.h"
 #include "ts_device.h"
 #include "ts_meta.h"
@@ -310,11 +314,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     epoch_raw = p.ctrl[kCtrlEpoch];
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
-    if (app) {
-      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
-      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
-      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
-    }
     scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
 #pragma unroll
@@ -322,6 +321,11 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
     scan_issue_tile<D>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
                        Pmax, member * kWaves + wave_id());
+    if (app) {  // last: first needed once the metadata is in, and loads return in order
+      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
+      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
+      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
+    }
   };
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
   TS_MARK(23);
@@ -398,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // count this workgroup in (once): it has read the epoch and, in append mode,
     // the sequence length
     if (!kLoop || exchange) {
-      if (arrived < 0 && threadIdx.x == 0 && (exchange || app))
+      if (arrived == -1 && threadIdx.x == 0 && (exchange || app))
         arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
     }
 
@@ -439,22 +443,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     select_begin(sl, tmin, tmax);
     __syncthreads();
     TS_MARK(4);
-    // the new token lands in its pool slot (one member's first lanes; the
-    // block-table row is complete in LDS by now).  Nothing in this launch reads
-    // it from there: the attention splices it in from the caller's arrays.
-    if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
-      const int phys = bt_lds[j_new];
-      if (phys >= 0 && phys < at.n_phys) {
-        const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
-        *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
-        const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
-              (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
-      }
-    }
-
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
     int32_t* sel_row = (p.sel_out && member == 0) ? p.sel_out + (size_t)u * at.Kmax : nullptr;
@@ -467,6 +455,24 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     });
     __syncthreads();
     TS_MARK(5);
+    // The workgroup that counted itself in last knows that every other one has
+    // read the epoch word and, with one unit per workgroup, its sequence length:
+    // its first wave re-arms the count, advances the epoch and (append mode)
+    // the lengths, here where the count's return has long arrived and nothing
+    // waits for the few stores.
+    if (wave_id() == 0 && uniform(arrived) == (int)gridDim.x - 1) {
+      arrived = -2;
+      if (lane_id() == 0) {
+        atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
+        if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+      }
+      if (app && !kLoop) {
+        for (int i = lane_id(); i < p.B; i += kWave) {
+          const int len = p.seq_lens_w[i];
+          if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
+        }
+      }
+    }
 
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     const size_t new_row = ((size_t)b * at.Hkv + h) * D;
@@ -493,6 +499,21 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       }
       __syncthreads();
     }
+    // the new token lands in its pool slot (one member's first lanes).  Nothing
+    // in this launch reads it from there (the attention splices it in from the
+    // caller's arrays), so it is done here, off the path to the result.
+    if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
+      const int phys = bt_lds[j_new];
+      if (phys >= 0 && phys < at.n_phys) {
+        const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
+        *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
+        const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
+              (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
+      }
+    }
     if (!kLoop) break;
     if (dynamic) {
       __syncthreads();
@@ -506,27 +527,14 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (u >= p.units) break;
     issue_unit(u);
   }
-  // Append mode: the sequence lengths advance once every workgroup is past its
-  // last read of them.  With one unit per workgroup that is known to the
-  // workgroup that counted itself in last (all the others had read theirs by
-  // then); with several units per workgroup, to the last workgroup to finish.
+  // Append mode with several units per workgroup: the lengths advance when the
+  // last workgroup finishes.
   auto advance_lengths = [&] {
     for (int i = threadIdx.x; i < p.B; i += kThreads) {
       const int len = p.seq_lens_w[i];
       if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
     }
   };
-  __syncthreads();
-  if (threadIdx.x == 0) s_flag = arrived == (int)gridDim.x - 1;
-  __syncthreads();
-  const bool counted_in_last = uniform(s_flag) != 0;
-  if (counted_in_last) {
-    if (threadIdx.x == 0) {
-      atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
-      if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
-    }
-    if (app && !kLoop) advance_lengths();
-  }
   if (dynamic || (kLoop && app)) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();
     if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1;
@@ -594,13 +602,23 @@ static int allow_lds(KernelT kernel, size_t bytes) {
              : TS_ERR_LAUNCH;
 }
 
-// Workgroups of `kernel` that can be resident on the whole device at once.
+// Workgroups of `kernel` that can be resident on the whole device at once.  The
+// runtime's answer is remembered per (kernel, LDS size): the query costs more
+// host time than the launch itself.
 template <typename KernelT>
 static int resident_capacity(KernelT kernel, size_t lds) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, size_t>, int> known;
+  const std::pair<const void*, size_t> key(reinterpret_cast<const void*>(kernel), lds);
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = known.find(key);
+  if (it != known.end()) return it->second;
   int per_cu = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, lds) != hipSuccess)
     return 0;
-  return per_cu * num_compute_units();
+  const int cap = per_cu * num_compute_units();
+  if (cap > 0) known[key] = cap;
+  return cap;
 }
 
 static MetaParams meta_params(const ts_layout* L) {
@@ -729,7 +747,7 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
 
 extern "C" {
 
-int ts_version(void) { return 2; }
+int ts_version(void) { return 3; }
 
 #ifdef TS_PROFILE
 int ts_debug_set_profile_buffer(void* buf) {

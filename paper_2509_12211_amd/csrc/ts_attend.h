@@ -258,8 +258,12 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 
   short4_t qf[D / 16];
   load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  // The new token's page is the sequence's last, so in the ascending list it can
+  // only be the very last entry: one wave of one workgroup ever needs the token.
   TokenPatch<D, S> patch;
-  if (kPatch) patch.load(nt);
+  const bool splice = kPatch && nt.j >= 0 && count > 0 && wave == (count - 1) % kWaves &&
+                      uniform(sel_at(count - 1)) == nt.j;
+  if (splice) patch.load(nt);
   WaveAcc<D> acc;
   acc.init();
 
@@ -299,7 +303,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
         if (x0 + i < n) {
-          if (kPatch && nt.j >= 0 && page[i] == nt.j) patch.apply(f[i], nt.slot);
+          if (splice && page[i] == nt.j) patch.apply(f[i], nt.slot);
           attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
         }
         if (kBranchless || x0 + i + NBUF < n) valid[i] = issue(f[i], page[i], x0 + i + NBUF);
