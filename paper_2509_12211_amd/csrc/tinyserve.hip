@@ -73,6 +73,11 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   const int cap = (max_topk + 3) / 4;  // at least one page per wave
   if (g > cap) g = cap;
   if (g > kMaxCluster) g = kMaxCluster;
+  // Short sequences: a cluster's exchange and merge (a few microseconds of
+  // waiting on the slowest member) cost more than one workgroup needs to score
+  // ~600 pages and attend ~80 by itself (measured on the 256- and 512-page
+  // configurations).
+  if (target_workgroups == kTargetWorkgroups && Pmax <= 640 && max_topk <= 80) g = 1;
   if (g_tune_splits > 0 && target_workgroups == kTargetWorkgroups)
     g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
   if (g > max_topk) g = max_topk;
@@ -362,7 +367,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           // (the empty asm pins the first use of the two values to this point:
           // using them earlier would put a memory round trip in front of the scan)
           asm volatile("" : "+v"(L_raw), "+v"(K_raw), "+v"(epoch_raw));
-          tag = (uint32_t)uniform(epoch_raw) + 1u;
+          // the tag is fixed by the first unit: the epoch word may already have
+          // been advanced (by the workgroup that counted itself in last) when a
+          // later unit's loads go out
+          if (tag == 0u) tag = (uint32_t)uniform(epoch_raw) + 1u;
           L_unit = uniform(L_raw);
           if (app && L_unit / S < Pmax) {  // a sequence with no room left is not extended
             j_new = L_unit / S;

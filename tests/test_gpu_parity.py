@@ -109,11 +109,21 @@ def built():
     return True
 
 
+@pytest.fixture
+def splits(request):
+    """Workgroups per (sequence, KV head): 0 = the library's own choice (a single
+    workgroup for sequences this short), otherwise a forced cluster size."""
+    ts.set_tuning(0, request.param, 0)
+    yield request.param
+    ts.set_tuning(0, 0, 0)
+
+
 @pytest.mark.parametrize("name", list(REDUCED))
-@pytest.mark.parametrize("scale_mode", ["rsqrt_d", "one"])
-def test_reduced_all_units(oracle, built, name, scale_mode):
+@pytest.mark.parametrize("scale_mode,splits", [("rsqrt_d", 0), ("one", 3), ("rsqrt_d", 8)],
+                         indirect=["splits"])
+def test_reduced_all_units(oracle, built, name, scale_mode, splits):
     spec = REDUCED[name]
-    print(f"[case] reduced {name} scale={scale_mode}", flush=True)
+    print(f"[case] reduced {name} scale={scale_mode} splits={splits}", flush=True)
     # paper-literal scale runs on two dense pools, the usual one on the interleaved K|V pool
     w = wl.make_workload(spec, DEV, seed=2000 + len(name), n_q=2,
                          interleave=(scale_mode == "rsqrt_d"))
@@ -239,12 +249,13 @@ def _bits_equal(a, b):
 
 
 @pytest.mark.parametrize("name", list(APPEND_FUSED))
-def test_append_and_decode_equals_separate_calls(oracle, built, name):
+@pytest.mark.parametrize("splits", [0, 2, 5], indirect=True)
+def test_append_and_decode_equals_separate_calls(oracle, built, name, splits):
     """ts_append_and_decode == ts_append_token_meta followed by ts_query_aware_decode:
     same outputs, same metadata, same pool contents, same lengths, step after step
     across page boundaries, including a sequence that runs out of room."""
     spec = APPEND_FUSED[name]
-    print(f"[case] append+decode {name}", flush=True)
+    print(f"[case] append+decode {name} splits={splits}", flush=True)
     n_new = 36
     scale = 1.0 / math.sqrt(spec.d)
     sessions = []
