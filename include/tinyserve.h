@@ -154,12 +154,20 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
  * the scoring, selection and attention of this same call, and seq_lens[b] is
  * advanced by one before the call completes.  A sequence whose new page would
  * be >= P_max is left unchanged.  The block-table entry of the page that
- * receives the token must be valid. */
+ * receives the token must be valid.  It is a single launch whenever all
+ * (sequence, KV head) units are worked on at once (up to one per compute unit);
+ * for larger batches, which are bound by bandwidth, the append is enqueued as a
+ * kernel of its own in front of the decode on the same stream. */
 int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,
                          const void* q, int32_t topk, const int32_t* topk_per_seq,
                          int32_t max_topk, float softmax_scale, float* out, float* scores_out,
                          int32_t* sel_out, int32_t* sel_count_out, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/* Host-only (needs the device to be present): 1 if ts_append_and_decode runs
+ * this layout as a single launch, 2 if it enqueues the append as a kernel of
+ * its own first; a negative ts_status on error. */
+int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk);
 
 /* Host-only: bytes of workspace the three calls above need for this layout and
  * max_topk (0 on invalid arguments).  Reads only the scalar fields. */

@@ -271,6 +271,7 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 // (ts_append_and_decode); the plain build carries none of its registers.
 template <int D, int S, bool kLoop, bool kApp>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
+  static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_flag;
   TS_MARK_INIT();
@@ -451,6 +452,26 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     select_begin(sl, tmin, tmax);
     __syncthreads();
     TS_MARK(4);
+    // The new token lands in its pool slot (one member's first lanes; the
+    // block-table row is complete in LDS once the barrier above is passed).
+    // Nothing in this launch reads it from there: the attention splices it in
+    // from the caller's arrays, so it is done at the very end of the unit, off
+    // the path to the result.
+    auto store_new_token = [&] {
+      if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
+        const int phys = bt_lds[j_new];
+        if (phys >= 0 && phys < at.n_phys) {
+          const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
+          *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
+          const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
+                (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
+        }
+      }
+    };
+
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
     int32_t* sel_row = (p.sel_out && member == 0) ? p.sel_out + (size_t)u * at.Kmax : nullptr;
@@ -474,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
         atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
         if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
       }
-      if (app && !kLoop) {
+      if (app) {
         for (int i = lane_id(); i < p.B; i += kWave) {
           const int len = p.seq_lens_w[i];
           if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
@@ -507,21 +528,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       }
       __syncthreads();
     }
-    // the new token lands in its pool slot (one member's first lanes).  Nothing
-    // in this launch reads it from there (the attention splices it in from the
-    // caller's arrays), so it is done here, off the path to the result.
-    if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
-      const int phys = bt_lds[j_new];
-      if (phys >= 0 && phys < at.n_phys) {
-        const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
-        *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
-        const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
-              (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
-      }
-    }
+    if (kApp) store_new_token();
     if (!kLoop) break;
     if (dynamic) {
       __syncthreads();
@@ -535,24 +542,11 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (u >= p.units) break;
     issue_unit(u);
   }
-  // Append mode with several units per workgroup: the lengths advance when the
-  // last workgroup finishes.
-  auto advance_lengths = [&] {
-    for (int i = threadIdx.x; i < p.B; i += kThreads) {
-      const int len = p.seq_lens_w[i];
-      if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
-    }
-  };
-  if (dynamic || (kLoop && app)) {  // the last workgroup out re-arms the counters for the next launch
+  if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();
-    if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1;
-    __syncthreads();
-    if (uniform(s_flag)) {
-      if (threadIdx.x == 0) {
-        atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
-        atomic_store_agent(&p.ctrl[kCtrlExit], 0);
-      }
-      if (app) advance_lengths();
+    if (threadIdx.x == 0 && atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
+      atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
+      atomic_store_agent(&p.ctrl[kCtrlExit], 0);
     }
   }
 }
@@ -717,37 +711,48 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-#define TS_LAUNCH_FUSED(DD, SS, APP)                                                          \
+  // One unit per cluster and everything resident: the loop-free build, which
+  // also exists with the append folded in.  Otherwise (thousands of units, bound
+  // by bandwidth) the looping build; an append then runs as a launch of its own
+  // in front of it: the looping build has no registers to spare for it, and
+  // against hundreds of microseconds the extra launch does not count.
+#define TS_LAUNCH_FUSED(DD, SS)                                                               \
   do {                                                                                        \
-    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true, APP>, pl.lds_fused)) !=       \
+    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true, false>, pl.lds_fused)) !=     \
             TS_OK ||                                                                          \
-        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, APP>, pl.lds_fused)) != TS_OK) \
+        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, false>, pl.lds_fused)) !=    \
+            TS_OK ||                                                                          \
+        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, true>, pl.lds_fused)) != TS_OK) \
       return st;                                                                              \
-    int cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false, APP>, pl.lds_fused); \
+    int cap1 = k_new ? resident_capacity(query_aware_decode_kernel<DD, SS, false, true>,      \
+                                         pl.lds_fused)                                        \
+                     : resident_capacity(query_aware_decode_kernel<DD, SS, false, false>,     \
+                                         pl.lds_fused);                                       \
     if (cap1 > cus * per_cu) cap1 = cus * per_cu;                                             \
     if (pl.units * pl.g <= cap1) { /* one unit per cluster */                                 \
-      query_aware_decode_kernel<DD, SS, false, APP>                                           \
-          <<<(unsigned)(pl.units * pl.g), kThreads, pl.lds_fused, s>>>(p);                    \
+      const unsigned grid = (unsigned)(pl.units * pl.g);                                      \
+      if (k_new)                                                                              \
+        query_aware_decode_kernel<DD, SS, false, true><<<grid, kThreads, pl.lds_fused, s>>>(p); \
+      else                                                                                    \
+        query_aware_decode_kernel<DD, SS, false, false><<<grid, kThreads, pl.lds_fused, s>>>(p); \
       break;                                                                                  \
     }                                                                                         \
-    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true, APP>, pl.lds_fused);  \
+    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true, false>, pl.lds_fused); \
     if (cap > cus * per_cu) cap = cus * per_cu;                                               \
     int clusters = cap / pl.g;                                                                \
     if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */               \
     if (clusters > pl.units) clusters = pl.units;                                             \
-    query_aware_decode_kernel<DD, SS, true, APP>                                              \
+    if (k_new) {                                                                              \
+      if ((st = ts_append_token_meta(layout, k_new, v_new, 1, stream)) != TS_OK) return st;   \
+      p.k_new = p.v_new = nullptr;                                                            \
+    }                                                                                         \
+    query_aware_decode_kernel<DD, SS, true, false>                                            \
         <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                      \
   } while (0)
-#define TS_LAUNCH_FUSED_DS(APP)                            \
-  do {                                                     \
-    if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16, APP);  \
-    else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32, APP);   \
-    else if (D == 128 && S == 16) TS_LAUNCH_FUSED(128, 16, APP); \
-    else TS_LAUNCH_FUSED(128, 32, APP);                    \
-  } while (0)
-  if (k_new) TS_LAUNCH_FUSED_DS(true);
-  else TS_LAUNCH_FUSED_DS(false);
-#undef TS_LAUNCH_FUSED_DS
+  if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16);
+  else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32);
+  else if (D == 128 && S == 16) TS_LAUNCH_FUSED(128, 16);
+  else TS_LAUNCH_FUSED(128, 32);
 #undef TS_LAUNCH_FUSED
   return launch_status();
 }
@@ -939,6 +944,29 @@ int ts_dense_decode_attention(const ts_layout* layout, const void* q, float soft
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
   return launch_attention(layout, pl, q, nullptr, nullptr, layout->max_pages_per_seq, softmax_scale,
                           out, workspace, stream);
+}
+
+int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
+  const int st = check_layout(layout);
+  if (st != TS_OK) return st;
+  if (max_topk < 1) return TS_ERR_SHAPE;
+  const Plan pl = make_plan(layout, max_topk);
+  const int cus = num_compute_units();
+  if (cus <= 0) return TS_ERR_DEVICE;
+  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
+  const int D = layout->head_dim, S = layout->page_size;
+  int cap1;
+  if (D == 64 && S == 16)
+    cap1 = resident_capacity(query_aware_decode_kernel<64, 16, false, true>, pl.lds_fused);
+  else if (D == 64 && S == 32)
+    cap1 = resident_capacity(query_aware_decode_kernel<64, 32, false, true>, pl.lds_fused);
+  else if (D == 128 && S == 16)
+    cap1 = resident_capacity(query_aware_decode_kernel<128, 16, false, true>, pl.lds_fused);
+  else
+    cap1 = resident_capacity(query_aware_decode_kernel<128, 32, false, true>, pl.lds_fused);
+  if (cap1 <= 0) return TS_ERR_DEVICE;
+  if (cap1 > cus * per_cu) cap1 = cus * per_cu;
+  return pl.units * pl.g <= cap1 ? 1 : 2;
 }
 
 int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,

@@ -26,7 +26,7 @@ TS_ERR_DEVICE = -6
 EXPORTS = [
     "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
     "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_append_and_decode",
-    "ts_dense_workspace_bytes", "ts_dense_decode_attention", "ts_workspace_bytes",
+    "ts_append_and_decode_launches", "ts_dense_workspace_bytes", "ts_dense_decode_attention", "ts_workspace_bytes",
     "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
 ]
 
@@ -70,6 +70,7 @@ def lib():
         L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_append_and_decode.argtypes = [lp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_append_and_decode_launches.argtypes = [lp, i32]
         L.ts_dense_workspace_bytes.argtypes = [lp]
         L.ts_dense_workspace_bytes.restype = sz
         L.ts_dense_decode_attention.argtypes = [lp, vp, f32, vp, vp, sz, vp]
@@ -208,6 +209,13 @@ def dense_decode_attention(layout, q, softmax_scale, out, workspace):
     _check(lib().ts_dense_decode_attention(
         ctypes.byref(layout), _ptr(q), float(softmax_scale), _ptr(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream()), "ts_dense_decode_attention")
+
+
+def append_and_decode_launches(layout, max_topk) -> int:
+    n = int(lib().ts_append_and_decode_launches(ctypes.byref(layout), int(max_topk)))
+    if n < 0:
+        raise TinyServeError(n, "ts_append_and_decode_launches")
+    return n
 
 
 def set_tuning(reserved=0, num_splits=0, workgroups_per_cu=0):

@@ -269,6 +269,8 @@ def test_append_and_decode_equals_separate_calls(oracle, built, name, splits):
         ts.build_page_meta(sess.layout)
         sessions.append(sess)
     a, f = sessions
+    single = spec.B * spec.Hkv * max(splits, 1) <= 256
+    assert ts.append_and_decode_launches(f.layout, f.w.K_max) == (1 if single else 2)
     units = [(b, h) for b in range(min(spec.B, 6)) for h in range(spec.Hkv)]
     for i in range(n_new):
         ts.append_token_meta(a.layout, a.w.k_new[i], a.w.v_new[i], advance_seq_lens=True)
@@ -313,6 +315,7 @@ def test_many_units_loop_build(oracle, built, name):
     scale = 1.0 / math.sqrt(spec.d)
     n_units = spec.B * spec.Hkv
     assert n_units > 256
+    assert ts.append_and_decode_launches(sess.layout, w.K_max) == 2   # append runs on its own
     rng = np.random.default_rng(9)
     picks = sorted(set(rng.integers(0, n_units, 10).tolist()) | {0, 255, 256, n_units - 1})
     units = [(u // spec.Hkv, u % spec.Hkv) for u in picks]
