@@ -229,8 +229,13 @@ def main():
 
     launch = args.launch
 
+    # steps per captured graph: whole rotations over the layers, at least 8 steps (a
+    # graph of one or two kernels would be timed by its own launch overhead)
+    per_graph = n_layers * max(1, -(-8 // n_layers))
+
     def capture(body):
-        """Capture one rotation over the layers (kernel nodes only, no memset nodes)."""
+        """Capture per_graph steps, rotating over the layers (kernel nodes only, no memset
+        nodes)."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -240,8 +245,8 @@ def main():
             side.synchronize()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                for i in range(n_layers):
-                    body(layers[i], gstream)
+                for i in range(per_graph):
+                    body(layers[i % n_layers], gstream)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         return g
@@ -271,9 +276,9 @@ def main():
 
     # ---- timed region: exactly `steps` steps -------------------------------------
     if graph is not None:
-        reps_w = max(1, warmup // n_layers)
-        reps = max(1, steps // n_layers)
-        steps, warmup = reps * n_layers, reps_w * n_layers
+        reps_w = max(1, warmup // per_graph)
+        reps = max(1, steps // per_graph)
+        steps, warmup = reps * per_graph, reps_w * per_graph
         for _ in range(reps_w):
             graph.replay()
         wall, ev = time_region(torch, lambda i: graph.replay(), reps)
@@ -289,7 +294,7 @@ def main():
     n_roof = steps
     if graph_fused is not None:
         graph_fused.replay()
-        _, ev_fused = time_region(torch, lambda i: graph_fused.replay(), n_roof // n_layers)
+        _, ev_fused = time_region(torch, lambda i: graph_fused.replay(), n_roof // per_graph)
     else:
         for i in range(min(warmup, 2 * n_layers)):
             fused_only(i)

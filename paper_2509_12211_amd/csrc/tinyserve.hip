@@ -128,18 +128,6 @@ struct FusedParams {
   int topk, S, units, g, cstride, B;
 };
 
-// Element-wise box update of eight packed bf16: lo = k where k < lo, hi = k
-// where k > hi (strict, as the stand-alone append kernel does it).
-__device__ __forceinline__ uint32_t widen_pair(uint32_t box, uint32_t k, bool is_min) {
-  const float bl = bf16_lo(box), bh = bf16_hi(box), kl = bf16_lo(k), kh = bf16_hi(k);
-  const bool tl = is_min ? kl < bl : kl > bl, th = is_min ? kh < bh : kh > bh;
-  return ((tl ? k : box) & 0x0000ffffu) | ((th ? k : box) & 0xffff0000u);
-}
-__device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, bool is_min) {
-  return make_uint4(widen_pair(box.x, k.x, is_min), widen_pair(box.y, k.y, is_min),
-                    widen_pair(box.z, k.z, is_min), widen_pair(box.w, k.w, is_min));
-}
-
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
 
 // ---------------------------------------------------------------------------

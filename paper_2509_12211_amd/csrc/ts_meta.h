@@ -68,50 +68,63 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
   }
 }
 
-// One workgroup per sequence: every (KV head, channel) of the new token widens
-// (or opens) the box of page seq_len / S and, when v_new is given, lands in its
-// pool slot.  The kernel is a chain of dependent memory round trips, so it is
-// arranged to need only two: the token's values (which do not depend on the
-// length) go out together with the length, then the block-table entry and the
-// old box together.  All threads read seq_lens[b] before the barrier; thread 0
-// advances it after.
+// Element-wise box update of eight packed bf16: lo = k where k < lo, hi = k
+// where k > hi (strict, as the stand-alone append kernel does it).
+__device__ __forceinline__ uint32_t widen_pair(uint32_t box, uint32_t k, bool is_min) {
+  const float bl = bf16_lo(box), bh = bf16_hi(box), kl = bf16_lo(k), kh = bf16_hi(k);
+  const bool tl = is_min ? kl < bl : kl > bl, th = is_min ? kh < bh : kh > bh;
+  return ((tl ? k : box) & 0x0000ffffu) | ((th ? k : box) & 0xffff0000u);
+}
+__device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, bool is_min) {
+  return make_uint4(widen_pair(box.x, k.x, is_min), widen_pair(box.y, k.y, is_min),
+                    widen_pair(box.z, k.z, is_min), widen_pair(box.w, k.w, is_min));
+}
+
+// One workgroup per sequence.  A thread takes eight channels of one KV head at a
+// time: it widens (or opens) the 16-byte chunk of the box of page seq_len / S
+// and, when v_new is given, puts the token into its pool slot (one 16-byte store
+// for the key; the value tile is channel-major, so eight 2-byte stores).  The
+// kernel is a chain of dependent memory round trips, arranged to need only two:
+// the token's values (which do not depend on the length) go out together with
+// the length, then the block-table entry and the old box together.  All threads
+// read seq_lens[b] before the barrier; thread 0 advances it after.
 __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams p, int D,
                                                                       const uint16_t* k_new,
                                                                       const uint16_t* v_new,
                                                                       int advance) {
-  const int b = blockIdx.x, n = p.Hkv * D;
-  const size_t row = (size_t)b * n;  // [Hkv][D] values of this sequence's token
-  const int first = min((int)threadIdx.x, n - 1);
-  uint16_t kn = k_new[row + first];
-  uint16_t vn = v_new ? v_new[row + first] : (uint16_t)0;
+  const int b = blockIdx.x, n8 = p.Hkv * D / 8, cpr = D / 8;   // chunks, chunks per head row
+  const uint4* k_src = reinterpret_cast<const uint4*>(k_new + (size_t)b * p.Hkv * D);
+  const uint4* v_src = reinterpret_cast<const uint4*>((v_new ? v_new : k_new) + (size_t)b * p.Hkv * D);
+  const int first = min((int)threadIdx.x, n8 - 1);
+  const uint4 k0 = k_src[first], v0 = v_src[first];   // fetched ahead of the length
   const int L = p.seq_lens[b];
   const int sh = __builtin_ctz(p.S);  // page sizes are powers of two
   const int j = L >> sh, slot = L & (p.S - 1);
   const bool fits = j < p.Pmax;
   const int jc = fits ? j : 0;
   const int phys = p.block_table[(size_t)b * p.Pmax + jc];
-  bool ok = fits;
-  for (int idx = threadIdx.x; idx < n; idx += kThreads) {
-    if (idx != (int)threadIdx.x) {
-      kn = k_new[row + idx];
-      vn = v_new ? v_new[row + idx] : (uint16_t)0;
-    }
-    const int h = idx / D, c = idx % D;
-    const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + jc) * D + c;
-    const uint16_t lo = p.page_min[m], hi = p.page_max[m];  // fetched before phys is looked at
-    ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
+  for (int i0 = threadIdx.x; i0 < n8; i0 += kThreads) {
+    const int h = i0 / cpr, c8 = (i0 % cpr) * 8;
+    const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + jc) * D + c8;
+    const uint4 lo = *reinterpret_cast<const uint4*>(p.page_min + m);   // before phys is looked at
+    const uint4 hi = *reinterpret_cast<const uint4*>(p.page_max + m);
+    const uint4 kn = i0 == (int)threadIdx.x ? k0 : k_src[i0];
+    const uint4 vn = i0 == (int)threadIdx.x ? v0 : v_src[i0];
+    const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
     if (ok) {
-      const float x = bf16_to_f32(kn);
-      if (slot == 0 || x < bf16_to_f32(lo)) p.page_min[m] = kn;
-      if (slot == 0 || x > bf16_to_f32(hi)) p.page_max[m] = kn;
+      *reinterpret_cast<uint4*>(p.page_min + m) = slot == 0 ? kn : widen_box(lo, kn, true);
+      *reinterpret_cast<uint4*>(p.page_max + m) = slot == 0 ? kn : widen_box(hi, kn, false);
       if (v_new != nullptr) {
         const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
-        p.k_pool_w[tile + (size_t)slot * D + c] = kn;
-        p.v_pool_w[tile + (size_t)c * p.S + slot] = vn;
+        *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot * D + c8) = kn;
+        const uint32_t vw[4] = {vn.x, vn.y, vn.z, vn.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          p.v_pool_w[tile + (size_t)(c8 + i) * p.S + slot] = (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
       }
     }
   }
-  ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
+  const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
   __syncthreads();
   if (ok && advance && threadIdx.x == 0) p.seq_lens[b] = L + 1;
 }
