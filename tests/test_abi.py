@@ -30,6 +30,15 @@ def test_library_exports_every_declared_symbol():
     assert "workspace" in ts.strerror(ts.TS_ERR_WORKSPACE)
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "tinyserve.h"\nint main(void) { ts_layout l; (void)l; return TS_OK; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
+
+
 def _layout(**kw):
     base = dict(num_seqs=2, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16,
                 max_pages_per_seq=64, num_phys_pages=128, kv_tile_stride=0,

@@ -384,6 +384,57 @@ def test_dense_baseline_matches_oracle(oracle, built, name):
     assert torch.equal(first, sess.out)
 
 
+@pytest.mark.parametrize("splits", [0, 4], indirect=True)
+def test_graph_replays_match_eager(built, splits):
+    """A captured HIP graph of decode steps (the form bench.py times) replayed several
+    times, with eager work and synchronisations in between: every replay must equal
+    the same steps issued eagerly on a twin.  The launch tag of the score exchange is
+    device state for exactly this reason (kernel arguments are frozen in a graph)."""
+    print(f"[case] graph replay splits={splits}", flush=True)
+    spec = wl.WorkloadSpec("graph", 3, 8, 2, 64, 16, 1200, 10, keys="offset", headroom=160)
+    scale = 1.0 / math.sqrt(spec.d)
+    twins = []
+    for _ in range(2):
+        w = wl.make_workload(spec, DEV, seed=21, n_q=2, n_new=2, poison=0.0)
+        sess = Session(w, poison_meta=False)
+        ts.build_page_meta(sess.layout)
+        twins.append(sess)
+    e, g = twins
+
+    def steps(sess):     # two decode steps: one launch each, then a plain fused call
+        w = sess.w
+        ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[0], w.topk, w.K_max, scale,
+                             sess.out, sess.ws)
+        ts.append_and_decode(sess.layout, w.k_new[1], w.v_new[1], w.q[1], w.topk, w.K_max, scale,
+                             sess.out, sess.ws)
+        ts.query_aware_decode(sess.layout, w.q[0], w.topk, w.K_max, scale, sess.out, sess.ws,
+                              scores_out=sess.scores, sel_out=sess.sel,
+                              sel_count_out=sess.sel_count)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        steps(g)                       # warm-up on the capture stream (also advances g)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            steps(g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    steps(e)                           # e catches up with the warm-up
+    for r in range(5):
+        graph.replay()
+        steps(e)
+        torch.cuda.synchronize()
+        assert ts.workspace_status(g.ws) == 0 and ts.workspace_status(e.ws) == 0
+        assert torch.equal(e.seq_lens, g.seq_lens), f"replay {r}"
+        assert torch.equal(e.sel, g.sel) and torch.equal(e.scores, g.scores), f"replay {r}"
+        assert _bits_equal(e.page_min, g.page_min) and _bits_equal(e.w.k_pool, g.w.k_pool)
+        assert (e.out - g.out).abs().max().item() <= 1e-6, f"replay {r}"
+        # unrelated eager work between replays
+        torch.empty(1 << 20, device=DEV).normal_().sum().item()
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
