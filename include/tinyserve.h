@@ -139,7 +139,14 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
 /* Algorithm 1 as ONE kernel launch: score -> select -> gather -> attend.
  * Arguments as in the three staged calls.  scores_out (fp32 [B][Hkv][P_max]),
  * sel_out (int32 [B][Hkv][max_topk]) and sel_count_out (int32 [B]) are
- * optional (NULL = not reported). */
+ * optional (NULL = not reported).
+ * With few (sequence, KV head) units the kernel spreads each over several
+ * workgroups that exchange data while running, and sizes its grid so that all
+ * of them are resident at once on an otherwise idle device.  If other kernels
+ * occupy compute units at the same time, a workgroup may wait for a partner
+ * that cannot start; every such wait is bounded (about a second), after which
+ * the launch finishes with invalid results and ts_workspace_status reports
+ * non-zero.  It never hangs. */
 int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           const int32_t* topk_per_seq, int32_t max_topk, float softmax_scale,
                           float* out, float* scores_out, int32_t* sel_out,
