@@ -118,13 +118,11 @@ struct FusedParams {
   int32_t* ctrl;        // control words
   int32_t* attend_done; // [units * cstride]
   // One token per sequence appended by the same launch (k_new == nullptr: none).
+  // (the pool, the metadata and the lengths are then written through the
+  // pointers above: the caller's buffers are writable, the const is this
+  // library's view of them in the calls that only read)
   const uint16_t* k_new;   // [B][Hkv][D]
   const uint16_t* v_new;
-  uint16_t* k_pool_w;
-  uint16_t* v_pool_w;
-  uint16_t* page_min_w;
-  uint16_t* page_max_w;
-  int32_t* seq_lens_w;
   int topk, S, units, g, cstride, B;
 };
 
@@ -309,17 +307,17 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
     scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
+    if (app) {  // behind the query (needed first), ahead of the metadata (needed with it)
+      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
+      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
+      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
+    }
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
 #pragma unroll
     for (int k = 0; k < kBtRegs; ++k)   // no branch around the loads
       bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
     scan_issue_tile<D>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
                        Pmax, member * kWaves + wave_id());
-    if (app) {  // last: first needed once the metadata is in, and loads return in order
-      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
-      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
-      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
-    }
   };
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
   TS_MARK(23);
@@ -372,13 +370,15 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
         },
         [&](uint4& mn, uint4& mx, int pg) {
           // the wave that scores the new token's page first widens (or opens)
-          // its box, in registers and in memory
-          if (pg == j_new) {
+          // its box, in registers and in memory (the outer test is uniform over
+          // the wave: all the others jump over the block instead of executing
+          // it with every lane masked off)
+          if (__ballot(pg == j_new) != 0ull && pg == j_new) {
             mn = slot_new == 0 ? kn16 : widen_box(mn, kn16, true);
             mx = slot_new == 0 ? kn16 : widen_box(mx, kn16, false);
             const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
-            *reinterpret_cast<uint4*>(p.page_min_w + row) = mn;
-            *reinterpret_cast<uint4*>(p.page_max_w + row) = mx;
+            *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_min) + row) = mn;
+            *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_max) + row) = mx;
           }
         },
         [&](int pg, float s) {
@@ -443,22 +443,28 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // The new token lands in its pool slot (one member's first lanes; the
     // block-table row is complete in LDS once the barrier above is passed).
     // Nothing in this launch reads it from there: the attention splices it in
-    // from the caller's arrays, so it is done at the very end of the unit, off
-    // the path to the result.
+    // from the caller's arrays.  It is done now rather than at the end (stores
+    // issued last would hold up the completion of the kernel), by the first
+    // lanes of the last wave (the first wave carries the workgroup's atomics).
     auto store_new_token = [&] {
-      if (j_new >= 0 && member == 0 && (int)threadIdx.x < LPR) {
+      const int t = (int)threadIdx.x - (kThreads - kWave);
+      if (j_new >= 0 && member == 0 && t >= 0 && t < LPR) {
         const int phys = bt_lds[j_new];
         if (phys >= 0 && phys < at.n_phys) {
           const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
-          *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot_new * D + threadIdx.x * 8) = kn16;
+          uint16_t* k_pool_w = const_cast<uint16_t*>(at.k_pool);
+          uint16_t* v_pool_w = const_cast<uint16_t*>(at.v_pool);
+          *reinterpret_cast<uint4*>(k_pool_w + tile + (size_t)slot_new * D + t * 8) = kn16;
           const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
 #pragma unroll
           for (int i = 0; i < 8; ++i)
-            p.v_pool_w[tile + (size_t)(threadIdx.x * 8 + i) * S + slot_new] =
+            v_pool_w[tile + (size_t)(t * 8 + i) * S + slot_new] =
                 (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
         }
       }
     };
+
+    if (kApp) store_new_token();
 
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
@@ -484,9 +490,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
         if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
       }
       if (app) {
+        int32_t* seq_lens_w = const_cast<int32_t*>(at.seq_lens);
         for (int i = lane_id(); i < p.B; i += kWave) {
-          const int len = p.seq_lens_w[i];
-          if (len / S < Pmax) p.seq_lens_w[i] = len + 1;
+          const int len = seq_lens_w[i];
+          if (len / S < Pmax) seq_lens_w[i] = len + 1;
         }
       }
     }
@@ -516,7 +523,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
       }
       __syncthreads();
     }
-    if (kApp) store_new_token();
     if (!kLoop) break;
     if (dynamic) {
       __syncthreads();
@@ -686,11 +692,6 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.cstride = pl.cstride;
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);
-  p.k_pool_w = static_cast<uint16_t*>(layout->k_pool);
-  p.v_pool_w = static_cast<uint16_t*>(layout->v_pool);
-  p.page_min_w = static_cast<uint16_t*>(layout->page_min);
-  p.page_max_w = static_cast<uint16_t*>(layout->page_max);
-  p.seq_lens_w = layout->seq_lens;
   p.B = layout->num_seqs;
   p.topk = topk;
   p.S = layout->page_size;
