@@ -147,7 +147,8 @@ def cpu_baseline(spec, layer, wl, budget_s=20.0):
     us_step = med * 1e6 * spec.B / n_seq
     return {"value": round(us_step, 1), "unit": "us/step", "cores": oracle.max_threads(),
             "kind": "oracle",
-            "sample": f"{n_seq} of {spec.B} sequences (all KV heads), score+select+attend, "
+            "sample": f"{n_seq} of {spec.B} sequences (all KV heads), score+select+attend (the append "
+                      f"of one token, microseconds on a CPU, is not in the timed loop), "
                       f"median of {len(times)} runs scaled by {spec.B}/{n_seq}; attention loop "
                       f"OpenMP over query heads, scoring and selection single-threaded"}
 
