@@ -167,6 +167,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip timing the dense (whole-cache) attention beside the step")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the per-launch percentiles, the warm figure and the plain copy")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known size against which "
@@ -303,6 +305,64 @@ def main():
     fused_us = ev_fused / n_roof * 1e6
     achieved = by["total"] / (fused_us * 1e-6) / 1e9
 
+    # ---- distribution of single launches, the same step on data left warm, and a plain
+    # ---- copy of the same number of bytes ------------------------------------------
+    extra = {}
+    if not args.no_extras:
+        # (1) every launch bracketed by its own pair of events (eager, cold rotation); the
+        # pair adds its own few microseconds, so these sit above the graph figure
+        n_one = min(steps, 200)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(n_one)]
+        for i in range(2 * n_layers):
+            fused_only(i)
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fused_only(i)
+            b.record()
+        torch.cuda.synchronize()
+        one = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        extra["single_launch_event_us"] = {
+            "p10": round(one[n_one // 10], 2), "p50": round(one[n_one // 2], 2),
+            "p90": round(one[(9 * n_one) // 10], 2), "launches": n_one,
+            "note": "dominant kernel, eager, one event pair per launch (adds its own overhead)"}
+        # (2) warm: the same layer again and again, so metadata and KV pages are found in
+        # the caches left by the previous launch
+        n_warm = 64
+        for i in range(8):
+            (layers[0].both if single_kernel else layers[0].fused)(stream, 0)
+        _, ev_w = time_region(
+            torch, lambda i: (layers[0].both if single_kernel else layers[0].fused)(stream, 0),
+            n_warm)
+        extra["warm_us_per_launch"] = round(ev_w / n_warm * 1e6, 2)
+        # (3) a plain device copy that moves as many bytes as the step's algorithmic bytes
+        # (half read, half written), rotating over buffers so that it is cold as well
+        half = max(by["total"] // 2 // 4, 1)
+        n_buf = max(2, min(32, (1 << 30) // max(by["total"], 1)))
+        srcs = [torch.ones(half, dtype=torch.float32, device=dev) for _ in range(n_buf)]
+        dsts = [torch.empty_like(t) for t in srcs]
+        for i in range(n_buf):
+            dsts[i].copy_(srcs[i])
+        g_copy = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g_copy, stream=side):
+                for i in range(n_buf):
+                    dsts[i].copy_(srcs[i])
+        torch.cuda.current_stream().wait_stream(side)
+        g_copy.replay()
+        reps_c = max(2, 256 // n_buf)
+        _, ev_c = time_region(torch, lambda i: g_copy.replay(), reps_c)
+        copy_us = ev_c / (reps_c * n_buf) * 1e6
+        extra["copy_same_bytes"] = {
+            "us": round(copy_us, 2), "GBps": round(2 * half * 4 / (copy_us * 1e-6) / 1e9, 1),
+            "kernel_pct_of_copy_bandwidth": round(100.0 * copy_us / fused_us, 1),
+            "note": "torch device-to-device copy kernel, bytes read + written = algorithmic bytes "
+                    "of the step, cold buffers, HIP graph"}
+        del srcs, dsts, g_copy
+
     # ---- other entry points, for the record ---------------------------------------
     _, ev_b = time_region(torch, lambda i: ts.build_page_meta(layers[i % n_layers].layout),
                           2 * n_layers)
@@ -376,6 +436,7 @@ def main():
         "other_kernels_us": {"ts_build_page_meta": round(build_us, 2),
                              "ts_append_token_meta": round(append_us, 2)},
     }
+    result.update(extra)
     if dense is not None:
         result["dense_baseline"] = dense
     if not args.no_cpu_baseline:
