@@ -48,7 +48,7 @@ static double bf16_to_double(uint16_t bits) {
 
 static int pages_of(int len, int S) { return (len + S - 1) / S; }
 
-int tso_version(void) { return 1; }
+int tso_version(void) { return 2; }
 
 int tso_max_threads(void) {
 #ifdef _OPENMP
@@ -221,11 +221,14 @@ void tso_select_topk_pages(const double* scores, const int32_t* seq_lens, int B,
  * a_i = scale * q.k_i over the tokens of the selected pages only,
  * alpha = softmax(a) over exactly those tokens, o = sum_i alpha_i v_i.
  * (The paper writes softmax(q.k) with no scale: scale = 1 is its literal
- * form.)  A (sequence, head) with no selected token yields o = 0. */
+ * form.)  A (sequence, head) with no selected token yields o = 0.
+ * lse (nullable, [B][Hq]): log of the softmax denominator, log sum_i exp(a_i)
+ * over the same tokens (-inf with none): the share of the dense softmax mass
+ * that falls on the selected tokens is exp(lse_selected - lse_all). */
 void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uint16_t* V,
                                  const int32_t* sel, const int32_t* sel_count,
                                  const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
-                                 int S, int Kmax, double scale, double* out) {
+                                 int S, int Kmax, double scale, double* out, double* lse) {
   int G = Hq / Hkv;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1)
@@ -265,6 +268,7 @@ void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uin
       double w = a[i] / denom;
       for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)tok[i] * d + c]);
     }
+    if (lse) lse[(size_t)b * Hq + g] = cnt > 0 ? amax + log(denom) : -INFINITY;
     free(a);
     free(tok);
   }
@@ -274,7 +278,7 @@ void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uin
  * expression opening Section 3.5); used only as the K = P special case. */
 void tso_dense_decode_attention(const uint16_t* q, const uint16_t* K, const uint16_t* V,
                                 const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
-                                double scale, double* out) {
+                                double scale, double* out, double* lse) {
   int G = Hq / Hkv;
   for (int b = 0; b < B; ++b) {
     int L = seq_lens[b];
@@ -303,6 +307,7 @@ void tso_dense_decode_attention(const uint16_t* q, const uint16_t* K, const uint
         double w = a[t] / denom;
         for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)t * d + c]);
       }
+      if (lse) lse[(size_t)b * Hq + g] = L > 0 ? amax + log(denom) : -INFINITY;
       free(a);
     }
   }
@@ -321,7 +326,7 @@ void tso_query_aware_decode(const uint16_t* q, const uint16_t* K, const uint16_t
   tso_select_topk_pages(scores, seq_lens, B, Hkv, S, Pmax, topk, topk_per_seq, Kmax, sel,
                         sel_count, gap);
   tso_sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, B, Hq, Hkv, Lmax, d, S, Kmax,
-                              scale, out);
+                              scale, out, NULL);
 }
 
 /* True per-page maximum of q.k for one query head (the quantity Eq. 2

@@ -112,28 +112,30 @@ def select_topk_pages(scores, seq_lens, S, topk, Kmax, topk_per_seq=None):
     return sel, cnt, gap
 
 
-def sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, S, scale):
+def sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, S, scale, return_lse=False):
     q, K, V = _u16(q), _u16(K), _u16(V)
     B, Hq, d = q.shape
     _, Hkv, Lmax, _ = K.shape
     sel, sel_count, seq_lens = _i32(sel), _i32(sel_count), _i32(seq_lens)
     Kmax = sel.shape[2]
     out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64) if return_lse else None
     _load().tso_sparse_decode_attention(_p(q), _p(K), _p(V), _p(sel), _p(sel_count), _p(seq_lens),
                                         B, Hq, Hkv, Lmax, d, S, Kmax, ctypes.c_double(scale),
-                                        _p(out))
-    return out
+                                        _p(out), _p(lse))
+    return (out, lse) if return_lse else out
 
 
-def dense_decode_attention(q, K, V, seq_lens, scale):
+def dense_decode_attention(q, K, V, seq_lens, scale, return_lse=False):
     q, K, V = _u16(q), _u16(K), _u16(V)
     B, Hq, d = q.shape
     _, Hkv, Lmax, _ = K.shape
     seq_lens = _i32(seq_lens)
     out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64) if return_lse else None
     _load().tso_dense_decode_attention(_p(q), _p(K), _p(V), _p(seq_lens), B, Hq, Hkv, Lmax, d,
-                                       ctypes.c_double(scale), _p(out))
-    return out
+                                       ctypes.c_double(scale), _p(out), _p(lse))
+    return (out, lse) if return_lse else out
 
 
 def query_aware_decode(q, K, V, page_min, page_max, seq_lens, S, topk, Kmax, scale,

@@ -170,6 +170,61 @@ def test_single_key_uniform_values(oracle):
 
 
 # ----------------------------------------------------------------------------
+# log of the softmax denominator (reported next to the attention output)
+# ----------------------------------------------------------------------------
+def test_lse_closed_form_equal_logits(oracle):
+    """n tokens with the same logit a: the denominator is n * exp(a)."""
+    d, S = 4, 4
+    K = np.tile(bf16_bits([[0.5, -1.0, 2.0, 0.25]]), (8, 1)).reshape(1, 1, 8, d)
+    V = rand_bf16(np.random.default_rng(0), (1, 1, 8, d))
+    q = bf16_bits([[1.0, 2.0, -1.0, 4.0]]).reshape(1, 1, d)
+    logit = 0.7 * (0.5 * 1.0 - 1.0 * 2.0 - 2.0 * 1.0 + 0.25 * 4.0)
+    _, lse = oracle.sparse_decode_attention(q, K, V, np.array([[[1]]], dtype=np.int32), [1], [7], S,
+                                            0.7, return_lse=True)
+    assert lse[0, 0] == pytest.approx(logit + np.log(3.0), abs=1e-13)   # tokens 4, 5, 6
+    _, lse = oracle.dense_decode_attention(q, K, V, [7], 0.7, return_lse=True)
+    assert lse[0, 0] == pytest.approx(logit + np.log(7.0), abs=1e-13)
+    _, lse = oracle.sparse_decode_attention(q, K, V, np.array([[[0]]], dtype=np.int32), [0], [7], S,
+                                            0.7, return_lse=True)
+    assert lse[0, 0] == -np.inf
+
+
+def test_lse_against_library_and_partition(oracle):
+    """Against scipy's logsumexp of independently computed logits; and the softmax
+    mass of disjoint page sets adds up to that of their union (the whole cache: 1)."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, d, S = 2, 4, 2, 8, 4
+    lens = np.array([22, 13], dtype=np.int32)
+    Lmax, G = 24, Hq // Hkv
+    K = rand_bf16(rng, (B, Hkv, Lmax, d))
+    V = rand_bf16(rng, (B, Hkv, Lmax, d))
+    q = rand_bf16(rng, (B, Hq, d), 2.0)
+    scale = 0.3
+    _, dense = oracle.dense_decode_attention(q, K, V, lens, scale, return_lse=True)
+    Kv, qv = bf16_val(K), bf16_val(q)
+    for b in range(B):
+        for g in range(Hq):
+            a = scale * (Kv[b, g // G, :lens[b]] @ qv[b, g])
+            assert dense[b, g] == pytest.approx(logsumexp(a), abs=1e-12)
+    # pages {0, 2, 4} and {1, 3, 5} partition every sequence (absent pages hold no token)
+    even = np.tile(np.array([0, 2, 4], dtype=np.int32), (B, Hkv, 1))
+    odd = np.tile(np.array([1, 3, 5], dtype=np.int32), (B, Hkv, 1))
+    # sequence 1 has 4 pages: its lists are {0, 2} and {1, 3}
+    even[1, :, 2] = -1
+    odd[1, :, 2] = -1
+    cnt_b = np.array([3, 2], dtype=np.int32)
+    _, le = oracle.sparse_decode_attention(q, K, V, even, cnt_b, lens, S, scale, return_lse=True)
+    _, lo = oracle.sparse_decode_attention(q, K, V, odd, cnt_b, lens, S, scale, return_lse=True)
+    np.testing.assert_allclose(np.exp(le - dense) + np.exp(lo - dense), 1.0, rtol=0, atol=1e-12)
+    for b in range(B):
+        for g in range(Hq):
+            toks = [t for j in even[b, g // G, :cnt_b[b]] for t in range(j * S, min((j + 1) * S, lens[b]))]
+            a = scale * (Kv[b, g // G, toks] @ qv[b, g])
+            assert le[b, g] == pytest.approx(logsumexp(a), abs=1e-12)
+
+
+# ----------------------------------------------------------------------------
 # K = P  ==>  dense softmax attention, against torch's SDPA (a library routine)
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("scale", [1.0, 0.125])
