@@ -32,7 +32,7 @@
  *     scored and attended over the tokens it holds; pool slots past seq_lens[b]
  *     may hold anything (NaN included) and never influence a result.
  *
- * Supported shapes: head_dim in {64, 128}; page_size in {16, 32};
+ * Supported shapes: head_dim in {64, 128}; page_size in {4, 8, 16, 32, 64};
  * 1 <= G = Hq / Hkv <= 16; max_pages_per_seq <= TS_MAX_PAGES_PER_SEQ.
  */
 #ifndef TINYSERVE_H_
@@ -129,12 +129,16 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
  * weighted sum of their values.  The paper writes softmax(q.k) with no factor:
  * softmax_scale = 1 is its literal form, 1/sqrt(d) the usual one.
  * out: fp32 [B][Hq][d]; a (b, head) with no token gets zeros.  bf16 inputs,
- * fp32 accumulation.  workspace: ts_workspace_bytes(layout, max_topk) bytes,
- * initialised once with ts_workspace_init. */
+ * fp32 accumulation.  lse_out (optional, NULL = not reported): fp32 [B][Hq],
+ * the natural logarithm of the softmax denominator, log sum_t exp(softmax_scale
+ * * q.k_t) over the attended tokens (-inf with no token); the share of the
+ * dense softmax mass that a selection captures is exp(lse_sparse - lse_dense).
+ * workspace: ts_workspace_bytes(layout, max_topk) bytes, initialised once with
+ * ts_workspace_init. */
 int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
                                const int32_t* sel_count, int32_t max_topk, float softmax_scale,
-                               float* out, void* workspace, size_t workspace_bytes,
-                               void* stream);
+                               float* out, float* lse_out, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 /* Algorithm 1 as ONE kernel launch: score -> select -> gather -> attend.
  * Arguments as in the three staged calls.  scores_out (fp32 [B][Hkv][P_max]),
@@ -183,12 +187,14 @@ size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk);
 /* The comparison the paper measures against (the FullCache rows of its latency
  * tables; Section 3.5 opens with this Attn(q_t, K, V) over the whole cache):
  * single-query softmax attention over EVERY cached token of every sequence,
- * through the same block table and pool layout, fp32 out [B][Hq][d].  Needs a
- * workspace of its own size, ts_dense_workspace_bytes(layout) (host-only, 0 on
- * an invalid layout), initialised with ts_workspace_init. */
+ * through the same block table and pool layout, fp32 out [B][Hq][d]; lse_out
+ * as in ts_sparse_decode_attention (optional).  Needs a workspace of its own
+ * size, ts_dense_workspace_bytes(layout) (host-only, 0 on an invalid layout),
+ * initialised with ts_workspace_init. */
 size_t ts_dense_workspace_bytes(const ts_layout* layout);
 int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
-                              void* workspace, size_t workspace_bytes, void* stream);
+                              float* lse_out, void* workspace, size_t workspace_bytes,
+                              void* stream);
 
 /* Zeroes the whole workspace.  Required once after allocation (and after a
  * launch that was aborted); every call leaves the workspace ready for the

@@ -83,6 +83,9 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   if (g > max_topk) g = max_topk;
   if (g < 1) g = 1;
   pl.chunk = (max_topk + g - 1) / g;
+  // pages smaller than an MFMA tile are attended four / two at a time: whole
+  // groups per workgroup
+  if (L->page_size < 16) pl.chunk = (pl.chunk + 3) / 4 * 4;
   pl.g = (max_topk + pl.chunk - 1) / pl.chunk;
   size_t off = kCtrlWords * sizeof(int32_t);
   pl.off_unit = off;
@@ -564,7 +567,9 @@ static int check_layout(const ts_layout* L) {
       (L->kv_tile_stride < L->head_dim * L->page_size || L->kv_tile_stride % 8 != 0))
     return TS_ERR_SHAPE;
   if (L->head_dim != 64 && L->head_dim != 128) return TS_ERR_UNSUPPORTED;
-  if (L->page_size != 16 && L->page_size != 32) return TS_ERR_UNSUPPORTED;
+  if (L->page_size != 4 && L->page_size != 8 && L->page_size != 16 && L->page_size != 32 &&
+      L->page_size != 64)
+    return TS_ERR_UNSUPPORTED;
   if (L->num_q_heads / L->num_kv_heads > 16) return TS_ERR_UNSUPPORTED;
   if (L->max_pages_per_seq > TS_MAX_PAGES_PER_SEQ) return TS_ERR_UNSUPPORTED;
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
@@ -644,6 +649,7 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.block_table = L->block_table;
   a.seq_lens = L->seq_lens;
   a.out = out;
+  a.lse = nullptr;
   a.partials = reinterpret_cast<float*>(ws + pl.off_part);
   a.Hq = L->num_q_heads;
   a.Hkv = L->num_kv_heads;
@@ -661,6 +667,24 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
 }  // namespace ts
 
 using namespace ts;
+
+// CALL(D, S) for the layout's head_dim / page_size (check_layout has admitted them).
+#define TS_DISPATCH_PAGE(DD, S, CALL) \
+  switch (S) {                        \
+    case 4: CALL(DD, 4); break;       \
+    case 8: CALL(DD, 8); break;       \
+    case 16: CALL(DD, 16); break;     \
+    case 32: CALL(DD, 32); break;     \
+    default: CALL(DD, 64); break;     \
+  }
+#define TS_DISPATCH_SHAPE(D, S, CALL)   \
+  do {                                  \
+    if ((D) == 64) {                    \
+      TS_DISPATCH_PAGE(64, S, CALL)     \
+    } else {                            \
+      TS_DISPATCH_PAGE(128, S, CALL)    \
+    }                                   \
+  } while (0)
 
 static int launch_fused(const ts_layout* layout, const void* k_new, const void* v_new,
                         const void* q, int32_t topk, const int32_t* topk_per_seq,
@@ -738,10 +762,7 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
     query_aware_decode_kernel<DD, SS, true, false>                                            \
         <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                      \
   } while (0)
-  if (D == 64 && S == 16) TS_LAUNCH_FUSED(64, 16);
-  else if (D == 64 && S == 32) TS_LAUNCH_FUSED(64, 32);
-  else if (D == 128 && S == 16) TS_LAUNCH_FUSED(128, 16);
-  else TS_LAUNCH_FUSED(128, 32);
+  TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_FUSED);
 #undef TS_LAUNCH_FUSED
   return launch_status();
 }
@@ -749,7 +770,7 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
 
 extern "C" {
 
-int ts_version(void) { return 3; }
+int ts_version(void) { return 4; }
 
 #ifdef TS_PROFILE
 int ts_debug_set_profile_buffer(void* buf) {
@@ -878,33 +899,27 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
 
 static int launch_attention(const ts_layout* layout, const Plan& pl, const void* q,
                             const int32_t* sel, const int32_t* sel_count, int32_t max_topk,
-                            float softmax_scale, float* out, void* workspace, void* stream) {
+                            float softmax_scale, float* out, float* lse_out, void* workspace,
+                            void* stream) {
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
+  a.lse = lse_out;
   int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units * pl.cstride;
   const size_t lds = (size_t)kWaves * a.G * (layout->head_dim + 2) * 4;
   dim3 grid(pl.g, pl.units);
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
-  if (D == 64 && S == 16)
-    sparse_attention_kernel<64, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
-                                                               pl.cstride);
-  else if (D == 64 && S == 32)
-    sparse_attention_kernel<64, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
-                                                               pl.cstride);
-  else if (D == 128 && S == 16)
-    sparse_attention_kernel<128, 16><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
-                                                               pl.cstride);
-  else
-    sparse_attention_kernel<128, 32><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done,
-                                                               pl.cstride);
+#define TS_LAUNCH_ATTENTION(DD, SS) \
+  sparse_attention_kernel<DD, SS><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride)
+  TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_ATTENTION);
+#undef TS_LAUNCH_ATTENTION
   return launch_status();
 }
 
 int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
                                const int32_t* sel_count, int32_t max_topk, float softmax_scale,
-                               float* out, void* workspace, size_t workspace_bytes,
-                               void* stream) {
+                               float* out, float* lse_out, void* workspace,
+                               size_t workspace_bytes, void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
   if (!q || !sel || !sel_count || !out || !workspace || !layout->k_pool || !layout->v_pool ||
@@ -913,8 +928,8 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
   if (max_topk < 1) return TS_ERR_SHAPE;
   const Plan pl = make_plan(layout, max_topk);
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
-  return launch_attention(layout, pl, q, sel, sel_count, max_topk, softmax_scale, out, workspace,
-                          stream);
+  return launch_attention(layout, pl, q, sel, sel_count, max_topk, softmax_scale, out, lse_out,
+                          workspace, stream);
 }
 
 size_t ts_dense_workspace_bytes(const ts_layout* layout) {
@@ -923,7 +938,8 @@ size_t ts_dense_workspace_bytes(const ts_layout* layout) {
 }
 
 int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              float* lse_out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
   if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
@@ -932,7 +948,7 @@ int ts_dense_decode_attention(const ts_layout* layout, const void* q, float soft
   const Plan pl = make_plan(layout, layout->max_pages_per_seq, kDenseTargetWorkgroups);
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
   return launch_attention(layout, pl, q, nullptr, nullptr, layout->max_pages_per_seq, softmax_scale,
-                          out, workspace, stream);
+                          out, lse_out, workspace, stream);
 }
 
 int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
@@ -944,15 +960,11 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
   if (cus <= 0) return TS_ERR_DEVICE;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
   const int D = layout->head_dim, S = layout->page_size;
-  int cap1;
-  if (D == 64 && S == 16)
-    cap1 = resident_capacity(query_aware_decode_kernel<64, 16, false, true>, pl.lds_fused);
-  else if (D == 64 && S == 32)
-    cap1 = resident_capacity(query_aware_decode_kernel<64, 32, false, true>, pl.lds_fused);
-  else if (D == 128 && S == 16)
-    cap1 = resident_capacity(query_aware_decode_kernel<128, 16, false, true>, pl.lds_fused);
-  else
-    cap1 = resident_capacity(query_aware_decode_kernel<128, 32, false, true>, pl.lds_fused);
+  int cap1 = 0;
+#define TS_CAPACITY(DD, SS) \
+  cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false, true>, pl.lds_fused)
+  TS_DISPATCH_SHAPE(D, S, TS_CAPACITY);
+#undef TS_CAPACITY
   if (cap1 <= 0) return TS_ERR_DEVICE;
   if (cap1 > cus * per_cu) cap1 = cus * per_cu;
   return pl.units * pl.g <= cap1 ? 1 : 2;

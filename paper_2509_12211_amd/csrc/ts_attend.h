@@ -11,6 +11,13 @@
 // products, so the running max / sum / rescale factor are per-lane scalars.
 // K tiles [S][D] and V tiles [D][S] (channel-major) let every lane fetch its
 // operand with plain 8/16-byte loads; nothing is transposed on chip.
+//
+// Page sizes other than 16 and 32 map onto the same two fragment shapes: a
+// wave works on fragments of F = 16 tokens (S <= 16) or F = 32 tokens
+// (S >= 32).  With S < 16 a fragment is made of 16 / S consecutive entries of
+// the selected list (each lane picks the tile of the page its MFMA row or its
+// four value tokens belong to); with S = 64 a page is two fragments, its first
+// and its second 32 tokens.
 #pragma once
 #include "ts_device.h"
 
@@ -34,65 +41,105 @@ struct AttendParams {
   const int32_t* block_table;  // [B][Pmax]
   const int32_t* seq_lens;     // [B]
   float* out;                  // [B][Hq][D]
+  float* lse;                  // nullable [B][Hq]: log of the softmax denominator
   float* partials;             // [B*Hkv][n_split][G][D+2]
   int Hq, Hkv, G, Pmax, Kmax, n_phys, n_split, chunk;
   int tile_stride;             // elements between consecutive (page, head) tiles
   float scale_log2;            // softmax_scale * log2(e)
 };
 
-template <int D, int S>
+template <int S>
+struct PageGeom {
+  static_assert(S == 4 || S == 8 || S == 16 || S == 32 || S == 64, "page size");
+  static constexpr int F = S <= 16 ? 16 : 32;     // tokens per fragment
+  static constexpr int NS = S < 16 ? 16 / S : 1;  // list entries (pages) per fragment
+  static constexpr int NH = S > 32 ? S / 32 : 1;  // fragments per page
+  static constexpr uint32_t kAll = F == 32 ? 0xffffffffu : 0xffffu;
+  // fragments needed for `count` list entries
+  __device__ __forceinline__ static int items(int count) {
+    return S < 16 ? (count + NS - 1) / NS : count * NH;
+  }
+};
+
+// A fragment of F tokens (F = 16 or 32) in MFMA operand order.
+template <int D, int F>
 struct PageFrag {
-  static constexpr int NT = S / 16;   // 16-token tiles per page
+  static constexpr int NT = F / 16;   // 16-token tiles per fragment
   static constexpr int KQ = D / 32;   // 16-byte K loads per lane per tile (D/4 channels)
   static constexpr int NCB = D / 16;  // 16-channel output blocks
   uint4 k[NT][KQ];
   uint2 v[NT][NCB];
 };
 
-// Token held by MFMA row r of tile t.  For S = 32 the rows are permuted so that
-// the eight tokens a lane needs for the two P.V products are contiguous in the
-// channel-major V tile.
-template <int S>
+// Fragment token held by MFMA row r of tile t.  For F = 32 the rows are permuted
+// so that the eight tokens a lane needs for the two P.V products are contiguous
+// in the channel-major V tile.
+template <int F>
 __device__ __forceinline__ int tile_token(int t, int r) {
-  return S == 16 ? r : 8 * (r >> 2) + 4 * t + (r & 3);
+  return F == 16 ? r : 8 * (r >> 2) + 4 * t + (r & 3);
 }
 
+// Fetch one fragment of a page with S >= 16 tokens.  ktile / vtile: the page's
+// K and V tiles; hoff: first token of the fragment inside the page (0, or 32
+// for the second half of a 64-token page).  `spread` is 1 for a real fragment
+// and 0 for a placeholder fetch: with 0 every lane reads the first bytes of the
+// tile, so the instruction touches one cache line instead of the whole tile
+// (the data is never used).
 template <int D, int S>
-__device__ __forceinline__ void zero_page(PageFrag<D, S>& f) {
-#pragma unroll
-  for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
-#pragma unroll
-    for (int i = 0; i < PageFrag<D, S>::KQ; ++i) f.k[t][i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < PageFrag<D, S>::NCB; ++i) f.v[t][i] = make_uint2(0, 0);
-  }
-}
-
-// `spread` is 1 for a real page and 0 for a placeholder fetch: with 0 every
-// lane reads the first bytes of the tile, so the instruction touches one cache
-// line instead of the whole tile (the data is never used).
-template <int D, int S>
-__device__ __forceinline__ void load_page(PageFrag<D, S>& f, const uint16_t* ktile,
-                                          const uint16_t* vtile, int spread) {
+__device__ __forceinline__ void load_page(PageFrag<D, PageGeom<S>::F>& f, const uint16_t* ktile,
+                                          const uint16_t* vtile, int hoff, int spread) {
+  constexpr int F = PageGeom<S>::F;
+  static_assert(S >= 16, "whole-page fragments");
   const int lane = lane_id(), r = (lane & 15) * spread, kb = (lane >> 4) * spread;
+  hoff *= spread;
 #pragma unroll
-  for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
-    const uint16_t* krow = ktile + tile_token<S>(t, r) * D * spread + kb * (D / 4);
+  for (int t = 0; t < PageFrag<D, F>::NT; ++t) {
+    const uint16_t* krow = ktile + (hoff + tile_token<F>(t, r)) * D * spread + kb * (D / 4);
 #pragma unroll
-    for (int i = 0; i < PageFrag<D, S>::KQ; ++i)
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i)
       f.k[t][i] = *reinterpret_cast<const uint4*>(krow + i * 8 * spread);
   }
 #pragma unroll
-  for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) {
-    const uint16_t* vrow = vtile + (16 * cb * spread + r) * S;
-    if (S == 16) {
+  for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) {
+    const uint16_t* vrow = vtile + (16 * cb * spread + r) * S + hoff;
+    if (F == 16) {
       f.v[0][cb] = *reinterpret_cast<const uint2*>(vrow + 4 * kb);
     } else {
       const uint4 w = *reinterpret_cast<const uint4*>(vrow + 8 * kb);
       f.v[0][cb] = make_uint2(w.x, w.y);
-      f.v[S == 16 ? 0 : 1][cb] = make_uint2(w.z, w.w);
+      f.v[F == 16 ? 0 : 1][cb] = make_uint2(w.z, w.w);
     }
   }
+}
+
+// Fetch one 16-token fragment made of 16 / S small pages: toff[s] is the
+// element offset of the tile of the fragment's s-th page (the same offset in
+// the K and in the V pool).  Fragment token x lives in page x / S, slot x % S.
+// spread as above (0: every lane reads the first bytes of page 0's tiles).
+template <int D, int S>
+__device__ __forceinline__ void load_small_pages(PageFrag<D, 16>& f, const uint16_t* k_pool,
+                                                 const uint16_t* v_pool,
+                                                 const size_t (&toff)[PageGeom<S>::NS],
+                                                 int spread) {
+  constexpr int NS = PageGeom<S>::NS;
+  static_assert(S < 16, "several pages per fragment");
+  const int lane = lane_id(), r = (lane & 15) * spread, kb = (lane >> 4) * spread;
+  // K: MFMA row r is fragment token r; V: this lane's four tokens are 4 * kb .. + 3
+  const int sk = r / S, sv = (4 * kb) / S;
+  size_t ok = toff[0], ov = toff[0];
+#pragma unroll
+  for (int s = 1; s < NS; ++s) {
+    ok = sk == s ? toff[s] : ok;
+    ov = sv == s ? toff[s] : ov;
+  }
+  const uint16_t* krow = k_pool + ok + (r % S) * D + kb * (D / 4);
+#pragma unroll
+  for (int i = 0; i < PageFrag<D, 16>::KQ; ++i)
+    f.k[0][i] = *reinterpret_cast<const uint4*>(krow + i * 8 * spread);
+  const uint16_t* vbase = v_pool + ov + (4 * kb) % S;
+#pragma unroll
+  for (int cb = 0; cb < PageFrag<D, 16>::NCB; ++cb)
+    f.v[0][cb] = *reinterpret_cast<const uint2*>(vbase + (16 * cb * spread + r) * S);
 }
 
 // A token appended in the same launch: it belongs to page j (-1: none), slot
@@ -106,32 +153,33 @@ struct NewToken {
   const uint16_t* v_row;
 };
 
-template <int D, int S>
+template <int D, int F>
 struct TokenPatch {
-  uint4 k[PageFrag<D, S>::KQ];       // this lane's D/4 channels of the key
-  uint32_t v[PageFrag<D, S>::NCB];   // value of channel 16 * cb + lane % 16
+  uint4 k[PageFrag<D, F>::KQ];       // this lane's D/4 channels of the key
+  uint32_t v[PageFrag<D, F>::NCB];   // value of channel 16 * cb + lane % 16
   __device__ __forceinline__ void load(const NewToken& nt) {
     const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < PageFrag<D, S>::KQ; ++i)
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i)
       k[i] = *reinterpret_cast<const uint4*>(nt.k_row + kb * (D / 4) + i * 8);
 #pragma unroll
-    for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) v[cb] = nt.v_row[16 * cb + r];
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) v[cb] = nt.v_row[16 * cb + r];
   }
-  // Splice into a page fetched from the pool (registers only).
-  __device__ __forceinline__ void apply(PageFrag<D, S>& f, int slot) const {
+  // Splice into a fragment fetched from the pool (registers only); x: the
+  // token's position inside the fragment.
+  __device__ __forceinline__ void apply(PageFrag<D, F>& f, int x) const {
     const int lane = lane_id(), r = lane & 15, kb = lane >> 4;
 #pragma unroll
-    for (int t = 0; t < PageFrag<D, S>::NT; ++t) {
-      if (tile_token<S>(t, r) == slot) {
+    for (int t = 0; t < PageFrag<D, F>::NT; ++t) {
+      if (tile_token<F>(t, r) == x) {
 #pragma unroll
-        for (int i = 0; i < PageFrag<D, S>::KQ; ++i) f.k[t][i] = k[i];
+        for (int i = 0; i < PageFrag<D, F>::KQ; ++i) f.k[t][i] = k[i];
       }
-      // V words of tile t hold tokens tile_token<S>(t, 4 * kb) .. + 3
-      const int e = slot - tile_token<S>(t, 4 * kb);
+      // V words of tile t hold tokens tile_token<F>(t, 4 * kb) .. + 3
+      const int e = x - tile_token<F>(t, 4 * kb);
       if (e >= 0 && e < 4) {
 #pragma unroll
-        for (int cb = 0; cb < PageFrag<D, S>::NCB; ++cb) {
+        for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) {
           const uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
           const uint32_t put = (e & 1) ? (v[cb] << 16) : v[cb];
           if (e < 2) f.v[t][cb].x = (f.v[t][cb].x & keep) | put;
@@ -141,6 +189,12 @@ struct TokenPatch {
     }
   }
 };
+
+// Natural log of sum_t exp(scale * q.k_t) from the running maximum m (log2
+// domain) and the sum l of exp2(logit - m); -inf when no token was attended.
+__device__ __forceinline__ float log_sum_exp(float m, float l) {
+  return l > 0.f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+}
 
 template <int D>
 struct WaveAcc {
@@ -169,12 +223,13 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
   }
 }
 
-// One page: logits, online-softmax update, weighted value accumulation.
-// `valid` = number of tokens the page holds (tokens >= valid are masked).
-template <int D, int S>
-__device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short4_t (&qf)[D / 16],
-                                            int valid, float scale_log2, WaveAcc<D>& a) {
-  constexpr int NT = PageFrag<D, S>::NT, NCB = PageFrag<D, S>::NCB;
+// One fragment: logits, online-softmax update, weighted value accumulation.
+// Bit x of `vmask` says whether fragment token x exists (tokens past the end of
+// the sequence, and the tokens of a missing page, are masked).
+template <int D, int F>
+__device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short4_t (&qf)[D / 16],
+                                            uint32_t vmask, float scale_log2, WaveAcc<D>& a) {
+  constexpr int NT = PageFrag<D, F>::NT, NCB = PageFrag<D, F>::NCB;
   const int kb = lane_id() >> 4;
   float4_t sc[NT];
   float mx = -INFINITY;
@@ -186,10 +241,10 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
       sc[t] = mfma16(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
       sc[t] = mfma16(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
     }
+    const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const int tok = tile_token<S>(t, 4 * kb + v);
-      const float x = tok < valid ? sc[t][v] * scale_log2 : -INFINITY;
+      const float x = (mine >> v) & 1u ? sc[t][v] * scale_log2 : -INFINITY;
       sc[t][v] = x;
       mx = fmaxf(mx, x);
     }
@@ -201,7 +256,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
   a.l *= alpha;
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) a.o[cb] *= alpha;
-  const bool partial = valid < S;
+  const bool partial = vmask != (F == 32 ? 0xffffffffu : 0xffffu);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     // softmax weights split into two bf16 terms (truncated high part + remainder)
@@ -217,15 +272,15 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
     const short4_t ph = as_short4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
     const short4_t pl = as_short4((lo[0] >> 16) | (lo[1] & 0xffff0000u),
                                   (lo[2] >> 16) | (lo[3] & 0xffff0000u));
+    const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       uint32_t v0 = f.v[t][cb].x, v1 = f.v[t][cb].y;
-      if (partial) {  // slots past the sequence end may hold anything: zero them
-        const int t0 = tile_token<S>(t, 4 * kb);
-        if (t0 + 0 >= valid) v0 &= 0xffff0000u;
-        if (t0 + 1 >= valid) v0 &= 0x0000ffffu;
-        if (t0 + 2 >= valid) v1 &= 0xffff0000u;
-        if (t0 + 3 >= valid) v1 &= 0x0000ffffu;
+      if (partial) {  // slots that hold no token may hold anything: zero them
+        if (!(mine & 1u)) v0 &= 0xffff0000u;
+        if (!(mine & 2u)) v0 &= 0x0000ffffu;
+        if (!(mine & 4u)) v1 &= 0xffff0000u;
+        if (!(mine & 8u)) v1 &= 0x0000ffffu;
       }
       const short4_t vf = as_short4(v0, v1);
       a.o[cb] = mfma16(vf, ph, a.o[cb]);
@@ -235,8 +290,9 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, S>& f, const short
 }
 
 // The workgroup attends `count` selected pages of unit (b, h): entry i of its
-// list is page sel_at(i), stored in physical page phys_at(page).  Wave w takes
-// entries w, w + kWaves, ...  The four wave states are merged through LDS
+// list is page sel_at(i), stored in physical page phys_at(page).  The list is
+// cut into fragments (PageGeom<S>); wave w takes fragments w, w + kWaves, ...
+// The four wave states are merged through LDS
 // (lds: kWaves * G * (D + 2) floats).  With n_split == 1 the normalised result
 // goes to `out`; otherwise the unnormalised partial (o[D], m, l per head) is
 // handed to the combining workgroup through agent-scope stores.
@@ -250,63 +306,103 @@ template <int D, int S, bool kBranchless, bool kPatch, typename SelAt, typename 
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
                                              PhysAt phys_at, float* lds) {
+  using Geo = PageGeom<S>;
+  constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
   const int lane = lane_id(), wave = wave_id();
   const int head = lane & 15, kb = lane >> 4;
   const int G = p.G;
   L = uniform(L);
   count = uniform(count);
+  const int n_items = Geo::items(count);
 
   short4_t qf[D / 16];
   load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
   // The new token's page is the sequence's last, so in the ascending list it can
   // only be the very last entry: one wave of one workgroup ever needs the token.
-  TokenPatch<D, S> patch;
-  const bool splice = kPatch && nt.j >= 0 && count > 0 && wave == (count - 1) % kWaves &&
-                      uniform(sel_at(count - 1)) == nt.j;
+  // splice_item: the fragment it falls into, splice_x: its position there.
+  TokenPatch<D, F> patch;
+  int splice_item = -1, splice_x = 0;
+  if (kPatch && nt.j >= 0 && count > 0 && uniform(sel_at(count - 1)) == nt.j) {
+    if (S < 16) {
+      splice_item = (count - 1) / NS;
+      splice_x = ((count - 1) % NS) * S + nt.slot;
+    } else {
+      splice_item = (count - 1) * NH + nt.slot / F;
+      splice_x = nt.slot % F;
+    }
+  }
+  const bool splice = kPatch && splice_item >= 0 && wave == splice_item % kWaves;
   if (splice) patch.load(nt);
   WaveAcc<D> acc;
   acc.init();
 
-  for (int batch = wave; batch < count; batch += kWave * kWaves) {
-    // lane x holds the ids of this wave's x-th page of the batch
-    const int my_i = batch + lane * kWaves;
-    int my_j = -1, my_phys = -1;
-    if (my_i < count) {
-      my_j = sel_at(my_i);
-      if (my_j >= 0 && my_j < p.Pmax) my_phys = phys_at(my_j);
+  for (int batch = wave; batch < n_items; batch += kWave * kWaves) {
+    // lane x holds the page ids of this wave's x-th fragment of the batch
+    const int my_item = batch + lane * kWaves;
+    int my_j[NS], my_phys[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      my_j[s] = -1;
+      my_phys[s] = -1;
+      const int e = S < 16 ? my_item * NS + s : my_item / NH;
+      if (my_item < n_items && e < count) {
+        my_j[s] = sel_at(e);
+        if (my_j[s] >= 0 && my_j[s] < p.Pmax) my_phys[s] = phys_at(my_j[s]);
+      }
     }
-    const int n = min(kWave, (count - batch + kWaves - 1) / kWaves);
-    // A ring of NBUF page buffers: up to NBUF pages of this wave are in flight
-    // (4 KiB - 8 KiB each) before the first is consumed.
-    constexpr int NBUF = (D * S <= 1024) ? 4 : ((D == 64 && D * S <= 2048) ? 3 : 2);
-    PageFrag<D, S> f[NBUF];
-    int valid[NBUF], page[NBUF];
+    const int n = min(kWave, (n_items - batch + kWaves - 1) / kWaves);
+    // A ring of NBUF fragment buffers: up to NBUF fragments of this wave are in
+    // flight (2 KiB - 8 KiB each) before the first is consumed.
+    constexpr int NBUF = (D * F <= 1024) ? 4 : ((D == 64 && D * F <= 2048) ? 3 : 2);
+    PageFrag<D, F> f[NBUF];
+    uint32_t vmask[NBUF];
+    int item[NBUF];
     // No branch around the loads (a load under a branch makes the compiler
     // wait for ALL outstanding loads wherever it needs one of them, so the ring
-    // would drain before the first page is used): a slot past the end of the
-    // list, or one whose page id is out of range, re-reads a page that is
-    // certainly mapped (a single cache line of it) and counts zero valid tokens.
-    auto issue = [&](PageFrag<D, S>& fr, int& jp, int x) -> int {
+    // would drain before the first fragment is used): a slot past the end of
+    // the list, or one whose page id is out of range, re-reads a page that is
+    // certainly mapped (a single cache line of it) and has no valid token.
+    auto issue = [&](PageFrag<D, F>& fr, int& it, int x) -> uint32_t {
       const int xc = min(x, n - 1);
-      const int j = __builtin_amdgcn_readlane(my_j, xc);
-      jp = j;
-      const int phys = __builtin_amdgcn_readlane(my_phys, xc);
-      const bool good = x < n && phys >= 0 && phys < p.n_phys;
-      const size_t tile = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
-      load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile, good ? 1 : 0);
-      return good ? max(0, min(S, L - j * S)) : 0;
+      it = batch + xc * kWaves;
+      if constexpr (S >= 16) {
+        const int j = __builtin_amdgcn_readlane(my_j[0], xc);
+        const int phys = __builtin_amdgcn_readlane(my_phys[0], xc);
+        const int hoff = NH > 1 ? (it % NH) * F : 0;
+        const bool good = x < n && phys >= 0 && phys < p.n_phys;
+        const size_t tile = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
+        load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile, hoff, good ? 1 : 0);
+        const int valid = good ? max(0, min(F, L - j * S - hoff)) : 0;
+        return valid >= 32 ? 0xffffffffu : (1u << valid) - 1u;
+      } else {
+        size_t toff[NS];
+        uint32_t m = 0;
+        bool any = false;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const int j = __builtin_amdgcn_readlane(my_j[s], xc);
+          const int phys = __builtin_amdgcn_readlane(my_phys[s], xc);
+          const bool good = x < n && phys >= 0 && phys < p.n_phys;
+          toff[s] = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
+          const int valid = good ? max(0, min(S, L - j * S)) : 0;
+          m |= ((1u << valid) - 1u) << (s * S);
+          any = any || good;
+        }
+        load_small_pages<D, S>(fr, p.k_pool, p.v_pool, toff, any ? 1 : 0);
+        return m;
+      }
     };
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i) valid[i] = issue(f[i], page[i], i);
+    for (int i = 0; i < NBUF; ++i) vmask[i] = issue(f[i], item[i], i);
     TS_MARK(17);
     for (int x0 = 0; x0 < n; x0 += NBUF) {
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
         if (x0 + i < n) {
-          if (splice && page[i] == nt.j) patch.apply(f[i], nt.slot);
-          attend_page<D, S>(f[i], qf, valid[i], p.scale_log2, acc);
+          if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
+          attend_page<D, F>(f[i], qf, vmask[i], p.scale_log2, acc);
         }
-        if (kBranchless || x0 + i + NBUF < n) valid[i] = issue(f[i], page[i], x0 + i + NBUF);
+        if (kBranchless || x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
       }
     }
   }
@@ -345,6 +441,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     }
     if (p.n_split == 1) {
       p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+      if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
     } else {
       store_agent(part + g * RS + c, O);
       if (c == 0) {
@@ -394,6 +491,7 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
       M = Mn;
     }
     p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+    if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
   }
 }
 

@@ -67,13 +67,13 @@ def lib():
         L.ts_append_token_meta.argtypes = [lp, vp, vp, ctypes.c_int, vp]
         L.ts_score_pages.argtypes = [lp, vp, vp, vp]
         L.ts_select_topk_pages.argtypes = [lp, vp, i32, vp, i32, vp, vp, vp]
-        L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
         L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_append_and_decode.argtypes = [lp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_append_and_decode_launches.argtypes = [lp, i32]
         L.ts_dense_workspace_bytes.argtypes = [lp]
         L.ts_dense_workspace_bytes.restype = sz
-        L.ts_dense_decode_attention.argtypes = [lp, vp, f32, vp, vp, sz, vp]
+        L.ts_dense_decode_attention.argtypes = [lp, vp, f32, vp, vp, vp, sz, vp]
         L.ts_workspace_bytes.argtypes = [lp, i32]
         L.ts_workspace_bytes.restype = sz
         L.ts_workspace_init.argtypes = [vp, sz, vp]
@@ -171,10 +171,11 @@ def new_workspace(layout, max_topk, device) -> torch.Tensor:
     return ws
 
 
-def sparse_decode_attention(layout, q, sel, sel_count, max_topk, softmax_scale, out, workspace):
+def sparse_decode_attention(layout, q, sel, sel_count, max_topk, softmax_scale, out, workspace,
+                            lse_out=None):
     _check(lib().ts_sparse_decode_attention(
         ctypes.byref(layout), _ptr(q), _ptr(sel), _ptr(sel_count), int(max_topk),
-        float(softmax_scale), _ptr(out), _ptr(workspace),
+        float(softmax_scale), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream()), "ts_sparse_decode_attention")
 
 
@@ -205,9 +206,10 @@ def new_dense_workspace(layout, device) -> torch.Tensor:
     return ws
 
 
-def dense_decode_attention(layout, q, softmax_scale, out, workspace):
+def dense_decode_attention(layout, q, softmax_scale, out, workspace, lse_out=None):
     _check(lib().ts_dense_decode_attention(
-        ctypes.byref(layout), _ptr(q), float(softmax_scale), _ptr(out), _ptr(workspace),
+        ctypes.byref(layout), _ptr(q), float(softmax_scale), _ptr(out), _ptr(lse_out),
+        _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream()), "ts_dense_decode_attention")
 
 

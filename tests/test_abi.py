@@ -64,7 +64,7 @@ def test_workspace_bytes_is_host_only_and_monotone():
     (dict(kv_tile_stride=512), ts.TS_ERR_SHAPE),      # smaller than one S*d tile
     (dict(kv_tile_stride=2052), ts.TS_ERR_SHAPE),     # tiles must stay 16-byte aligned
     (dict(head_dim=96), ts.TS_ERR_UNSUPPORTED),
-    (dict(page_size=8), ts.TS_ERR_UNSUPPORTED),
+    (dict(page_size=12), ts.TS_ERR_UNSUPPORTED),
     (dict(num_q_heads=64, num_kv_heads=2), ts.TS_ERR_UNSUPPORTED),
     (dict(max_pages_per_seq=1 << 20), ts.TS_ERR_UNSUPPORTED),
     (dict(page_min=None), ts.TS_ERR_NULL),
@@ -91,9 +91,9 @@ def test_argument_validation():
     assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 0, None, 8, p, p, None) == ts.TS_ERR_SHAPE
     assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 9, None, 8, p, p, None) == ts.TS_ERR_SHAPE
     assert lib.ts_select_topk_pages(ctypes.byref(lay), p, 4, None, 8, None, p, None) == ts.TS_ERR_NULL
-    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, p, p, 16,
+    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, p, None, p, 16,
                                           None) == ts.TS_ERR_WORKSPACE
-    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, None, p, big,
+    assert lib.ts_sparse_decode_attention(ctypes.byref(lay), p, p, p, 8, 1.0, None, None, p, big,
                                           None) == ts.TS_ERR_NULL
     assert lib.ts_query_aware_decode(ctypes.byref(lay), p, 4, None, 8, 1.0, p, None, None, None, p,
                                      16, None) == ts.TS_ERR_WORKSPACE
@@ -105,8 +105,10 @@ def test_argument_validation():
                                     None, p, big, None) == ts.TS_ERR_NULL
     assert lib.ts_append_and_decode(ctypes.byref(lay), p, p, p, 4, None, 8, 1.0, p, None, None,
                                     None, p, 16, None) == ts.TS_ERR_WORKSPACE
-    assert lib.ts_dense_decode_attention(ctypes.byref(lay), p, 1.0, p, p, 16, None) == ts.TS_ERR_WORKSPACE
-    assert lib.ts_dense_decode_attention(ctypes.byref(lay), None, 1.0, p, p, big, None) == ts.TS_ERR_NULL
+    assert lib.ts_dense_decode_attention(ctypes.byref(lay), p, 1.0, p, None, p, 16,
+                                         None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_dense_decode_attention(ctypes.byref(lay), None, 1.0, p, None, p, big,
+                                         None) == ts.TS_ERR_NULL
     assert lib.ts_dense_workspace_bytes(ctypes.byref(lay)) > 0
     assert lib.ts_dense_workspace_bytes(ctypes.byref(_layout(head_dim=96))) == 0
     assert lib.ts_workspace_init(None, 1024, None) == ts.TS_ERR_NULL

@@ -99,6 +99,15 @@ REDUCED = {
     "gqa4_d128_s32": wl.WorkloadSpec("gqa4_d128_s32", 2, 8, 2, 128, 32, 2500, 9),
     "gqa16_d64_s16": wl.WorkloadSpec("gqa16", 1, 16, 1, 64, 16, 1030, 70),
     "k_exceeds_p": wl.WorkloadSpec("k_exceeds_p", 2, 2, 2, 64, 16, 100, 32),
+    # pages smaller than an MFMA tile (four / two pages per 16-token fragment; list lengths
+    # that are no multiple of the group, a one-token last page)
+    "gqa8_d64_s4": wl.WorkloadSpec("s4", 2, 16, 2, 64, 4, 1501, 90, keys="offset"),
+    "gqa2_d128_s4": wl.WorkloadSpec("s4b", 2, 4, 2, 128, 4, 703, 33),
+    "mha_d128_s8": wl.WorkloadSpec("s8", 3, 4, 4, 128, 8, 1003, 37),
+    "mha_d64_s8_ragged": wl.WorkloadSpec("s8r", 5, 4, 4, 64, 8, 900, 0, L_min=1, budget_frac=0.25),
+    # 64-token pages (two 32-token fragments each); last page 8 and 40 tokens long
+    "gqa4_d64_s64": wl.WorkloadSpec("s64", 2, 8, 2, 64, 64, 5000, 11, keys="walk"),
+    "mha_d128_s64": wl.WorkloadSpec("s64b", 2, 4, 4, 128, 64, 3048, 7),
 }
 
 
@@ -241,6 +250,10 @@ APPEND_FUSED = {
     "mha_d128_s16_many": wl.WorkloadSpec("af2", 72, 4, 4, 128, 16, 300, 5, L_min=1, headroom=48),
     "gqa8_d64_s32": wl.WorkloadSpec("af3", 3, 16, 2, 64, 32, 700, 7, keys="walk", headroom=80),
     "gqa2_d128_s32": wl.WorkloadSpec("af4", 2, 4, 2, 128, 32, 500, 4, headroom=80),
+    "gqa4_d64_s4": wl.WorkloadSpec("af5", 3, 8, 2, 64, 4, 150, 9, L_min=1, headroom=48),
+    "mha_d128_s8": wl.WorkloadSpec("af6", 2, 4, 4, 128, 8, 300, 6, headroom=80),
+    "gqa2_d64_s64": wl.WorkloadSpec("af7", 2, 4, 2, 64, 64, 1000, 4, headroom=128),
+    "mha_d128_s64": wl.WorkloadSpec("af8", 3, 2, 2, 128, 64, 700, 3, L_min=1, headroom=128),
 }
 
 
@@ -302,6 +315,14 @@ MANY_UNITS = {
     "d128_s16": wl.WorkloadSpec("mu3", 70, 4, 4, 128, 16, 500, 0, L_min=1, budget_frac=0.3,
                                 headroom=32),
     "d128_s32": wl.WorkloadSpec("mu4", 36, 16, 8, 128, 32, 800, 5, L_min=1, headroom=64),
+    "d64_s4": wl.WorkloadSpec("mu5", 80, 4, 4, 64, 4, 300, 11, L_min=1, headroom=32),
+    "d64_s8": wl.WorkloadSpec("mu6", 40, 16, 8, 64, 8, 500, 0, L_min=1, budget_frac=0.2,
+                              headroom=32),
+    "d64_s64": wl.WorkloadSpec("mu7", 40, 16, 8, 64, 64, 1500, 5, L_min=1, headroom=128),
+    "d128_s4": wl.WorkloadSpec("mu8", 36, 16, 8, 128, 4, 250, 14, L_min=1, headroom=32),
+    "d128_s8": wl.WorkloadSpec("mu9", 70, 4, 4, 128, 8, 400, 0, L_min=1, budget_frac=0.3,
+                               headroom=32),
+    "d128_s64": wl.WorkloadSpec("mu10", 72, 4, 4, 128, 64, 1200, 4, L_min=1, headroom=128),
 }
 
 
@@ -359,29 +380,75 @@ def test_query_sums_read_back_through_one_hot_boxes(built):
         assert torch.equal(sess.scores[:, :, :128], qp), f"launch {i}"
 
 
+LSE_ATOL = 2e-3   # log of the softmax denominator, absolute (fp32 sums of bf16 products)
+
+
 @pytest.mark.parametrize("name", ["mha_d64_s16", "gqa8_d64_s32_walk", "mha_d128_s16_ragged",
-                                  "gqa4_d128_s32", "k_exceeds_p"])
+                                  "gqa4_d128_s32", "k_exceeds_p", "gqa8_d64_s4", "mha_d128_s8",
+                                  "gqa4_d64_s64", "mha_d128_s64"])
 def test_dense_baseline_matches_oracle(oracle, built, name):
     """ts_dense_decode_attention (attention over the whole cache, the comparison the
-    paper measures against) against the oracle's dense softmax attention."""
+    paper measures against) against the oracle's dense softmax attention, output and
+    log-denominator."""
     spec = REDUCED[name]
     print(f"[case] dense {name}", flush=True)
     w = wl.make_workload(spec, DEV, seed=11, n_q=1)
     sess = Session(w)
     scale = 1.0 / math.sqrt(spec.d)
     ws = ts.new_dense_workspace(sess.layout, DEV)
-    ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws)
+    lse = torch.full((spec.B, spec.Hq), float("nan"), dtype=torch.float32, device=DEV)
+    ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws, lse_out=lse)
     torch.cuda.synchronize()
     K, V = wl.logical_kv(w)
-    ref = oracle.dense_decode_attention(wl.bits(w.q[0]), wl.bits(K), wl.bits(V),
-                                        w.seq_lens.cpu().numpy(), scale)
+    ref, ref_lse = oracle.dense_decode_attention(wl.bits(w.q[0]), wl.bits(K), wl.bits(V),
+                                                 w.seq_lens.cpu().numpy(), scale, return_lse=True)
     err = np.abs(sess.out.cpu().numpy().astype(np.float64) - ref).max()
     assert err <= 2e-3, f"dense attention off by {err}"
-    # a second call on the same workspace (counters left re-armed)
+    err = np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max()
+    assert err <= LSE_ATOL, f"dense log-denominator off by {err}"
+    # a second call on the same workspace (counters left re-armed), without the extra output
     first = sess.out.clone()
     ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws)
     torch.cuda.synchronize()
     assert torch.equal(first, sess.out)
+
+
+@pytest.mark.parametrize("name", ["gqa8_d64_s16_offset", "gqa8_d64_s32_walk", "mha_d128_s16_ragged",
+                                  "gqa2_d128_s4", "mha_d64_s8_ragged", "gqa4_d64_s64"])
+@pytest.mark.parametrize("splits", [0, 3], indirect=True)
+def test_selected_mass_matches_oracle(oracle, built, name, splits):
+    """The log-denominator of ts_sparse_decode_attention over the selected pages, and
+    from it the share of the dense softmax mass the selection captures,
+    exp(lse_selected - lse_dense), against the oracle on the same selection."""
+    spec = REDUCED[name]
+    print(f"[case] selected mass {name} splits={splits}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=13, n_q=1)
+    sess = Session(w)
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    ts.score_pages(sess.layout, w.q[0], sess.scores)
+    ts.select_topk_pages(sess.layout, sess.scores, w.topk, w.K_max, sess.sel, sess.sel_count,
+                         topk_per_seq=w.topk_per_seq)
+    lse_s = torch.full((spec.B, spec.Hq), float("nan"), dtype=torch.float32, device=DEV)
+    lse_d = torch.full_like(lse_s, float("nan"))
+    ts.sparse_decode_attention(sess.layout, w.q[0], sess.sel, sess.sel_count, w.K_max, scale,
+                               sess.out, sess.ws, lse_out=lse_s)
+    dws = ts.new_dense_workspace(sess.layout, DEV)
+    dense_out = torch.empty_like(sess.out)
+    ts.dense_decode_attention(sess.layout, w.q[0], scale, dense_out, dws, lse_out=lse_d)
+    torch.cuda.synchronize()
+    K, V = wl.logical_kv(w)
+    args = (wl.bits(w.q[0]), wl.bits(K), wl.bits(V))
+    lens = w.seq_lens.cpu().numpy()
+    o_out, o_lse = oracle.sparse_decode_attention(*args, sess.sel.cpu().numpy(),
+                                                  sess.sel_count.cpu().numpy(), lens, spec.S, scale,
+                                                  return_lse=True)
+    _, o_dense = oracle.dense_decode_attention(*args, lens, scale, return_lse=True)
+    assert np.abs(sess.out.cpu().numpy() - o_out).max() <= 2e-3
+    assert np.abs(lse_s.cpu().numpy() - o_lse).max() <= LSE_ATOL
+    mass = torch.exp(lse_s - lse_d).cpu().numpy().astype(np.float64)
+    o_mass = np.exp(o_lse - o_dense)
+    assert np.all(mass <= 1.0 + 1e-2) and np.abs(mass - o_mass).max() <= 5e-3
 
 
 @pytest.mark.parametrize("splits", [0, 4], indirect=True)
@@ -449,6 +516,26 @@ def test_degenerate_lengths(oracle, built):
     assert torch.all(sess.out[0] == 0)          # no token: zeros
     sess.staged(0.125)
     compare_units(oracle, sess, units, 0.125, what="degenerate/staged")
+
+
+@pytest.mark.parametrize("S", [4, 8, 64])
+def test_full_size_other_page_sizes(oracle, built, S):
+    """The TinyLLaMA-shaped workload with the page size of the paper's page-size
+    ablation (Table 7: 16K context, budget 2048 tokens), default launch shape,
+    sampled units; one step through the launch that appends."""
+    spec = wl.scaled(wl.SPECS["tinyllama"], S=S, topk=2048 // S)
+    print(f"[case] full tinyllama S={S}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=1200 + S, n_q=2, n_new=1)
+    sess = Session(w)
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    units = unit_samples(w, 6, seed=4)
+    sess.fused(scale, q_idx=1)
+    compare_units(oracle, sess, units, scale, q_idx=1, what=f"full/S{S}")
+    ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[0], w.topk, w.K_max, scale,
+                         sess.out, sess.ws, scores_out=sess.scores, sel_out=sess.sel,
+                         sel_count_out=sess.sel_count)
+    compare_units(oracle, sess, units, scale, q_idx=0, what=f"full/S{S}/append")
 
 
 FULL = ["tiny", "gpt2_345m", "tinyllama", "longctx", "ragged"]
