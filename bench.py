@@ -115,6 +115,26 @@ def time_region(torch, fn, n):
     return (t1 - t0), e0.elapsed_time(e1) * 1e-3
 
 
+def capture_graph(torch, layers, body, per_graph):
+    """Capture per_graph calls of body(layer, stream), rotating over the layers (kernel
+    nodes only, no memset nodes)."""
+    n_layers = len(layers)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gstream = ctypes.c_void_p(side.cuda_stream)
+        for i in range(n_layers):       # warm the kernels on the capture stream
+            body(layers[i], gstream)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for i in range(per_graph):
+                body(layers[i % n_layers], gstream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    return g
+
+
 def cpu_baseline(spec, layer, wl, budget_s=20.0):
     """The CPU oracle, as it stands, on the same step (score + select + attend over
     the layer's metadata and KV) for a bounded number of sequences / repetitions."""
@@ -237,22 +257,7 @@ def main():
     per_graph = n_layers * max(1, -(-8 // n_layers))
 
     def capture(body):
-        """Capture per_graph steps, rotating over the layers (kernel nodes only, no memset
-        nodes)."""
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            gstream = ctypes.c_void_p(side.cuda_stream)
-            for i in range(n_layers):       # warm the kernels on the capture stream
-                body(layers[i], gstream)
-            side.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                for i in range(per_graph):
-                    body(layers[i % n_layers], gstream)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        return g
+        return capture_graph(torch, layers, body, per_graph)
 
     def body_step(ly, st):
         if one_launch:

@@ -75,9 +75,11 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   if (g > kMaxCluster) g = kMaxCluster;
   // Short sequences: a cluster's exchange and merge (a few microseconds of
   // waiting on the slowest member) cost more than one workgroup needs to score
-  // ~600 pages and attend ~80 by itself (measured on the 256- and 512-page
-  // configurations).
-  if (target_workgroups == kTargetWorkgroups && Pmax <= 640 && max_topk <= 80) g = 1;
+  // ~600 pages and attend ~1300 tokens by itself (measured on the 256- and
+  // 512-page configurations with 16-token pages).
+  if (target_workgroups == kTargetWorkgroups && Pmax <= 640 &&
+      (long long)max_topk * L->page_size <= 1280)
+    g = 1;
   if (g_tune_splits > 0 && target_workgroups == kTargetWorkgroups)
     g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
   if (g > max_topk) g = max_topk;
