@@ -48,7 +48,7 @@ static double bf16_to_double(uint16_t bits) {
 
 static int pages_of(int len, int S) { return (len + S - 1) / S; }
 
-int tso_version(void) { return 2; }
+int tso_version(void) { return 3; }
 
 int tso_max_threads(void) {
 #ifdef _OPENMP
@@ -159,11 +159,13 @@ void tso_score_pages(const uint16_t* q, const uint16_t* page_min, const uint16_t
 typedef struct {
   double score;
   int32_t id;
+  int32_t forced;
 } tso_cand;
 
 static int cand_before(const void* pa, const void* pb) {
   const tso_cand* a = (const tso_cand*)pa;
   const tso_cand* b = (const tso_cand*)pb;
+  if (a->forced != b->forced) return b->forced - a->forced; /* always-kept pages first */
   if (a->score > b->score) return -1;
   if (a->score < b->score) return 1;
   return (a->id > b->id) - (a->id < b->id); /* equal scores: lower page id first */
@@ -180,10 +182,17 @@ static int int_asc(const void* pa, const void* pb) {
  * topk_per_seq[b] when that pointer is non-NULL, else topk.
  * gap (nullable) receives, per (b, h), the relative distance between the last
  * kept and the first dropped score, |s_K - s_{K+1}| / max(|s_K|, |s_{K+1}|),
- * or +inf when nothing is dropped. */
+ * or +inf when nothing is dropped or the last kept page is an always-kept one.
+ *
+ * The paper selects by score alone (keep_first = keep_last = 0).  As an option
+ * outside the paper, the first keep_first pages of a sequence (attention sinks)
+ * and its last keep_last pages (the newest tokens) can be kept whatever their
+ * score: they rank ahead of every other page (among themselves by page id) and
+ * count towards K_b. */
 void tso_select_topk_pages(const double* scores, const int32_t* seq_lens, int B, int Hkv, int S,
                            int Pmax, int topk, const int32_t* topk_per_seq, int Kmax,
-                           int32_t* sel, int32_t* sel_count, double* gap) {
+                           int keep_first, int keep_last, int32_t* sel, int32_t* sel_count,
+                           double* gap) {
   tso_cand* cand = (tso_cand*)malloc(sizeof(tso_cand) * (size_t)(Pmax > 0 ? Pmax : 1));
   for (int b = 0; b < B; ++b) {
     int Pb = pages_of(seq_lens[b], S);
@@ -199,13 +208,15 @@ void tso_select_topk_pages(const double* scores, const int32_t* seq_lens, int B,
       for (int j = 0; j < Pb; ++j) {
         cand[j].score = s[j];
         cand[j].id = j;
+        cand[j].forced = (j < keep_first || j >= Pb - keep_last) ? 1 : 0;
+        if (cand[j].forced) cand[j].score = 0.0; /* forced pages rank by id alone */
       }
       qsort(cand, (size_t)Pb, sizeof(tso_cand), cand_before);
       for (int i = 0; i < Kmax; ++i) row[i] = i < Kb ? cand[i].id : -1;
       qsort(row, (size_t)Kb, sizeof(int32_t), int_asc);
       if (gap) {
         double g = INFINITY;
-        if (Kb > 0 && Kb < Pb) {
+        if (Kb > 0 && Kb < Pb && !cand[Kb - 1].forced) {
           double a = cand[Kb - 1].score, c = cand[Kb].score;
           double den = fabs(a) > fabs(c) ? fabs(a) : fabs(c);
           g = den > 0.0 ? fabs(a - c) / den : 0.0;
@@ -320,11 +331,11 @@ void tso_query_aware_decode(const uint16_t* q, const uint16_t* K, const uint16_t
                             const uint16_t* page_min, const uint16_t* page_max,
                             const int32_t* seq_lens, int B, int Hq, int Hkv, int Lmax, int d,
                             int S, int Pmax, int topk, const int32_t* topk_per_seq, int Kmax,
-                            double scale, double* scores, int32_t* sel, int32_t* sel_count,
-                            double* gap, double* out) {
+                            int keep_first, int keep_last, double scale, double* scores,
+                            int32_t* sel, int32_t* sel_count, double* gap, double* out) {
   tso_score_pages(q, page_min, page_max, seq_lens, B, Hq, Hkv, d, S, Pmax, 0, scores);
-  tso_select_topk_pages(scores, seq_lens, B, Hkv, S, Pmax, topk, topk_per_seq, Kmax, sel,
-                        sel_count, gap);
+  tso_select_topk_pages(scores, seq_lens, B, Hkv, S, Pmax, topk, topk_per_seq, Kmax, keep_first,
+                        keep_last, sel, sel_count, gap);
   tso_sparse_decode_attention(q, K, V, sel, sel_count, seq_lens, B, Hq, Hkv, Lmax, d, S, Kmax,
                               scale, out, NULL);
 }

@@ -99,7 +99,8 @@ def score_pages(q, page_min, page_max, seq_lens, S, form=0):
     return scores
 
 
-def select_topk_pages(scores, seq_lens, S, topk, Kmax, topk_per_seq=None):
+def select_topk_pages(scores, seq_lens, S, topk, Kmax, topk_per_seq=None, keep_first=0,
+                      keep_last=0):
     scores = np.ascontiguousarray(scores, dtype=np.float64)
     B, Hkv, Pmax = scores.shape
     seq_lens = _i32(seq_lens)
@@ -108,7 +109,7 @@ def select_topk_pages(scores, seq_lens, S, topk, Kmax, topk_per_seq=None):
     cnt = np.empty((B,), dtype=np.int32)
     gap = np.empty((B, Hkv), dtype=np.float64)
     _load().tso_select_topk_pages(_p(scores), _p(seq_lens), B, Hkv, S, Pmax, int(topk), _p(tps),
-                                  Kmax, _p(sel), _p(cnt), _p(gap))
+                                  Kmax, int(keep_first), int(keep_last), _p(sel), _p(cnt), _p(gap))
     return sel, cnt, gap
 
 
@@ -139,7 +140,7 @@ def dense_decode_attention(q, K, V, seq_lens, scale, return_lse=False):
 
 
 def query_aware_decode(q, K, V, page_min, page_max, seq_lens, S, topk, Kmax, scale,
-                       topk_per_seq=None):
+                       topk_per_seq=None, keep_first=0, keep_last=0):
     """score -> select -> attend.  Returns dict(scores, sel, sel_count, gap, out)."""
     q, K, V = _u16(q), _u16(K), _u16(V)
     page_min, page_max = _u16(page_min), _u16(page_max)
@@ -155,7 +156,7 @@ def query_aware_decode(q, K, V, page_min, page_max, seq_lens, S, topk, Kmax, sca
     out = np.empty((B, Hq, d), dtype=np.float64)
     _load().tso_query_aware_decode(_p(q), _p(K), _p(V), _p(page_min), _p(page_max), _p(seq_lens),
                                    B, Hq, Hkv, Lmax, d, S, Pmax, int(topk), _p(tps), Kmax,
-                                   ctypes.c_double(scale), _p(scores), _p(sel), _p(cnt), _p(gap),
+                                   int(keep_first), int(keep_last), ctypes.c_double(scale), _p(scores), _p(sel), _p(cnt), _p(gap),
                                    _p(out))
     return dict(scores=scores, sel=sel, sel_count=cnt, gap=gap, out=out)
 

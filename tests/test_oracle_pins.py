@@ -330,6 +330,39 @@ def test_tie_break_prefers_lower_page_id(oracle):
 # ----------------------------------------------------------------------------
 # incremental metadata == metadata rebuilt from scratch, after every append
 # ----------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(8))
+def test_always_kept_pages(oracle, seed):
+    """Optional always-kept pages (first keep_first, last keep_last of each sequence):
+    against an independent numpy ranking in which those pages get +inf, on random
+    scores with ties; with both counts zero the plain selection is unchanged."""
+    rng = np.random.default_rng(500 + seed)
+    B, Hkv, S, Pmax = 3, 2, 4, 40
+    lens = rng.integers(0, Pmax * S + 1, size=B).astype(np.int32)
+    lens[0] = Pmax * S
+    sc = np.round(rng.standard_normal((B, Hkv, Pmax)) * 4) / 4        # ties are common
+    kf, kl = int(rng.integers(0, 4)), int(rng.integers(0, 5))
+    K = int(rng.integers(1, 12))
+    Kmax = 12
+    sel, cnt, gap = oracle.select_topk_pages(sc, lens, S, K, Kmax, keep_first=kf, keep_last=kl)
+    for b in range(B):
+        Pb = -(-int(lens[b]) // S)
+        Kb = min(K, Pb)
+        assert cnt[b] == Kb
+        for h in range(Hkv):
+            s = sc[b, h, :Pb].copy()
+            forced = np.array([j < kf or j >= Pb - kl for j in range(Pb)], dtype=bool)
+            s[forced] = np.inf
+            order = np.lexsort((np.arange(Pb), -s))          # score descending, then id ascending
+            expect = sorted(order[:Kb].tolist())
+            assert sel[b, h, :Kb].tolist() == expect
+            assert np.all(sel[b, h, Kb:] == -1)
+            if forced.sum() <= Kb:                            # every always-kept page is in
+                assert set(np.nonzero(forced)[0].tolist()) <= set(expect)
+    plain = oracle.select_topk_pages(sc, lens, S, K, Kmax)
+    zero = oracle.select_topk_pages(sc, lens, S, K, Kmax, keep_first=0, keep_last=0)
+    assert all(np.array_equal(a, b) for a, b in zip(plain, zero))
+
+
 def test_append_equals_rebuild(oracle):
     rng = np.random.default_rng(21)
     B, Hkv, d, S = 3, 2, 8, 4
