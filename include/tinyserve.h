@@ -51,7 +51,8 @@ typedef enum ts_status {
   TS_OK = 0,
   TS_ERR_NULL = -1,        /* a required pointer is NULL                                   */
   TS_ERR_SHAPE = -2,       /* non-positive dimension, Hq % Hkv != 0, topk < 1, max_topk < topk,
-                              0 < kv_tile_stride < S*d or not a multiple of 8 */
+                              0 < kv_tile_stride < S*d or not a multiple of 8, a negative
+                              keep_*_pages count */
   TS_ERR_UNSUPPORTED = -3, /* head_dim / page_size / group size / page count outside the built set */
   TS_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than ts_workspace_bytes()             */
   TS_ERR_LAUNCH = -5,      /* the HIP runtime reported an error when enqueueing             */
@@ -90,6 +91,13 @@ typedef struct ts_layout {
   int32_t* seq_lens;
   void* page_min;
   void* page_max;
+  /* Selection option outside the paper (which selects by score alone; leave both 0
+   * for that): the first keep_first_pages pages of every sequence (attention
+   * sinks) and its last keep_last_pages pages (the newest tokens) are selected
+   * whatever their score.  They count towards K; if they alone exceed it, the
+   * lowest page ids among them are kept. */
+  int32_t keep_first_pages;
+  int32_t keep_last_pages;
 } ts_layout;
 
 /* Section 3.4 / Eq. 1.  Rebuilds page_min / page_max of every page j < P_b of
@@ -118,7 +126,9 @@ int ts_score_pages(const ts_layout* layout, const void* q, float* scores, void* 
  * equal scores resolved in favour of the lower page id; K = topk_per_seq[b] if
  * that pointer is non-NULL, else topk.  sel: int32 [B][Hkv][max_topk], page
  * ids ascending, padded with -1.  sel_count: int32 [B] = K_b.  The comparison
- * is on the fp32 values as given (-0 ranks equal to +0; NaN is undefined). */
+ * is on the fp32 values as given (-0 ranks equal to +0; NaN is undefined).
+ * layout->keep_first_pages / keep_last_pages (see ts_layout) are honoured here
+ * and in the fused calls. */
 int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t topk,
                          const int32_t* topk_per_seq, int32_t max_topk, int32_t* sel,
                          int32_t* sel_count, void* stream);

@@ -129,6 +129,7 @@ struct FusedParams {
   const uint16_t* k_new;   // [B][Hkv][D]
   const uint16_t* v_new;
   int topk, S, units, g, cstride, B;
+  int keep_first, keep_last;   // pages kept whatever their score (0, 0: the paper's selection)
 };
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
@@ -157,7 +158,8 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
                                                                const int32_t* seq_lens, int topk,
                                                                const int32_t* topk_per_seq,
                                                                int32_t* sel, int32_t* sel_count,
-                                                               int Hkv, int S, int Pmax, int Kmax) {
+                                                               int Hkv, int S, int Pmax, int Kmax,
+                                                               int keep_first, int keep_last) {
   extern __shared__ __align__(16) unsigned char smem[];
   TS_MARK_INIT();
   TS_MARK(0);
@@ -173,6 +175,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
   // eight loads per thread in flight per round (a plain loop would pay one
   // memory round trip per iteration); the key range is gathered on the way
   const KeyLayout kl = KeyLayout::make(Pb);
+  const ForcedPages fp = ForcedPages::make(keep_first, keep_last, Pb);
   uint32_t tmin = 0xffffffffu, tmax = 0u;
   for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
     float v[8];
@@ -183,16 +186,17 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
       const int j = j0 + i * kThreads;
       if (j < Pb) {
         const uint32_t k = score_key(v[i]);
-        L.keys[kl.at(j)] = k;
-        tmin = min(tmin, k);
-        tmax = max(tmax, k);
+        const bool forced = fp.has(j);
+        L.keys[kl.at(j)] = forced ? kForcedKey : k;
+        tmin = forced ? tmin : min(tmin, k);
+        tmax = forced ? tmax : max(tmax, k);
       }
     }
   }
   select_begin(L, tmin, tmax);
   __syncthreads();
   TS_MARK(1);
-  select_topk_lds(L, kl, Pb, Kb, [&](int rank, int page) { row[rank] = page; });
+  select_topk_lds(L, kl, Pb, Kb, fp, [&](int rank, int page) { row[rank] = page; });
   TS_MARK(5);
 }
 
@@ -342,6 +346,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 
     // 1. score my share of the pages; the unit's block-table row is parked in LDS
     KeyLayout kl;
+    ForcedPages fp;
     int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
@@ -371,6 +376,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           pb_scan = uniform(min(pages_of(L_unit, S), Pmax));
           kl = KeyLayout::make(pb_scan);
+          fp = ForcedPages::make(p.keep_first, p.keep_last, pb_scan);
           return pb_scan;
         },
         [&](uint4& mn, uint4& mx, int pg) {
@@ -391,9 +397,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
             store_agent_tagged(srow + pg, s, tag);
           } else if (pg < pb_scan) {
             const uint32_t k = score_key(s);
-            sl.keys[kl.at(pg)] = k;
-            tmin = min(tmin, k);
-            tmax = max(tmax, k);
+            const bool forced = fp.has(pg);
+            sl.keys[kl.at(pg)] = forced ? kForcedKey : k;
+            tmin = forced ? tmin : min(tmin, k);
+            tmax = forced ? tmax : max(tmax, k);
           }
           if (srow_out) srow_out[pg] = s;
         });
@@ -433,9 +440,10 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           const int j = j0 + i * kThreads;
           if (j < Pb) {
             const uint32_t k = score_key(__uint_as_float((uint32_t)v[i]));
-            sl.keys[kl.at(j)] = k;
-            tmin = min(tmin, k);
-            tmax = max(tmax, k);
+            const bool forced = fp.has(j);
+            sl.keys[kl.at(j)] = forced ? kForcedKey : k;
+            tmin = forced ? tmin : min(tmin, k);
+            tmax = forced ? tmax : max(tmax, k);
           }
         }
       }
@@ -477,7 +485,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (sel_row)
       for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
     if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
-    select_topk_lds(sl, kl, Pb, Kb, [&](int rank, int page) {
+    select_topk_lds(sl, kl, Pb, Kb, fp, [&](int rank, int page) {
       if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
       if (sel_row) sel_row[rank] = page;
     });
@@ -575,6 +583,7 @@ static int check_layout(const ts_layout* L) {
   if (L->num_q_heads / L->num_kv_heads > 16) return TS_ERR_UNSUPPORTED;
   if (L->max_pages_per_seq > TS_MAX_PAGES_PER_SEQ) return TS_ERR_UNSUPPORTED;
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
+  if (L->keep_first_pages < 0 || L->keep_last_pages < 0) return TS_ERR_SHAPE;
   return TS_OK;
 }
 
@@ -720,6 +729,8 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.v_new = static_cast<const uint16_t*>(v_new);
   p.B = layout->num_seqs;
   p.topk = topk;
+  p.keep_first = layout->keep_first_pages;
+  p.keep_last = layout->keep_last_pages;
   p.S = layout->page_size;
   p.units = pl.units;
   p.g = pl.g;
@@ -895,7 +906,8 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
   if ((st = allow_lds(select_topk_kernel, lds)) != TS_OK) return st;
   select_topk_kernel<<<units, kThreads, lds, (hipStream_t)stream>>>(
       scores, layout->seq_lens, topk, topk_per_seq, sel, sel_count, layout->num_kv_heads,
-      layout->page_size, layout->max_pages_per_seq, max_topk);
+      layout->page_size, layout->max_pages_per_seq, max_topk, layout->keep_first_pages,
+      layout->keep_last_pages);
   return launch_status();
 }
 

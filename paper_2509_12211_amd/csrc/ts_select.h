@@ -24,6 +24,30 @@ __device__ __forceinline__ float key_score(uint32_t k) {
   return (k & 0x80000000u) ? __uint_as_float(k & 0x7fffffffu) : __uint_as_float(~k);
 }
 
+// Pages kept whatever their score (an option outside the paper: the first pages
+// of a sequence as attention sinks, its last pages as the newest tokens).  They
+// carry the key kForcedKey, above every score's key, so they rank ahead of all
+// other pages and among themselves by page id; callers leave them out of the key
+// range they hand to select_begin.
+constexpr uint32_t kForcedKey = 0xffffffffu;
+struct ForcedPages {
+  int first;       // pages [0, first) are kept
+  int last_begin;  // pages [last_begin, Pb) are kept; first <= last_begin <= Pb
+  int count;       // first + Pb - last_begin
+  __device__ __forceinline__ static ForcedPages make(int keep_first, int keep_last, int Pb) {
+    ForcedPages f;
+    f.first = min(max(keep_first, 0), Pb);
+    f.last_begin = max(f.first, Pb - max(keep_last, 0));
+    f.count = f.first + Pb - f.last_begin;
+    return f;
+  }
+  __device__ __forceinline__ bool has(int page) const { return page < first || page >= last_begin; }
+  // key of a page's score for the selection
+  __device__ __forceinline__ uint32_t key(int page, uint32_t score_key_of_page) const {
+    return has(page) ? kForcedKey : score_key_of_page;
+  }
+};
+
 constexpr int kRadixBits = 11;
 constexpr int kRadixBins = 1 << kRadixBits;
 static_assert(TS_MAX_PAGES_PER_SEQ / kThreads <= 64, "a thread's chunk must fit a 64-bit mask");
@@ -111,9 +135,12 @@ __device__ __forceinline__ void select_begin(const SelectLds& L, uint32_t tmin, 
 // listed in LDS and every wave ranks them directly; only a cut-off bin with
 // more than kMaxCandidates pages (heavy ties) goes through exact radix passes
 // on the integer keys instead.
+//
+// fp: the always-kept pages (their keys are kForcedKey: linear_slot puts them
+// into the top bin, everything after that works on the integer keys).
 template <typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLayout& kl, int Pb,
-                                                int Kb, Emit emit) {
+                                                int Kb, const ForcedPages& fp, Emit emit) {
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   static_assert(kWaves <= 8, "red[] layout holds 8 wave slots");
   constexpr int kBatch = 8;  // LDS reads issued together
@@ -122,6 +149,10 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   if (Kb <= 0) return;
   if (Kb >= Pb) {  // everything is kept
     for (int j = tid; j < Pb; j += kThreads) emit(j, j);
+    return;
+  }
+  if (fp.count >= Kb) {  // the always-kept pages fill the budget: the Kb lowest ids of them
+    for (int r = tid; r < Kb; r += kThreads) emit(r, r < fp.first ? r : fp.last_begin + (r - fp.first));
     return;
   }
   const int C = kl.C;
@@ -193,8 +224,9 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   TS_MARK(10);
   const float smin = key_score(kmin);
   const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
-  auto linear_slot = [&](uint32_t k) {   // 0 = highest scores
-    return kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
+  auto linear_slot = [&](uint32_t k) {   // 0 = highest scores (and the always-kept pages)
+    const int s = kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
+    return k == kForcedKey ? 0 : s;
   };
   int need = Kb, cut_slot = 0;
   // how the pages at the cut are told apart from those above it
@@ -275,7 +307,10 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   //   kRadix      g: above the cut;  e: keys k with k - clo in [base, base + 2^bits),
   //               one exact value when bits == 0
   // (all keys equal: kRadix with bits == 0, every page is e)
-  if (!(kmax > kmin)) mode = kRadix;
+  if (!(kmax > kmin)) {  // all scores equal: the always-kept pages, then the lowest ids
+    mode = kRadix;
+    need = Kb - fp.count;
+  }
   auto classify = [&](uint32_t k, int page) -> int {   // bit 0: g, bit 1: e
     if (mode == kWholeSlot) return linear_slot(k) <= cut_slot ? 1 : 0;
     if (mode == kThreshold) return (k > key_t || (k == key_t && page <= page_t)) ? 1 : 0;

@@ -40,6 +40,7 @@ class TsLayout(ctypes.Structure):
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
         ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
         ("page_min", ctypes.c_void_p), ("page_max", ctypes.c_void_p),
+        ("keep_first_pages", ctypes.c_int32), ("keep_last_pages", ctypes.c_int32),
     ]
 
 
@@ -104,7 +105,7 @@ def _check(status, where):
 
 
 def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, page_min,
-                page_max) -> TsLayout:
+                page_max, keep_first_pages=0, keep_last_pages=0) -> TsLayout:
     """Fill the C struct; tensors must stay alive while calls using it are in flight."""
     n_phys = 0 if k_pool is None else k_pool.shape[0]
     tile_stride = 0
@@ -121,7 +122,8 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                    None if block_table is None else block_table.data_ptr(),
                    None if seq_lens is None else seq_lens.data_ptr(),
                    None if page_min is None else page_min.data_ptr(),
-                   None if page_max is None else page_max.data_ptr())
+                   None if page_max is None else page_max.data_ptr(),
+                   int(keep_first_pages), int(keep_last_pages))
     return lay
 
 

@@ -19,6 +19,11 @@ correlated random-walk keys.  The token budget is the one of the named
 benchmark configuration (2048 and 1024 tokens).
 
 Prints one JSON line per configuration, then a table.
+
+--reuse measures instead the overlap of the page sets selected by consecutive
+decode steps, |S_t and S_t+1| / K (the reuse of Section 3.6's cost model), on
+the long-context random-walk workload, for query sequences of different
+step-to-step correlation, with and without always-kept first / last pages.
 """
 from __future__ import annotations
 
@@ -98,8 +103,66 @@ def measure(torch, ts, wl, spec, steps, dev):
     }
 
 
+def reuse(torch, ts, wl, steps, dev):
+    """Overlap of consecutive selections.  The query of step t+1 is
+    a * q_t + sqrt(1 - a^2) * noise (a = 0: independent queries)."""
+    base = wl.SPECS["longctx"]
+    rows = []
+    for keep in [(0, 0), (1, 2)]:
+        for a in [0.0, 0.9, 0.99, 0.999]:
+            spec = wl.scaled(base, headroom=steps + 64)
+            w = wl.make_workload(spec, dev, seed=1003, n_q=1, n_new=steps, poison=0.0)
+            pmin = torch.zeros((spec.B, spec.Hkv, w.P_max, spec.d), dtype=torch.bfloat16, device=dev)
+            pmax = torch.zeros_like(pmin)
+            lens = w.seq_lens.clone()
+            lay = ts.make_layout(spec.B, spec.Hq, spec.Hkv, spec.d, spec.S, w.P_max, w.k_pool,
+                                 w.v_pool, w.block_table, lens, pmin, pmax,
+                                 keep_first_pages=keep[0], keep_last_pages=keep[1])
+            ts.build_page_meta(lay)
+            ws = ts.new_workspace(lay, w.K_max, dev)
+            out = torch.empty((spec.B, spec.Hq, spec.d), dtype=torch.float32, device=dev)
+            sel = torch.empty((spec.B, spec.Hkv, w.K_max), dtype=torch.int32, device=dev)
+            g = torch.Generator(device=dev)
+            g.manual_seed(77)
+            q = torch.randn((spec.B, spec.Hq, spec.d), generator=g, device=dev)
+            prev, overlaps = None, []
+            scale = 1.0 / math.sqrt(spec.d)
+            for t in range(steps):
+                ts.append_and_decode(lay, w.k_new[t], w.v_new[t], q.to(torch.bfloat16), w.topk,
+                                     w.K_max, scale, out, ws, sel_out=sel)
+                cur = sel.clone()
+                if prev is not None:
+                    # both lists ascending, no padding (K < P): count common ids per unit
+                    common = (cur[:, :, :, None] == prev[:, :, None, :]).any(-1).sum(-1)
+                    overlaps.append(common.double().mean().item() / w.K_max)
+                prev = cur
+                q = a * q + math.sqrt(1.0 - a * a) * torch.randn(q.shape, generator=g, device=dev)
+            torch.cuda.synchronize()
+            assert ts.workspace_status(ws) == 0
+            o = sum(overlaps) / len(overlaps)
+            frac_new = 1.0 / spec.S + (1.0 - o) * spec.topk * spec.S / spec.L
+            r = {"workload": "longctx", "query_correlation": a, "keep_first": keep[0],
+                 "keep_last": keep[1], "steps": steps, "K": spec.topk,
+                 "overlap_mean": round(o, 4), "overlap_min": round(min(overlaps), 4),
+                 "overlap_query_blind": round(spec.topk * spec.S / spec.L, 4),
+                 "memory_fraction_no_reuse": round(1.0 / spec.S + spec.topk * spec.S / spec.L, 4),
+                 "memory_fraction_new_pages_only": round(frac_new, 4)}
+            rows.append(r)
+            print(json.dumps(r), flush=True)
+            del w, pmin, pmax, ws
+            torch.cuda.empty_cache()
+    hdr = ("query_correlation", "keep_first", "keep_last", "overlap_mean", "overlap_min",
+           "overlap_query_blind", "memory_fraction_no_reuse", "memory_fraction_new_pages_only")
+    print("| " + " | ".join(hdr) + " |")
+    print("|" + "---|" * len(hdr))
+    for r in rows:
+        print("| " + " | ".join(str(r[h]) for h in hdr) + " |")
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--reuse", action="store_true",
+                    help="measure the overlap of consecutive steps' selections instead")
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--keys", default="offset,walk")
     ap.add_argument("--shapes", default="tinyllama,gpt2_345m")
@@ -113,6 +176,9 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.reuse:
+        reuse(torch, ts, wl, min(args.steps, 48), dev)
+        return
     rows = []
     for shape, keys in [(s, k) for s in args.shapes.split(",") for k in args.keys.split(",")]:
         base = wl.SPECS[shape]

@@ -23,14 +23,15 @@ def oracle_unit_inputs(w, b, h, q_idx=0, seq_lens=None):
     return wl.bits(q), wl.bits(K), wl.bits(V), L
 
 
-def oracle_unit(oracle, w, b, h, scale, q_idx=0, seq_lens=None, topk=None):
+def oracle_unit(oracle, w, b, h, scale, q_idx=0, seq_lens=None, topk=None, keep=(0, 0)):
     """Full oracle step for one unit; returns its dict plus the metadata."""
     q, K, V, L = oracle_unit_inputs(w, b, h, q_idx, seq_lens)
     S = w.spec.S
     pmin, pmax = oracle.build_page_meta(K, L, S, w.P_max)
     if topk is None:
         topk = int(w.topk_per_seq[b]) if w.topk_per_seq is not None else w.topk
-    r = oracle.query_aware_decode(q, K, V, pmin, pmax, L, S, topk, w.K_max, scale)
+    r = oracle.query_aware_decode(q, K, V, pmin, pmax, L, S, topk, w.K_max, scale,
+                                  keep_first=keep[0], keep_last=keep[1])
     r.update(pmin=pmin, pmax=pmax, q=q, K=K, V=V, L=L)
     return r
 

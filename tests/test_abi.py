@@ -4,6 +4,7 @@ symbol include/tinyserve.h declares, and validates arguments on the host
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -48,6 +49,25 @@ def _layout(**kw):
     return ts.TsLayout(**base)
 
 
+def test_struct_layout_matches_the_header(tmp_path):
+    """The ctypes mirror of ts_layout has the size and field offsets the C compiler
+    gives the struct in the header."""
+    fields = [n for n, _ in ts.TsLayout._fields_]
+    src = tmp_path / "lay.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "tinyserve.h"\n'
+        'int main(void) {\n  printf("%zu", sizeof(ts_layout));\n'
+        + "".join(f'  printf(" %zu", offsetof(ts_layout, {n}));\n' for n in fields)
+        + "  return 0;\n}\n")
+    exe = tmp_path / "lay"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True,
+                                          text=True).stdout.split()]
+    assert got[0] == ctypes.sizeof(ts.TsLayout)
+    assert got[1:] == [getattr(ts.TsLayout, n).offset for n in fields]
+
+
 def test_workspace_bytes_is_host_only_and_monotone():
     lay = _layout()
     n1 = ts.workspace_bytes(lay, 8)
@@ -60,6 +80,8 @@ def test_workspace_bytes_is_host_only_and_monotone():
 @pytest.mark.parametrize("kw,code", [
     (dict(num_seqs=0), ts.TS_ERR_SHAPE),
     (dict(num_q_heads=7), ts.TS_ERR_SHAPE),
+    (dict(keep_first_pages=-1), ts.TS_ERR_SHAPE),
+    (dict(keep_last_pages=-2), ts.TS_ERR_SHAPE),
     (dict(max_pages_per_seq=-1), ts.TS_ERR_SHAPE),
     (dict(kv_tile_stride=512), ts.TS_ERR_SHAPE),      # smaller than one S*d tile
     (dict(kv_tile_stride=2052), ts.TS_ERR_SHAPE),     # tiles must stay 16-byte aligned

@@ -22,8 +22,9 @@ DEV = "cuda:0"
 class Session:
     """Device buffers + layout struct for one workload."""
 
-    def __init__(self, w, poison_meta=True):
+    def __init__(self, w, poison_meta=True, keep=(0, 0)):
         self.w = w
+        self.keep = keep      # pages kept whatever their score: (first, last)
         sp = w.spec
         fill = float("nan") if poison_meta else 0.0
         self.page_min = torch.full((sp.B, sp.Hkv, w.P_max, sp.d), fill, dtype=torch.bfloat16,
@@ -31,7 +32,8 @@ class Session:
         self.page_max = torch.full_like(self.page_min, fill)
         self.seq_lens = w.seq_lens.clone()
         self.layout = ts.make_layout(sp.B, sp.Hq, sp.Hkv, sp.d, sp.S, w.P_max, w.k_pool, w.v_pool,
-                                     w.block_table, self.seq_lens, self.page_min, self.page_max)
+                                     w.block_table, self.seq_lens, self.page_min, self.page_max,
+                                     keep_first_pages=keep[0], keep_last_pages=keep[1])
         self.scores = torch.full((sp.B, sp.Hkv, w.P_max), float("nan"), dtype=torch.float32,
                                  device=DEV)
         self.sel = torch.full((sp.B, sp.Hkv, w.K_max), -7, dtype=torch.int32, device=DEV)
@@ -71,7 +73,7 @@ def compare_units(oracle, sess, units, scale, q_idx=0, what=""):
     worst = 0.0
     for (b, h) in units:
         tag = f"{what} unit(b={b},h={h})"
-        r = oracle_unit(oracle, w, b, h, scale, q_idx=q_idx, seq_lens=lens)
+        r = oracle_unit(oracle, w, b, h, scale, q_idx=q_idx, seq_lens=lens, keep=sess.keep)
         Pb = int(oracle.num_pages(int(lens[b]), sp.S))
         omin = wl.from_bits(r["pmin"]).to(torch.float64).numpy()[0, 0]
         omax = wl.from_bits(r["pmax"]).to(torch.float64).numpy()[0, 0]
@@ -183,8 +185,10 @@ def test_select_on_given_scores_is_exact(oracle, built):
     sc[5, 2] = np.round(sc[5, 2] * 512) / 512             # mostly pairs
     topk_ps = np.array([300, 100, 5, 7, 299, 200], dtype=np.int32)
     lens_d = torch.from_numpy(lens).to(DEV)
-    for per_seq in (False, True):
-        lay = ts.make_layout(B, Hkv, Hkv, 64, S, Pmax, None, None, None, lens_d, None, None)
+    for per_seq, (kf, kl) in [(False, (0, 0)), (True, (0, 0)), (False, (1, 2)), (True, (3, 0)),
+                              (True, (0, 4)), (False, (200, 150)), (True, (2, 1))]:
+        lay = ts.make_layout(B, Hkv, Hkv, 64, S, Pmax, None, None, None, lens_d, None, None,
+                             keep_first_pages=kf, keep_last_pages=kl)
         lay.num_phys_pages = 1      # no pool is read by the selection
         d_sc = torch.from_numpy(sc).to(DEV)
         sel = torch.full((B, Hkv, Kmax), -7, dtype=torch.int32, device=DEV)
@@ -193,9 +197,49 @@ def test_select_on_given_scores_is_exact(oracle, built):
         ts.select_topk_pages(lay, d_sc, 123, Kmax, sel, cnt, topk_per_seq=tps)
         torch.cuda.synchronize()
         osel, ocnt, _ = oracle.select_topk_pages(sc.astype(np.float64), lens, S, 123, Kmax,
-                                                 topk_per_seq=topk_ps if per_seq else None)
-        assert np.array_equal(cnt.cpu().numpy(), ocnt)
-        assert np.array_equal(sel.cpu().numpy(), osel)
+                                                 topk_per_seq=topk_ps if per_seq else None,
+                                                 keep_first=kf, keep_last=kl)
+        assert np.array_equal(cnt.cpu().numpy(), ocnt), (per_seq, kf, kl)
+        assert np.array_equal(sel.cpu().numpy(), osel), (per_seq, kf, kl)
+
+
+@pytest.mark.parametrize("name,keep", [("mha_d64_s16", (1, 2)), ("gqa8_d64_s32_walk", (2, 0)),
+                                       ("mha_d128_s16_ragged", (0, 3)), ("gqa8_d64_s4", (4, 8)),
+                                       ("gqa4_d64_s64", (1, 1)), ("k_exceeds_p", (3, 3)),
+                                       ("gqa16_d64_s16", (40, 40))])
+@pytest.mark.parametrize("splits", [0, 4], indirect=True)
+def test_always_kept_pages(oracle, built, name, keep, splits):
+    """Selection with always-kept first / last pages (an option outside the paper),
+    staged and fused, against the oracle; the last pair asks for more such pages
+    than the budget holds."""
+    spec = REDUCED[name]
+    print(f"[case] always-kept {name} keep={keep} splits={splits}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=99, n_q=1, n_new=1)
+    sess = Session(w, keep=keep)
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
+    sess.staged(scale)
+    compare_units(oracle, sess, units, scale, what=f"{name}/kept/staged")
+    staged_sel = sess.sel.clone()
+    sess.sel.fill_(-7)
+    sess.fused(scale)
+    compare_units(oracle, sess, units, scale, what=f"{name}/kept/fused")
+    assert torch.equal(staged_sel, sess.sel)
+    # the kept pages are there (when the budget holds them)
+    sel = sess.sel.cpu().numpy()
+    lens = sess.seq_lens.cpu().numpy()
+    for (b, h) in units:
+        Pb = -(-int(lens[b]) // spec.S)
+        kept = [j for j in range(Pb) if j < keep[0] or j >= Pb - keep[1]]
+        n = int(sess.sel_count[b])
+        if len(kept) <= n:
+            assert set(kept) <= set(sel[b, h, :n].tolist())
+    # and through the launch that appends: the newest page is the appended token's
+    ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[0], w.topk, w.K_max, scale,
+                         sess.out, sess.ws, topk_per_seq=w.topk_per_seq, scores_out=sess.scores,
+                         sel_out=sess.sel, sel_count_out=sess.sel_count)
+    compare_units(oracle, sess, units, scale, what=f"{name}/kept/append")
 
 
 def test_append_matches_oracle_and_rebuild(oracle, built):
