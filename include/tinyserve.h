@@ -47,6 +47,8 @@ extern "C" {
 
 #define TS_MAX_PAGES_PER_SEQ 16384
 
+enum { TS_OUT_F32 = 0, TS_OUT_BF16 = 1 };
+
 typedef enum ts_status {
   TS_OK = 0,
   TS_ERR_NULL = -1,        /* a required pointer is NULL                                   */
@@ -98,6 +100,11 @@ typedef struct ts_layout {
    * lowest page ids among them are kept. */
   int32_t keep_first_pages;
   int32_t keep_last_pages;
+  /* Format of the attention output `out` of every call: TS_OUT_F32 (0, the
+   * default) fp32 [B][Hq][d]; TS_OUT_BF16: the same values rounded to bf16
+   * (nearest even), `out` then points to 16-bit elements. */
+  int32_t out_format;
+  int32_t reserved0;         /* must be 0 */
 } ts_layout;
 
 /* Section 3.4 / Eq. 1.  Rebuilds page_min / page_max of every page j < P_b of
@@ -138,7 +145,8 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
  * (first sel_count[b] entries of each row), softmax over exactly those tokens,
  * weighted sum of their values.  The paper writes softmax(q.k) with no factor:
  * softmax_scale = 1 is its literal form, 1/sqrt(d) the usual one.
- * out: fp32 [B][Hq][d]; a (b, head) with no token gets zeros.  bf16 inputs,
+ * out: fp32 [B][Hq][d] (bf16 with layout->out_format = TS_OUT_BF16); a (b, head)
+ * with no token gets zeros.  bf16 inputs,
  * fp32 accumulation.  lse_out (optional, NULL = not reported): fp32 [B][Hq],
  * the natural logarithm of the softmax denominator, log sum_t exp(softmax_scale
  * * q.k_t) over the attended tokens (-inf with no token); the share of the
@@ -147,7 +155,7 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
  * ts_workspace_init. */
 int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
                                const int32_t* sel_count, int32_t max_topk, float softmax_scale,
-                               float* out, float* lse_out, void* workspace,
+                               void* out, float* lse_out, void* workspace,
                                size_t workspace_bytes, void* stream);
 
 /* Algorithm 1 as ONE kernel launch: score -> select -> gather -> attend.
@@ -163,7 +171,7 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
  * non-zero.  It never hangs. */
 int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           const int32_t* topk_per_seq, int32_t max_topk, float softmax_scale,
-                          float* out, float* scores_out, int32_t* sel_out,
+                          void* out, float* scores_out, int32_t* sel_out,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream);
 
@@ -181,7 +189,7 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
  * kernel of its own in front of the decode on the same stream. */
 int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,
                          const void* q, int32_t topk, const int32_t* topk_per_seq,
-                         int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                         int32_t max_topk, float softmax_scale, void* out, float* scores_out,
                          int32_t* sel_out, int32_t* sel_count_out, void* workspace,
                          size_t workspace_bytes, void* stream);
 
@@ -202,7 +210,7 @@ size_t ts_workspace_bytes(const ts_layout* layout, int32_t max_topk);
  * size, ts_dense_workspace_bytes(layout) (host-only, 0 on an invalid layout),
  * initialised with ts_workspace_init. */
 size_t ts_dense_workspace_bytes(const ts_layout* layout);
-int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
+int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, void* out,
                               float* lse_out, void* workspace, size_t workspace_bytes,
                               void* stream);
 

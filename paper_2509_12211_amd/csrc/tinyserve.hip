@@ -584,6 +584,7 @@ static int check_layout(const ts_layout* L) {
   if (L->max_pages_per_seq > TS_MAX_PAGES_PER_SEQ) return TS_ERR_UNSUPPORTED;
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
   if (L->keep_first_pages < 0 || L->keep_last_pages < 0) return TS_ERR_SHAPE;
+  if (L->out_format != TS_OUT_F32 && L->out_format != TS_OUT_BF16) return TS_ERR_UNSUPPORTED;
   return TS_OK;
 }
 
@@ -651,7 +652,7 @@ static MetaParams meta_params(const ts_layout* L) {
   return p;
 }
 
-static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void* q, float* out,
+static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void* q, void* out,
                                   unsigned char* ws, int max_topk, float softmax_scale) {
   AttendParams a;
   a.q = static_cast<const uint16_t*>(q);
@@ -659,7 +660,7 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.v_pool = static_cast<const uint16_t*>(L->v_pool);
   a.block_table = L->block_table;
   a.seq_lens = L->seq_lens;
-  a.out = out;
+  a.out = static_cast<float*>(out);
   a.lse = nullptr;
   a.partials = reinterpret_cast<float*>(ws + pl.off_part);
   a.Hq = L->num_q_heads;
@@ -672,6 +673,7 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.n_split = pl.g;
   a.chunk = pl.chunk;
   a.scale_log2 = softmax_scale * 1.4426950408889634f;
+  a.out_bf16 = L->out_format == TS_OUT_BF16 ? 1 : 0;
   return a;
 }
 
@@ -699,7 +701,7 @@ using namespace ts;
 
 static int launch_fused(const ts_layout* layout, const void* k_new, const void* v_new,
                         const void* q, int32_t topk, const int32_t* topk_per_seq,
-                        int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                        int32_t max_topk, float softmax_scale, void* out, float* scores_out,
                         int32_t* sel_out, int32_t* sel_count_out, void* workspace,
                         size_t workspace_bytes, void* stream) {
   int st = check_layout(layout);
@@ -913,7 +915,7 @@ int ts_select_topk_pages(const ts_layout* layout, const float* scores, int32_t t
 
 static int launch_attention(const ts_layout* layout, const Plan& pl, const void* q,
                             const int32_t* sel, const int32_t* sel_count, int32_t max_topk,
-                            float softmax_scale, float* out, float* lse_out, void* workspace,
+                            float softmax_scale, void* out, float* lse_out, void* workspace,
                             void* stream) {
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
@@ -932,7 +934,7 @@ static int launch_attention(const ts_layout* layout, const Plan& pl, const void*
 
 int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
                                const int32_t* sel_count, int32_t max_topk, float softmax_scale,
-                               float* out, float* lse_out, void* workspace,
+                               void* out, float* lse_out, void* workspace,
                                size_t workspace_bytes, void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
@@ -951,7 +953,7 @@ size_t ts_dense_workspace_bytes(const ts_layout* layout) {
   return make_plan(layout, layout->max_pages_per_seq, kDenseTargetWorkgroups).total;
 }
 
-int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, float* out,
+int ts_dense_decode_attention(const ts_layout* layout, const void* q, float softmax_scale, void* out,
                               float* lse_out, void* workspace, size_t workspace_bytes,
                               void* stream) {
   int st = check_layout(layout);
@@ -986,7 +988,7 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
 
 int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           const int32_t* topk_per_seq, int32_t max_topk, float softmax_scale,
-                          float* out, float* scores_out, int32_t* sel_out,
+                          void* out, float* scores_out, int32_t* sel_out,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream) {
   return launch_fused(layout, nullptr, nullptr, q, topk, topk_per_seq, max_topk, softmax_scale, out,
@@ -995,7 +997,7 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
 
 int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,
                          const void* q, int32_t topk, const int32_t* topk_per_seq,
-                         int32_t max_topk, float softmax_scale, float* out, float* scores_out,
+                         int32_t max_topk, float softmax_scale, void* out, float* scores_out,
                          int32_t* sel_out, int32_t* sel_count_out, void* workspace,
                          size_t workspace_bytes, void* stream) {
   const int st = check_layout(layout);

@@ -40,13 +40,20 @@ struct AttendParams {
   const uint16_t* v_pool;      // [n_phys][Hkv] tiles of [D][S], tile_stride apart
   const int32_t* block_table;  // [B][Pmax]
   const int32_t* seq_lens;     // [B]
-  float* out;                  // [B][Hq][D]
+  float* out;                  // [B][Hq][D] fp32, or bf16 when out_bf16 != 0
   float* lse;                  // nullable [B][Hq]: log of the softmax denominator
   float* partials;             // [B*Hkv][n_split][G][D+2]
   int Hq, Hkv, G, Pmax, Kmax, n_phys, n_split, chunk;
   int tile_stride;             // elements between consecutive (page, head) tiles
   float scale_log2;            // softmax_scale * log2(e)
+  int out_bf16;                // the final output is rounded to bf16 (nearest even)
 };
+
+// Element idx of the output, in the caller's format.
+__device__ __forceinline__ void store_out(const AttendParams& p, size_t idx, float v) {
+  if (p.out_bf16) reinterpret_cast<uint16_t*>(p.out)[idx] = f32_to_bf16_rn(v);
+  else p.out[idx] = v;
+}
 
 template <int S>
 struct PageGeom {
@@ -440,7 +447,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
       O += row[c] * wgt;
     }
     if (p.n_split == 1) {
-      p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+      store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
       if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
     } else {
       store_agent(part + g * RS + c, O);
@@ -490,7 +497,7 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
       }
       M = Mn;
     }
-    p.out[((size_t)b * p.Hq + (size_t)h * G + g) * D + c] = Lsum > 0.f ? O / Lsum : 0.f;
+    store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
     if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
   }
 }

@@ -81,6 +81,7 @@ def test_workspace_bytes_is_host_only_and_monotone():
     (dict(num_seqs=0), ts.TS_ERR_SHAPE),
     (dict(num_q_heads=7), ts.TS_ERR_SHAPE),
     (dict(keep_first_pages=-1), ts.TS_ERR_SHAPE),
+    (dict(out_format=7), ts.TS_ERR_UNSUPPORTED),
     (dict(keep_last_pages=-2), ts.TS_ERR_SHAPE),
     (dict(max_pages_per_seq=-1), ts.TS_ERR_SHAPE),
     (dict(kv_tile_stride=512), ts.TS_ERR_SHAPE),      # smaller than one S*d tile

@@ -495,6 +495,39 @@ def test_selected_mass_matches_oracle(oracle, built, name, splits):
     assert np.all(mass <= 1.0 + 1e-2) and np.abs(mass - o_mass).max() <= 5e-3
 
 
+@pytest.mark.parametrize("name", ["gqa8_d64_s16_offset", "mha_d128_s16_ragged", "gqa8_d64_s4",
+                                  "gqa4_d64_s64"])
+@pytest.mark.parametrize("splits", [0, 3], indirect=True)
+def test_bf16_output_is_the_rounded_fp32_output(built, name, splits):
+    """out_format = TS_OUT_BF16: every attention entry point writes its fp32 result (the
+    one the oracle comparisons above cover) rounded to bf16, nearest even: bit-equal to
+    torch's conversion of the fp32 output of the same call."""
+    spec = REDUCED[name]
+    print(f"[case] bf16 out {name} splits={splits}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=17, n_q=1, n_new=1)
+    a = Session(w)
+    ts.build_page_meta(a.layout)
+    lay16 = ts.make_layout(spec.B, spec.Hq, spec.Hkv, spec.d, spec.S, w.P_max, w.k_pool, w.v_pool,
+                           w.block_table, a.seq_lens, a.page_min, a.page_max,
+                           out_format=ts.TS_OUT_BF16)
+    out16 = torch.full((spec.B, spec.Hq, spec.d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    scale = 1.0 / math.sqrt(spec.d)
+    a.fused(scale)
+    ts.query_aware_decode(lay16, w.q[0], w.topk, w.K_max, scale, out16, a.ws,
+                          topk_per_seq=w.topk_per_seq)
+    torch.cuda.synchronize()
+    assert _bits_equal(out16, a.out.to(torch.bfloat16)), "fused"
+    out16.fill_(float("nan"))
+    ts.sparse_decode_attention(lay16, w.q[0], a.sel, a.sel_count, w.K_max, scale, out16, a.ws)
+    torch.cuda.synchronize()
+    assert _bits_equal(out16, a.out.to(torch.bfloat16)), "staged"
+    dws = ts.new_dense_workspace(a.layout, DEV)
+    ts.dense_decode_attention(a.layout, w.q[0], scale, a.out, dws)
+    ts.dense_decode_attention(lay16, w.q[0], scale, out16, dws)
+    torch.cuda.synchronize()
+    assert _bits_equal(out16, a.out.to(torch.bfloat16)), "dense"
+
+
 @pytest.mark.parametrize("splits", [0, 4], indirect=True)
 def test_graph_replays_match_eager(built, splits):
     """A captured HIP graph of decode steps (the form bench.py times) replayed several
