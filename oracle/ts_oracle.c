@@ -28,7 +28,9 @@
  * Pins (tests/test_oracle_pins.py): hand-worked two-page example, the bound
  * invariant r >= max q.k, K = P  ==> dense softmax attention (checked against
  * a library routine), brute force over all page subsets on tiny inputs,
- * closed forms for constant pages, append == rebuild.
+ * closed forms for constant pages, append == rebuild.  The INT8 cache functions
+ * at the end of the file are pinned to the bf16 ones (scales that are powers of
+ * two make the two caches hold the same numbers) and by hand-worked values.
  */
 #include <math.h>
 #include <stdint.h>
@@ -362,4 +364,183 @@ void tso_true_page_max(const uint16_t* q, const uint16_t* K, const int32_t* seq_
       }
     }
   }
+}
+
+/* ===========================================================================
+ * INT8 KV cache.  Section 3.1 names "FP16/INT8 KV formats" for the sparse
+ * attention executor and gives no format; the one defined here (and in the GPU
+ * library's header) is an extension of this build:
+ *   - keys and values are stored as int8 with one positive fp32 scale per
+ *     (token, KV head): the key of token t is  k_t[c] = Kq[t][c] * ks[t]  as a
+ *     real number (no rounding), likewise v_t[c] = Vq[t][c] * vs[t];
+ *   - queries and page metadata stay bf16.  A page's box must contain its
+ *     dequantised keys for Eq. 2 to remain an upper bound, so the channel-wise
+ *     min is rounded DOWN to bf16 and the max UP;
+ *   - a bf16 vector x is quantised as  scale = max_c |x_c| / 127  (1 if x = 0),
+ *     xq_c = round-half-even(x_c / scale), both in fp32 arithmetic.
+ * Everything after the metadata (Eq. 2, top-K, softmax attention over the
+ * selected tokens) is the paper's, applied to the dequantised keys / values.
+ *
+ * Logical shapes: Kq, Vq int8 [B][Hkv][Lmax][d]; ks, vs float [B][Hkv][Lmax].
+ * =========================================================================== */
+
+/* fp32 -> bf16 bits, rounded towards -inf (up == 0) or +inf (up != 0). */
+static uint16_t bf16_directed(float f, int up) {
+  uint32_t w;
+  memcpy(&w, &f, sizeof w);
+  uint16_t hi = (uint16_t)(w >> 16);
+  if ((w & 0xffffu) == 0u) return hi;            /* exactly representable */
+  int negative = (w >> 31) != 0;
+  /* truncation moves towards zero: that is down for positive values, up for negative */
+  if (negative ? !up : up) hi = (uint16_t)(hi + 1); /* one bf16 step away from zero */
+  return hi;
+}
+
+void tso_quantize_rows_i8(const uint16_t* x /*bf16 [n][d]*/, int n, int d, int8_t* xq /*[n][d]*/,
+                          float* scale /*[n]*/) {
+  for (int i = 0; i < n; ++i) {
+    float amax = 0.0f;
+    for (int c = 0; c < d; ++c) {
+      float v = fabsf((float)bf16_to_double(x[(size_t)i * d + c]));
+      if (v > amax) amax = v;
+    }
+    float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+    scale[i] = s;
+    for (int c = 0; c < d; ++c) {
+      float v = (float)bf16_to_double(x[(size_t)i * d + c]);
+      float r = rintf(v / s);                    /* default rounding mode: half to even */
+      if (r > 127.0f) r = 127.0f;
+      if (r < -127.0f) r = -127.0f;
+      xq[(size_t)i * d + c] = (int8_t)r;
+    }
+  }
+}
+
+/* Eq. 1 on the dequantised keys, box rounded outwards to bf16. */
+void tso_build_page_meta_i8(const int8_t* Kq, const float* ks, const int32_t* seq_lens, int B,
+                            int Hkv, int Lmax, int d, int S, int Pmax, uint16_t* page_min,
+                            uint16_t* page_max) {
+  for (int b = 0; b < B; ++b) {
+    int Pb = pages_of(seq_lens[b], S);
+    for (int h = 0; h < Hkv; ++h) {
+      const int8_t* Kbh = Kq + ((size_t)b * Hkv + h) * (size_t)Lmax * d;
+      const float* sbh = ks + ((size_t)b * Hkv + h) * (size_t)Lmax;
+      for (int j = 0; j < Pb && j < Pmax; ++j) {
+        int t0 = j * S;
+        int t1 = t0 + S < seq_lens[b] ? t0 + S : seq_lens[b];
+        uint16_t* mrow = page_min + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        uint16_t* Mrow = page_max + (((size_t)b * Hkv + h) * Pmax + j) * d;
+        for (int c = 0; c < d; ++c) {
+          double lo = INFINITY, hi = -INFINITY;
+          for (int t = t0; t < t1; ++t) {
+            double k = (double)Kbh[(size_t)t * d + c] * (double)sbh[t];
+            if (k < lo) lo = k;
+            if (k > hi) hi = k;
+          }
+          /* int8 x fp32 has at most 31 significant bits: the fp32 product below is the
+           * real product rounded once; rounding it outwards again keeps the box closed
+           * only if that first rounding did not cross the value, so round from double */
+          float flo = (float)lo, fhi = (float)hi;
+          if ((double)flo > lo) flo = nextafterf(flo, -INFINITY);
+          if ((double)fhi < hi) fhi = nextafterf(fhi, INFINITY);
+          mrow[c] = bf16_directed(flo, 0);
+          Mrow[c] = bf16_directed(fhi, 1);
+        }
+      }
+    }
+  }
+}
+
+/* Incremental form: the appended token (already quantised) opens or widens the
+ * box of page seq_lens[b] / S.  Must equal a rebuild, bit for bit. */
+void tso_append_token_meta_i8(const int8_t* kq_new /*[B][Hkv][d]*/, const float* ks_new /*[B][Hkv]*/,
+                              const int32_t* seq_lens, int B, int Hkv, int d, int S, int Pmax,
+                              uint16_t* page_min, uint16_t* page_max) {
+  for (int b = 0; b < B; ++b) {
+    int p = seq_lens[b];
+    int j = p / S;
+    if (j >= Pmax) continue;
+    for (int h = 0; h < Hkv; ++h) {
+      uint16_t* mrow = page_min + (((size_t)b * Hkv + h) * Pmax + j) * d;
+      uint16_t* Mrow = page_max + (((size_t)b * Hkv + h) * Pmax + j) * d;
+      for (int c = 0; c < d; ++c) {
+        double k = (double)kq_new[((size_t)b * Hkv + h) * d + c] * (double)ks_new[(size_t)b * Hkv + h];
+        float flo = (float)k, fhi = (float)k;
+        if ((double)flo > k) flo = nextafterf(flo, -INFINITY);
+        if ((double)fhi < k) fhi = nextafterf(fhi, INFINITY);
+        uint16_t lo = bf16_directed(flo, 0), hi = bf16_directed(fhi, 1);
+        if (p % S == 0) {
+          mrow[c] = lo;
+          Mrow[c] = hi;
+        } else {
+          if (bf16_to_double(lo) < bf16_to_double(mrow[c])) mrow[c] = lo;
+          if (bf16_to_double(hi) > bf16_to_double(Mrow[c])) Mrow[c] = hi;
+        }
+      }
+    }
+  }
+}
+
+/* Section 3.5 SparseAttn on the dequantised cache.  sel == NULL: every page of
+ * the sequence (the dense attention the paper compares against). */
+void tso_sparse_decode_attention_i8(const uint16_t* q, const int8_t* Kq, const float* ks,
+                                    const int8_t* Vq, const float* vs, const int32_t* sel,
+                                    const int32_t* sel_count, const int32_t* seq_lens, int B,
+                                    int Hq, int Hkv, int Lmax, int d, int S, int Kmax,
+                                    double scale, double* out, double* lse) {
+  int G = Hq / Hkv;
+  for (int bh = 0; bh < B * Hq; ++bh) {
+    int b = bh / Hq, g = bh % Hq, h = g / G;
+    const uint16_t* qg = q + ((size_t)b * Hq + g) * d;
+    size_t base = ((size_t)b * Hkv + h) * (size_t)Lmax;
+    double* o = out + ((size_t)b * Hq + g) * d;
+    int L = seq_lens[b];
+    int n = sel ? sel_count[b] : pages_of(L, S);
+    double* a = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * S);
+    int32_t* tok = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1) * S);
+    int cnt = 0;
+    double amax = -INFINITY;
+    for (int i = 0; i < n; ++i) {
+      int j = sel ? sel[((size_t)b * Hkv + h) * Kmax + i] : i;
+      for (int t = j * S; t < (j + 1) * S && t < L; ++t) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c)
+          dot += bf16_to_double(qg[c]) * ((double)Kq[(base + t) * d + c] * (double)ks[base + t]);
+        a[cnt] = scale * dot;
+        tok[cnt] = t;
+        if (a[cnt] > amax) amax = a[cnt];
+        ++cnt;
+      }
+    }
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    double denom = 0.0;
+    for (int i = 0; i < cnt; ++i) {
+      a[i] = exp(a[i] - amax);
+      denom += a[i];
+    }
+    for (int i = 0; i < cnt; ++i) {
+      double w = a[i] / denom;
+      for (int c = 0; c < d; ++c)
+        o[c] += w * ((double)Vq[(base + tok[i]) * d + c] * (double)vs[base + tok[i]]);
+    }
+    if (lse) lse[(size_t)b * Hq + g] = cnt > 0 ? amax + log(denom) : -INFINITY;
+    free(a);
+    free(tok);
+  }
+}
+
+/* Algorithm 1 with the metadata given: Eq. 2 scores, top-K, attention over the
+ * dequantised selected tokens. */
+void tso_query_aware_decode_i8(const uint16_t* q, const int8_t* Kq, const float* ks,
+                               const int8_t* Vq, const float* vs, const uint16_t* page_min,
+                               const uint16_t* page_max, const int32_t* seq_lens, int B, int Hq,
+                               int Hkv, int Lmax, int d, int S, int Pmax, int topk,
+                               const int32_t* topk_per_seq, int Kmax, int keep_first,
+                               int keep_last, double scale, double* scores, int32_t* sel,
+                               int32_t* sel_count, double* gap, double* out) {
+  tso_score_pages(q, page_min, page_max, seq_lens, B, Hq, Hkv, d, S, Pmax, 0, scores);
+  tso_select_topk_pages(scores, seq_lens, B, Hkv, S, Pmax, topk, topk_per_seq, Kmax, keep_first,
+                        keep_last, sel, sel_count, gap);
+  tso_sparse_decode_attention_i8(q, Kq, ks, Vq, vs, sel, sel_count, seq_lens, B, Hq, Hkv, Lmax, d,
+                                 S, Kmax, scale, out, NULL);
 }

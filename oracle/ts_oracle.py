@@ -169,3 +169,90 @@ def true_page_max(q, K, seq_lens, S, Pmax):
     best = np.empty((B, Hq, Pmax), dtype=np.float64)
     _load().tso_true_page_max(_p(q), _p(K), _p(seq_lens), B, Hq, Hkv, Lmax, d, S, Pmax, _p(best))
     return best
+
+
+# ---------------------------------------------------------------------------
+# INT8 KV cache (format defined in ts_oracle.c)
+# ---------------------------------------------------------------------------
+def _i8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.int8, a.dtype
+    return a
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def quantize_rows_i8(x):
+    """bf16 bits [..., d] -> (int8 [..., d], float32 scale [...])."""
+    x = _u16(x)
+    d = x.shape[-1]
+    n = x.size // d
+    xq = np.empty(x.shape, dtype=np.int8)
+    sc = np.empty(x.shape[:-1], dtype=np.float32)
+    _load().tso_quantize_rows_i8(_p(x), n, d, _p(xq), _p(sc))
+    return xq, sc
+
+
+def build_page_meta_i8(Kq, ks, seq_lens, S, Pmax):
+    Kq, ks = _i8(Kq), _f32(ks)
+    B, Hkv, Lmax, d = Kq.shape
+    seq_lens = _i32(seq_lens)
+    pmin = np.zeros((B, Hkv, Pmax, d), dtype=np.uint16)
+    pmax = np.zeros((B, Hkv, Pmax, d), dtype=np.uint16)
+    _load().tso_build_page_meta_i8(_p(Kq), _p(ks), _p(seq_lens), B, Hkv, Lmax, d, S, Pmax, _p(pmin),
+                                   _p(pmax))
+    return pmin, pmax
+
+
+def append_token_meta_i8(kq_new, ks_new, seq_lens, S, page_min, page_max):
+    """In-place update of page_min / page_max (uint16 arrays) for one appended token."""
+    kq_new, ks_new = _i8(kq_new), _f32(ks_new)
+    B, Hkv, d = kq_new.shape
+    assert page_min.dtype == np.uint16 and page_min.flags["C_CONTIGUOUS"]
+    assert page_max.dtype == np.uint16 and page_max.flags["C_CONTIGUOUS"]
+    Pmax = page_min.shape[2]
+    seq_lens = _i32(seq_lens)
+    _load().tso_append_token_meta_i8(_p(kq_new), _p(ks_new), _p(seq_lens), B, Hkv, d, S, Pmax,
+                                     _p(page_min), _p(page_max))
+
+
+def sparse_decode_attention_i8(q, Kq, ks, Vq, vs, sel, sel_count, seq_lens, S, scale,
+                               return_lse=False):
+    """sel = None: attention over every cached token (the dense baseline)."""
+    q, Kq, Vq, ks, vs = _u16(q), _i8(Kq), _i8(Vq), _f32(ks), _f32(vs)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = Kq.shape
+    seq_lens = _i32(seq_lens)
+    Kmax = 0
+    if sel is not None:
+        sel, sel_count = _i32(sel), _i32(sel_count)
+        Kmax = sel.shape[2]
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64) if return_lse else None
+    _load().tso_sparse_decode_attention_i8(
+        _p(q), _p(Kq), _p(ks), _p(Vq), _p(vs), _p(sel), _p(sel_count) if sel is not None else None,
+        _p(seq_lens), B, Hq, Hkv, Lmax, d, S, Kmax, ctypes.c_double(scale), _p(out), _p(lse))
+    return (out, lse) if return_lse else out
+
+
+def query_aware_decode_i8(q, Kq, ks, Vq, vs, page_min, page_max, seq_lens, S, topk, Kmax, scale,
+                          topk_per_seq=None, keep_first=0, keep_last=0):
+    q, Kq, Vq, ks, vs = _u16(q), _i8(Kq), _i8(Vq), _f32(ks), _f32(vs)
+    page_min, page_max = _u16(page_min), _u16(page_max)
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = Kq.shape
+    Pmax = page_min.shape[2]
+    seq_lens = _i32(seq_lens)
+    tps = None if topk_per_seq is None else _i32(topk_per_seq)
+    scores = np.empty((B, Hkv, Pmax), dtype=np.float64)
+    sel = np.empty((B, Hkv, Kmax), dtype=np.int32)
+    cnt = np.empty((B,), dtype=np.int32)
+    gap = np.empty((B, Hkv), dtype=np.float64)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    _load().tso_query_aware_decode_i8(
+        _p(q), _p(Kq), _p(ks), _p(Vq), _p(vs), _p(page_min), _p(page_max), _p(seq_lens), B, Hq, Hkv,
+        Lmax, d, S, Pmax, int(topk), _p(tps), Kmax, int(keep_first), int(keep_last),
+        ctypes.c_double(scale), _p(scores), _p(sel), _p(cnt), _p(gap), _p(out))
+    return dict(scores=scores, sel=sel, sel_count=cnt, gap=gap, out=out)

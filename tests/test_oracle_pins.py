@@ -363,6 +363,117 @@ def test_always_kept_pages(oracle, seed):
     assert all(np.array_equal(a, b) for a, b in zip(plain, zero))
 
 
+# ----------------------------------------------------------------------------
+# INT8 KV cache (an extension; format in oracle/ts_oracle.c)
+# ----------------------------------------------------------------------------
+def test_i8_quantisation_hand_worked(oracle):
+    """scale = max|x| / 127, codes = round-half-even(x / scale), in fp32."""
+    x = bf16_bits([[1.0, -0.5, 0.25, 0.0], [0.0, 0.0, 0.0, 0.0], [-3.0, 3.0, 1.5, -0.75]])
+    xq, sc = oracle.quantize_rows_i8(x)
+    assert sc[0] == np.float32(1.0) / np.float32(127.0)
+    # 0.5 * 127 = 63.5 and 0.25 * 127 = 31.75 up to the rounding of 1/127 in fp32:
+    # x / scale is evaluated in fp32 and comes out as exactly -63.5 and 31.75
+    assert xq[0].tolist() == [127, -64, 32, 0]
+    assert sc[1] == 1.0 and xq[1].tolist() == [0, 0, 0, 0]
+    assert sc[2] == np.float32(3.0) / np.float32(127.0)
+    assert xq[2].tolist() == [-127, 127, 64, -32]      # 63.5 -> 64 (even), 31.75 -> 32
+    # the largest entry always maps to +-127 and the error is at most half a step
+    rng = np.random.default_rng(5)
+    y = rand_bf16(rng, (50, 16), 3.0)
+    yq, ys = oracle.quantize_rows_i8(y)
+    assert np.all(np.abs(yq).max(axis=1) == 127)
+    err = np.abs(yq.astype(np.float64) * ys[:, None].astype(np.float64) - bf16_val(y))
+    assert np.all(err <= 0.5 * ys[:, None].astype(np.float64) * (1 + 1e-6))
+
+
+def test_i8_box_is_rounded_outwards(oracle):
+    """Metadata of an INT8 page: min rounded down, max rounded up to bf16, so the box
+    contains the dequantised keys; values that are bf16 numbers stay as they are."""
+    # one page of two tokens, d = 4, scale chosen so that products need > 8 bits
+    Kq = np.array([[[[3, -3, 64, 1], [5, -5, 64, -1]]]], dtype=np.int8)
+    ks = np.array([[[1.0 + 2.0 ** -10, 1.0 + 2.0 ** -10]]], dtype=np.float32)
+    pmin, pmax = oracle.build_page_meta_i8(Kq, ks, [2], 2, 1)
+    lo, hi = bf16_val(pmin)[0, 0, 0], bf16_val(pmax)[0, 0, 0]
+    s = 1.0 + 2.0 ** -10
+    true_lo = np.array([3 * s, -5 * s, 64 * s, -1 * s])
+    true_hi = np.array([5 * s, -3 * s, 64 * s, 1 * s])
+    assert np.all(lo <= true_lo) and np.all(hi >= true_hi)
+    # and tightly: the next bf16 number inwards would cut the value off
+    assert lo.tolist() == [3.0, -5.03125, 64.0, -1.0078125]
+    assert hi.tolist() == [5.03125, -3.0, 64.5, 1.0078125]
+    # exactly representable products are not moved
+    ks1 = np.ones((1, 1, 2), dtype=np.float32) * 0.5
+    pmin, pmax = oracle.build_page_meta_i8(Kq, ks1, [2], 2, 1)
+    assert bf16_val(pmin)[0, 0, 0].tolist() == [1.5, -2.5, 32.0, -0.5]
+    assert bf16_val(pmax)[0, 0, 0].tolist() == [2.5, -1.5, 32.0, 0.5]
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_i8_equals_bf16_path_for_power_of_two_scales(oracle, seed):
+    """With power-of-two scales the dequantised keys and values are bf16 numbers: every
+    INT8 function must then reproduce the (pinned) bf16 functions on the dequantised cache."""
+    rng = np.random.default_rng(40 + seed)
+    B, Hq, Hkv, d, S = 2, 4, 2, 8, 4
+    lens = np.array([27, 14], dtype=np.int32)
+    Lmax, Pmax, Kmax = 28, 7, 3
+    Kq = rng.integers(-127, 128, size=(B, Hkv, Lmax, d)).astype(np.int8)
+    Vq = rng.integers(-127, 128, size=(B, Hkv, Lmax, d)).astype(np.int8)
+    ks = (2.0 ** rng.integers(-8, -3, size=(B, Hkv, Lmax))).astype(np.float32)
+    vs = (2.0 ** rng.integers(-8, -3, size=(B, Hkv, Lmax))).astype(np.float32)
+    Kb = bf16_bits(Kq.astype(np.float64) * ks[..., None])
+    Vb = bf16_bits(Vq.astype(np.float64) * vs[..., None])
+    assert np.array_equal(bf16_val(Kb), Kq.astype(np.float64) * ks[..., None])   # exact
+    q = rand_bf16(rng, (B, Hq, d), 0.5)
+    pmin, pmax = oracle.build_page_meta(Kb, lens, S, Pmax)
+    qmin, qmax = oracle.build_page_meta_i8(Kq, ks, lens, S, Pmax)
+    for b in range(B):
+        Pb = -(-int(lens[b]) // S)
+        assert np.array_equal(pmin[b, :, :Pb], qmin[b, :, :Pb])
+        assert np.array_equal(pmax[b, :, :Pb], qmax[b, :, :Pb])
+    r = oracle.query_aware_decode(q, Kb, Vb, pmin, pmax, lens, S, 2, Kmax, 0.4)
+    ri = oracle.query_aware_decode_i8(q, Kq, ks, Vq, vs, qmin, qmax, lens, S, 2, Kmax, 0.4)
+    assert np.array_equal(r["sel"], ri["sel"]) and np.array_equal(r["scores"], ri["scores"])
+    np.testing.assert_allclose(ri["out"], r["out"], rtol=0, atol=1e-13)
+    dense, dl = oracle.dense_decode_attention(q, Kb, Vb, lens, 0.4, return_lse=True)
+    di, dli = oracle.sparse_decode_attention_i8(q, Kq, ks, Vq, vs, None, None, lens, S, 0.4,
+                                                return_lse=True)
+    np.testing.assert_allclose(di, dense, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dli, dl, rtol=0, atol=1e-12)
+    # append == rebuild, bit for bit
+    kq_new = rng.integers(-127, 128, size=(B, Hkv, d)).astype(np.int8)
+    ks_new = (1.0 + rng.random((B, Hkv))).astype(np.float32) * 0.01        # not powers of two
+    Kq2, ks2 = Kq.copy(), ks.copy()
+    for b in range(B):
+        Kq2[b, :, lens[b]] = kq_new[b]
+        ks2[b, :, lens[b]] = ks_new[b]
+    amin, amax = qmin.copy(), qmax.copy()
+    oracle.append_token_meta_i8(kq_new, ks_new, lens, S, amin, amax)
+    rmin, rmax = oracle.build_page_meta_i8(Kq2, ks2, lens + 1, S, Pmax)
+    for b in range(B):
+        Pb = -(-int(lens[b] + 1) // S)
+        assert np.array_equal(amin[b, :, :Pb], rmin[b, :, :Pb])
+        assert np.array_equal(amax[b, :, :Pb], rmax[b, :, :Pb])
+
+
+def test_i8_bound_invariant(oracle):
+    """Eq. 2 on the outward-rounded box bounds q.k for every dequantised key, zero slack."""
+    rng = np.random.default_rng(8)
+    B, Hq, Hkv, d, S = 1, 2, 2, 16, 8
+    L, Pmax = 61, 8
+    Kq = rng.integers(-127, 128, size=(B, Hkv, L, d)).astype(np.int8)
+    ks = (0.005 + 0.03 * rng.random((B, Hkv, L))).astype(np.float32)
+    q = rand_bf16(rng, (B, Hq, d))
+    pmin, pmax = oracle.build_page_meta_i8(Kq, ks, [L], S, Pmax)
+    sc = oracle.score_pages(q, pmin, pmax, [L], S)
+    qv = bf16_val(q)
+    for h in range(Hkv):
+        kd = Kq[0, h].astype(np.float64) * ks[0, h][:, None].astype(np.float64)
+        for j in range(Pmax):
+            toks = range(j * S, min((j + 1) * S, L))
+            best = max(sum(qv[0, h, c] * kd[t, c] for c in range(d)) for t in toks)
+            assert sc[0, h, j] >= best
+
+
 def test_append_equals_rebuild(oracle):
     rng = np.random.default_rng(21)
     B, Hkv, d, S = 3, 2, 8, 4
