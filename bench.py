@@ -58,7 +58,7 @@ class Layer:
         self.seq_lens = w.seq_lens.clone()
         self.layout = ts.make_layout(spec.B, spec.Hq, spec.Hkv, spec.d, spec.S, w.P_max, w.k_pool,
                                      w.v_pool, w.block_table, self.seq_lens, self.page_min,
-                                     self.page_max)
+                                     self.page_max, k_scale=w.k_scale, v_scale=w.v_scale)
         self.out = torch.zeros((spec.B, spec.Hq, spec.d), dtype=torch.float32, device=dev)
         self.ws = ts.new_workspace(self.layout, w.K_max, dev)
         ts.build_page_meta(self.layout)
@@ -146,18 +146,29 @@ def cpu_baseline(spec, layer, wl, budget_s=20.0):
     per_seq = spec.Hkv * int(lens_all.max()) * spec.d * 2
     n_seq = max(1, min(spec.B, (1 << 30) // max(per_seq, 1)))
     seqs = list(range(n_seq))
-    K, V = wl.logical_kv(w, seqs=seqs, seq_lens=lens_all)
     L = lens_all[:n_seq].numpy().astype(np.int32)
-    Kb, Vb, qb = wl.bits(K), wl.bits(V), wl.bits(w.q[0][:n_seq])
+    qb = wl.bits(w.q[0][:n_seq])
     pmin, pmax = wl.bits(layer.page_min[:n_seq]), wl.bits(layer.page_max[:n_seq])
     tps = None if w.topk_per_seq is None else w.topk_per_seq[:n_seq].cpu().numpy()
     scale = 1.0 / math.sqrt(spec.d)
+    if spec.kv == "int8":
+        kv = [t.cpu().numpy() for t in wl.logical_kv_i8(w, seqs=seqs, seq_lens=lens_all)]
+
+        def step():
+            oracle.query_aware_decode_i8(qb, *kv, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
+                                         topk_per_seq=tps)
+    else:
+        K, V = wl.logical_kv(w, seqs=seqs, seq_lens=lens_all)
+        Kb, Vb = wl.bits(K), wl.bits(V)
+
+        def step():
+            oracle.query_aware_decode(qb, Kb, Vb, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
+                                      topk_per_seq=tps)
     times = []
     t_start = time.perf_counter()
     while True:
         t0 = time.perf_counter()
-        oracle.query_aware_decode(qb, Kb, Vb, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
-                                  topk_per_seq=tps)
+        step()
         times.append(time.perf_counter() - t0)
         if len(times) >= 3 and time.perf_counter() - t_start > 0.5 * budget_s:
             break
@@ -184,6 +195,8 @@ def main():
     ap.add_argument("--step", default="one_launch", choices=["one_launch", "separate"],
                     help="one_launch: ts_append_and_decode; separate: ts_append_token_meta + "
                          "ts_query_aware_decode")
+    ap.add_argument("--kv-format", default="bf16", choices=["bf16", "int8"],
+                    help="format of the KV pool (int8: codes + one fp32 scale per token and head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip timing the dense (whole-cache) attention beside the step")
@@ -207,7 +220,7 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    spec = wl.SPECS[args.workload]
+    spec = wl.scaled(wl.SPECS[args.workload], kv=args.kv_format)
     lens_nom = torch.full((spec.B,), spec.L, dtype=torch.int32)
     nominal = wl.algorithmic_bytes(spec, lens_nom) if not spec.L_min else None
 
@@ -410,12 +423,13 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16" if args.kv_format == "bf16" else "int8 KV expanded to bf16 for the MFMA",
         "data": "synthetic",
         "effective_GBps": round(by["total"] / (us_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100.0 * by["total"] / (us_step * 1e-6) / HBM_PEAK, 2),
         "config": {
-            "workload": WORKLOAD_DESC[args.workload],
+            "workload": WORKLOAD_DESC[args.workload] + ("" if args.kv_format == "bf16"
+                                                          else ", INT8 KV pool"),
             "step": ("ts_append_and_decode (append + score + select + attend in one launch), one layer"
                      if single_kernel else
                      "ts_append_and_decode (large batch: append kernel + fused decode kernel), one layer"
@@ -434,7 +448,8 @@ def main():
             "peak": HBM_PEAK / 1e9,
             "unit": "GB/s",
             "frac": round(achieved * 1e9 / HBM_PEAK, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "traffic": (MEASURED_TRAFFIC_BYTES.get(args.workload)
+                        if args.kv_format == "bf16" else None),
             "us_per_launch": round(fused_us, 3),
             "launches": n_roof,
         },

@@ -48,6 +48,7 @@ extern "C" {
 #define TS_MAX_PAGES_PER_SEQ 16384
 
 enum { TS_OUT_F32 = 0, TS_OUT_BF16 = 1 };
+enum { TS_KV_BF16 = 0, TS_KV_INT8 = 1 };
 
 typedef enum ts_status {
   TS_OK = 0,
@@ -104,7 +105,23 @@ typedef struct ts_layout {
    * default) fp32 [B][Hq][d]; TS_OUT_BF16: the same values rounded to bf16
    * (nearest even), `out` then points to 16-bit elements. */
   int32_t out_format;
-  int32_t reserved0;         /* must be 0 */
+  /* Format of the KV pool: TS_KV_BF16 (0, the default) as described above, or
+   * TS_KV_INT8 (Section 3.1 names INT8 KV support and gives no format; this one
+   * is this library's):
+   *   k_pool int8 [num_phys_pages][Hkv][S][d], v_pool int8 [num_phys_pages][Hkv][d][S]
+   *   (kv_tile_stride counts bytes and must be a multiple of 16),
+   *   k_scale, v_scale fp32 [num_phys_pages][Hkv][S]: one positive scale per token
+   *   and KV head; the key of a token is code * scale as a real number.
+   * Queries, appended tokens and metadata stay bf16.  ts_build_page_meta rounds a
+   * page's minimum down and its maximum up to bf16, so the box contains the
+   * dequantised keys and Eq. 2 remains an upper bound.  ts_append_token_meta
+   * quantises the bf16 token: scale = max_c |x_c| / 127 (1 for a zero vector),
+   * code = x_c / scale rounded half to even, all in fp32; with v_new == NULL only
+   * the box is widened, by the key so quantised.  ts_append_and_decode runs the
+   * append as a kernel of its own in front of the fused kernel. */
+  int32_t kv_format;
+  float* k_scale;
+  float* v_scale;
 } ts_layout;
 
 /* Section 3.4 / Eq. 1.  Rebuilds page_min / page_max of every page j < P_b of

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
 
 // grid (g, units).  The last workgroup of a unit to deposit its partial merges
 // them (unit_done counts arrivals and is left at zero again).
-template <int D, int S>
+template <int D, int S, bool kInt8>
 __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams p,
                                                                     const int32_t* sel,
                                                                     const int32_t* sel_count,
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   const int32_t* sel_row = sel ? sel + (size_t)u * p.Kmax + c0 : nullptr;
   const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
   const NewToken none{-1, 0, p.q, p.q};
-  attend_split<D, S, true, false>(
+  attend_split<D, S, true, false, kInt8>(
       p, b, h, split, count, p.seq_lens[b], none,
       [&](int i) { return sel_row ? sel_row[i] : c0 + i; },
       [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
@@ -264,9 +264,10 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 //
 // kApp = true is the build that first appends one token per sequence
 // (ts_append_and_decode); the plain build carries none of its registers.
-template <int D, int S, bool kLoop, bool kApp>
+template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
   static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
+  static_assert(!(kInt8 && kApp), "the INT8 cache is appended to by a kernel of its own");
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_flag;
   TS_MARK_INIT();
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     const size_t new_row = ((size_t)b * at.Hkv + h) * D;
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
-    attend_split<D, S, !kLoop, kApp>(
+    attend_split<D, S, !kLoop, kApp, kInt8>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
     TS_MARK(6);
@@ -585,6 +586,8 @@ static int check_layout(const ts_layout* L) {
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
   if (L->keep_first_pages < 0 || L->keep_last_pages < 0) return TS_ERR_SHAPE;
   if (L->out_format != TS_OUT_F32 && L->out_format != TS_OUT_BF16) return TS_ERR_UNSUPPORTED;
+  if (L->kv_format != TS_KV_BF16 && L->kv_format != TS_KV_INT8) return TS_ERR_UNSUPPORTED;
+  if (L->kv_format == TS_KV_INT8 && L->kv_tile_stride % 16 != 0) return TS_ERR_SHAPE;
   return TS_OK;
 }
 
@@ -649,6 +652,8 @@ static MetaParams meta_params(const ts_layout* L) {
   p.Pmax = L->max_pages_per_seq;
   p.n_phys = L->num_phys_pages;
   p.tile_stride = tile_stride_of(L);
+  p.k_scale = L->k_scale;
+  p.v_scale = L->v_scale;
   return p;
 }
 
@@ -658,6 +663,8 @@ static AttendParams attend_params(const ts_layout* L, const Plan& pl, const void
   a.q = static_cast<const uint16_t*>(q);
   a.k_pool = static_cast<const uint16_t*>(L->k_pool);
   a.v_pool = static_cast<const uint16_t*>(L->v_pool);
+  a.k_scale = L->k_scale;
+  a.v_scale = L->v_scale;
   a.block_table = L->block_table;
   a.seq_lens = L->seq_lens;
   a.out = static_cast<float*>(out);
@@ -699,6 +706,51 @@ using namespace ts;
     }                                   \
   } while (0)
 
+// One unit per cluster and everything resident: the loop-free build, which for
+// the bf16 cache also exists with the append folded in.  Otherwise (thousands of
+// units, bound by bandwidth) the looping build; an append then runs as a launch
+// of its own in front of it: the looping build has no registers to spare for
+// it, and against hundreds of microseconds the extra launch does not count.
+// The INT8 cache is always appended to by its own kernel.
+// max_resident: workgroups the launch may count on being resident together.
+template <int D, int S, bool kInt8>
+static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Plan& pl,
+                              const void* k_new, const void* v_new, int max_resident,
+                              void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8>;
+  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8>;
+  auto app_kernel = query_aware_decode_kernel<D, S, false, !kInt8, kInt8>;   // == one_kernel for INT8
+  int st;
+  if ((st = allow_lds(loop_kernel, pl.lds_fused)) != TS_OK ||
+      (st = allow_lds(one_kernel, pl.lds_fused)) != TS_OK ||
+      (st = allow_lds(app_kernel, pl.lds_fused)) != TS_OK)
+    return st;
+  const bool fold_append = k_new && !kInt8;
+  int cap1 = resident_capacity(fold_append ? app_kernel : one_kernel, pl.lds_fused);
+  if (cap1 > max_resident) cap1 = max_resident;
+  const bool one_unit_each = pl.units * pl.g <= cap1;
+  if (k_new && !(one_unit_each && fold_append)) {
+    if ((st = ts_append_token_meta(layout, k_new, v_new, 1, stream)) != TS_OK) return st;
+    p.k_new = p.v_new = nullptr;
+  }
+  if (one_unit_each) {
+    const unsigned grid = (unsigned)(pl.units * pl.g);
+    if (p.k_new)
+      app_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
+    else
+      one_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
+    return TS_OK;
+  }
+  int cap = resident_capacity(loop_kernel, pl.lds_fused);
+  if (cap > max_resident) cap = max_resident;
+  int clusters = cap / pl.g;
+  if (clusters < 1) return TS_ERR_DEVICE;   // a cluster must be co-resident
+  if (clusters > pl.units) clusters = pl.units;
+  loop_kernel<<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);
+  return TS_OK;
+}
+
 static int launch_fused(const ts_layout* layout, const void* k_new, const void* v_new,
                         const void* q, int32_t topk, const int32_t* topk_per_seq,
                         int32_t max_topk, float softmax_scale, void* out, float* scores_out,
@@ -736,49 +788,16 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.S = layout->page_size;
   p.units = pl.units;
   p.g = pl.g;
-  hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-  // One unit per cluster and everything resident: the loop-free build, which
-  // also exists with the append folded in.  Otherwise (thousands of units, bound
-  // by bandwidth) the looping build; an append then runs as a launch of its own
-  // in front of it: the looping build has no registers to spare for it, and
-  // against hundreds of microseconds the extra launch does not count.
-#define TS_LAUNCH_FUSED(DD, SS)                                                               \
-  do {                                                                                        \
-    if ((st = allow_lds(query_aware_decode_kernel<DD, SS, true, false>, pl.lds_fused)) !=     \
-            TS_OK ||                                                                          \
-        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, false>, pl.lds_fused)) !=    \
-            TS_OK ||                                                                          \
-        (st = allow_lds(query_aware_decode_kernel<DD, SS, false, true>, pl.lds_fused)) != TS_OK) \
-      return st;                                                                              \
-    int cap1 = k_new ? resident_capacity(query_aware_decode_kernel<DD, SS, false, true>,      \
-                                         pl.lds_fused)                                        \
-                     : resident_capacity(query_aware_decode_kernel<DD, SS, false, false>,     \
-                                         pl.lds_fused);                                       \
-    if (cap1 > cus * per_cu) cap1 = cus * per_cu;                                             \
-    if (pl.units * pl.g <= cap1) { /* one unit per cluster */                                 \
-      const unsigned grid = (unsigned)(pl.units * pl.g);                                      \
-      if (k_new)                                                                              \
-        query_aware_decode_kernel<DD, SS, false, true><<<grid, kThreads, pl.lds_fused, s>>>(p); \
-      else                                                                                    \
-        query_aware_decode_kernel<DD, SS, false, false><<<grid, kThreads, pl.lds_fused, s>>>(p); \
-      break;                                                                                  \
-    }                                                                                         \
-    int cap = resident_capacity(query_aware_decode_kernel<DD, SS, true, false>, pl.lds_fused); \
-    if (cap > cus * per_cu) cap = cus * per_cu;                                               \
-    int clusters = cap / pl.g;                                                                \
-    if (clusters < 1) return TS_ERR_DEVICE; /* a cluster must be co-resident */               \
-    if (clusters > pl.units) clusters = pl.units;                                             \
-    if (k_new) {                                                                              \
-      if ((st = ts_append_token_meta(layout, k_new, v_new, 1, stream)) != TS_OK) return st;   \
-      p.k_new = p.v_new = nullptr;                                                            \
-    }                                                                                         \
-    query_aware_decode_kernel<DD, SS, true, false>                                            \
-        <<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);                      \
-  } while (0)
+  st = TS_ERR_UNSUPPORTED;
+#define TS_LAUNCH_FUSED(DD, SS)                                                                 \
+  st = layout->kv_format == TS_KV_INT8                                                          \
+           ? launch_fused_shape<DD, SS, true>(layout, p, pl, k_new, v_new, cus * per_cu, stream) \
+           : launch_fused_shape<DD, SS, false>(layout, p, pl, k_new, v_new, cus * per_cu, stream)
   TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_FUSED);
 #undef TS_LAUNCH_FUSED
+  if (st != TS_OK) return st;
   return launch_status();
 }
 
@@ -848,8 +867,18 @@ int ts_build_page_meta(const ts_layout* layout, void* stream) {
       !layout->page_max)
     return TS_ERR_NULL;
   MetaParams p = meta_params(layout);
-  dim3 grid((p.Pmax + kWaves - 1) / kWaves, p.Hkv, p.B);
   if (p.B > 65535) return TS_ERR_UNSUPPORTED;
+  if (layout->kv_format == TS_KV_INT8) {
+    if (!layout->k_scale) return TS_ERR_NULL;
+    const int ppb = kThreads / layout->head_dim;   // pages per workgroup
+    dim3 grid8((p.Pmax + ppb - 1) / ppb, p.Hkv, p.B);
+    if (layout->head_dim == 64)
+      build_page_meta_i8_kernel<64><<<grid8, kThreads, 0, (hipStream_t)stream>>>(p);
+    else
+      build_page_meta_i8_kernel<128><<<grid8, kThreads, 0, (hipStream_t)stream>>>(p);
+    return launch_status();
+  }
+  dim3 grid((p.Pmax + kWaves - 1) / kWaves, p.Hkv, p.B);
   if (layout->head_dim == 64)
     build_page_meta_kernel<64><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
   else
@@ -864,6 +893,13 @@ int ts_append_token_meta(const ts_layout* layout, const void* k_new, const void*
   if (!k_new || !layout->seq_lens || !layout->page_min || !layout->page_max) return TS_ERR_NULL;
   if (v_new && (!layout->k_pool || !layout->v_pool || !layout->block_table)) return TS_ERR_NULL;
   MetaParams p = meta_params(layout);
+  if (layout->kv_format == TS_KV_INT8) {
+    if (v_new && (!layout->k_scale || !layout->v_scale)) return TS_ERR_NULL;
+    append_token_i8_kernel<<<p.B, kThreads, 0, (hipStream_t)stream>>>(
+        p, layout->head_dim, static_cast<const uint16_t*>(k_new),
+        static_cast<const uint16_t*>(v_new), advance_seq_lens);
+    return launch_status();
+  }
   append_token_meta_kernel<<<p.B, kThreads, 0, (hipStream_t)stream>>>(
       p, layout->head_dim, static_cast<const uint16_t*>(k_new),
       static_cast<const uint16_t*>(v_new), advance_seq_lens);
@@ -925,8 +961,15 @@ static int launch_attention(const ts_layout* layout, const Plan& pl, const void*
   dim3 grid(pl.g, pl.units);
   hipStream_t s = (hipStream_t)stream;
   const int D = layout->head_dim, S = layout->page_size;
-#define TS_LAUNCH_ATTENTION(DD, SS) \
-  sparse_attention_kernel<DD, SS><<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride)
+#define TS_LAUNCH_ATTENTION(DD, SS)                                                               \
+  do {                                                                                            \
+    if (layout->kv_format == TS_KV_INT8)                                                          \
+      sparse_attention_kernel<DD, SS, true>                                                       \
+          <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride);                 \
+    else                                                                                          \
+      sparse_attention_kernel<DD, SS, false>                                                      \
+          <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride);                 \
+  } while (0)
   TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_ATTENTION);
 #undef TS_LAUNCH_ATTENTION
   return launch_status();
@@ -983,6 +1026,7 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
 #undef TS_CAPACITY
   if (cap1 <= 0) return TS_ERR_DEVICE;
   if (cap1 > cus * per_cu) cap1 = cus * per_cu;
+  if (layout->kv_format == TS_KV_INT8) return 2;   // always appended to by a kernel of its own
   return pl.units * pl.g <= cap1 ? 1 : 2;
 }
 

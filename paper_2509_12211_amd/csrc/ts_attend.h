@@ -19,6 +19,8 @@
 // four value tokens belong to); with S = 64 a page is two fragments, its first
 // and its second 32 tokens.
 #pragma once
+#include <type_traits>
+
 #include "ts_device.h"
 
 namespace ts {
@@ -38,6 +40,9 @@ struct AttendParams {
   const uint16_t* q;           // [B][Hq][D]
   const uint16_t* k_pool;      // [n_phys][Hkv] tiles of [S][D], tile_stride apart
   const uint16_t* v_pool;      // [n_phys][Hkv] tiles of [D][S], tile_stride apart
+                               // (INT8 cache: the same shapes in int8, stride in bytes)
+  const float* k_scale;        // INT8 cache only: fp32 [n_phys][Hkv][S], one scale per token
+  const float* v_scale;
   const int32_t* block_table;  // [B][Pmax]
   const int32_t* seq_lens;     // [B]
   float* out;                  // [B][Hq][D] fp32, or bf16 when out_bf16 != 0
@@ -149,6 +154,119 @@ __device__ __forceinline__ void load_small_pages(PageFrag<D, 16>& f, const uint1
     f.v[0][cb] = *reinterpret_cast<const uint2*>(vbase + (16 * cb * spread + r) * S);
 }
 
+// ---------------------------------------------------------------------------
+// INT8 cache: the same fragments fetched as int8 (half the bytes) together with
+// the per-token scales, and expanded to the bf16 MFMA operands in registers.
+// An int8 value is a bf16 number, so the products are those of the exact
+// integers; the token's scale multiplies the logit (K) and the softmax weight
+// (V) afterwards.
+// ---------------------------------------------------------------------------
+template <int D, int F>
+struct PageFrag8 {
+  static constexpr int NT = F / 16;
+  static constexpr int KW = D / 16;   // 32-bit words of this lane's D/4 key bytes
+  static constexpr int NCB = D / 16;
+  uint32_t k[NT][KW];
+  uint32_t v[NT][NCB];   // this lane's four tokens of channel 16 * cb + lane % 16
+  float4 ks[NT], vs[NT]; // scales of this lane's four tokens of tile t
+};
+
+// bytes b, b + 1 of w as two bf16 numbers
+__device__ __forceinline__ uint32_t i8_pair_to_bf16(uint32_t w, int b) {
+  const float lo = (float)(int)(int8_t)(w >> (8 * b));
+  const float hi = (float)(int)(int8_t)(w >> (8 * b + 8));
+  return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
+}
+
+template <int D, int F>
+__device__ __forceinline__ void expand_frag(const PageFrag8<D, F>& r, PageFrag<D, F>& f) {
+#pragma unroll
+  for (int t = 0; t < PageFrag<D, F>::NT; ++t) {
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i)
+      f.k[t][i] = make_uint4(i8_pair_to_bf16(r.k[t][2 * i], 0), i8_pair_to_bf16(r.k[t][2 * i], 2),
+                             i8_pair_to_bf16(r.k[t][2 * i + 1], 0),
+                             i8_pair_to_bf16(r.k[t][2 * i + 1], 2));
+#pragma unroll
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb)
+      f.v[t][cb] = make_uint2(i8_pair_to_bf16(r.v[t][cb], 0), i8_pair_to_bf16(r.v[t][cb], 2));
+  }
+}
+
+// One fragment of a page with S >= 16 tokens (see load_page).  scales: the
+// page's S scales in k_scale / v_scale.
+template <int D, int S>
+__device__ __forceinline__ void load_page8(PageFrag8<D, PageGeom<S>::F>& f, const uint8_t* ktile,
+                                           const uint8_t* vtile, const float* kscale,
+                                           const float* vscale, int hoff, int spread) {
+  constexpr int F = PageGeom<S>::F;
+  static_assert(S >= 16, "whole-page fragments");
+  const int lane = lane_id(), r = (lane & 15) * spread, kb = (lane >> 4) * spread;
+  hoff *= spread;
+#pragma unroll
+  for (int t = 0; t < PageFrag8<D, F>::NT; ++t) {
+    const uint8_t* krow = ktile + (hoff + tile_token<F>(t, r)) * D * spread + kb * (D / 4);
+    if (D == 64) {
+      const uint4 w = *reinterpret_cast<const uint4*>(krow);
+      f.k[t][0] = w.x; f.k[t][1] = w.y; f.k[t][2] = w.z; f.k[t][3] = w.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < D / 64; ++i) {
+        const uint4 w = *reinterpret_cast<const uint4*>(krow + 16 * i * spread);
+        f.k[t][4 * i] = w.x; f.k[t][4 * i + 1] = w.y; f.k[t][4 * i + 2] = w.z; f.k[t][4 * i + 3] = w.w;
+      }
+    }
+    const int tok0 = hoff + tile_token<F>(t, 4 * kb);
+    f.ks[t] = *reinterpret_cast<const float4*>(kscale + tok0);
+    f.vs[t] = *reinterpret_cast<const float4*>(vscale + tok0);
+  }
+#pragma unroll
+  for (int cb = 0; cb < PageFrag8<D, F>::NCB; ++cb) {
+    const uint8_t* vrow = vtile + (16 * cb * spread + r) * S + hoff;
+    if (F == 16) {
+      f.v[0][cb] = *reinterpret_cast<const uint32_t*>(vrow + 4 * kb);
+    } else {
+      const uint2 w = *reinterpret_cast<const uint2*>(vrow + 8 * kb);
+      f.v[0][cb] = w.x;
+      f.v[F == 16 ? 0 : 1][cb] = w.y;
+    }
+  }
+}
+
+// One 16-token fragment made of 16 / S small pages (see load_small_pages);
+// soff[s]: offset of the s-th page's scales in k_scale / v_scale.
+template <int D, int S>
+__device__ __forceinline__ void load_small_pages8(PageFrag8<D, 16>& f, const uint8_t* k_pool,
+                                                  const uint8_t* v_pool, const float* k_scale,
+                                                  const float* v_scale,
+                                                  const size_t (&toff)[PageGeom<S>::NS],
+                                                  const size_t (&soff)[PageGeom<S>::NS],
+                                                  int spread) {
+  constexpr int NS = PageGeom<S>::NS;
+  static_assert(S < 16, "several pages per fragment");
+  const int lane = lane_id(), r = (lane & 15) * spread, kb = (lane >> 4) * spread;
+  const int sk = r / S, sv = (4 * kb) / S;
+  size_t ok = toff[0], ov = toff[0], os = soff[0];
+#pragma unroll
+  for (int s = 1; s < NS; ++s) {
+    ok = sk == s ? toff[s] : ok;
+    ov = sv == s ? toff[s] : ov;
+    os = sv == s ? soff[s] : os;
+  }
+  const uint8_t* krow = k_pool + ok + (r % S) * D + kb * (D / 4);
+#pragma unroll
+  for (int i = 0; i < D / 64; ++i) {
+    const uint4 w = *reinterpret_cast<const uint4*>(krow + 16 * i * spread);
+    f.k[0][4 * i] = w.x; f.k[0][4 * i + 1] = w.y; f.k[0][4 * i + 2] = w.z; f.k[0][4 * i + 3] = w.w;
+  }
+  f.ks[0] = *reinterpret_cast<const float4*>(k_scale + os + (4 * kb) % S);
+  f.vs[0] = *reinterpret_cast<const float4*>(v_scale + os + (4 * kb) % S);
+  const uint8_t* vbase = v_pool + ov + (4 * kb) % S;
+#pragma unroll
+  for (int cb = 0; cb < PageFrag8<D, 16>::NCB; ++cb)
+    f.v[0][cb] = *reinterpret_cast<const uint32_t*>(vbase + (16 * cb * spread + r) * S);
+}
+
 // A token appended in the same launch: it belongs to page j (-1: none), slot
 // `slot` of that page; its key / value rows (D bf16 each) are read from the
 // caller's arrays and spliced into the page's operands in registers, so the
@@ -233,9 +351,14 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
 // One fragment: logits, online-softmax update, weighted value accumulation.
 // Bit x of `vmask` says whether fragment token x exists (tokens past the end of
 // the sequence, and the tokens of a missing page, are masked).
-template <int D, int F>
+//
+// kScaled (INT8 cache): ks[t] / vs[t] hold the scales of this lane's four tokens of
+// tile t; a logit is multiplied by its token's key scale, and a softmax weight by
+// its token's value scale on its way into the P.V product (not in the running sum).
+template <int D, int F, bool kScaled = false>
 __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short4_t (&qf)[D / 16],
-                                            uint32_t vmask, float scale_log2, WaveAcc<D>& a) {
+                                            uint32_t vmask, float scale_log2, WaveAcc<D>& a,
+                                            const float4* ks = nullptr, const float4* vs = nullptr) {
   constexpr int NT = PageFrag<D, F>::NT, NCB = PageFrag<D, F>::NCB;
   const int kb = lane_id() >> 4;
   float4_t sc[NT];
@@ -249,9 +372,12 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
       sc[t] = mfma16(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
     }
     const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
+    float kst[4] = {1.f, 1.f, 1.f, 1.f};
+    if (kScaled) { kst[0] = ks[t].x; kst[1] = ks[t].y; kst[2] = ks[t].z; kst[3] = ks[t].w; }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const float x = (mine >> v) & 1u ? sc[t][v] * scale_log2 : -INFINITY;
+      const float raw = kScaled ? sc[t][v] * kst[v] : sc[t][v];
+      const float x = (mine >> v) & 1u ? raw * scale_log2 : -INFINITY;
       sc[t][v] = x;
       mx = fmaxf(mx, x);
     }
@@ -269,21 +395,25 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
     // softmax weights split into two bf16 terms (truncated high part + remainder)
     // so the P.V product keeps ~16 significant bits of each weight
     uint32_t hi[4], lo[4];
+    const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);
+    float vst[4] = {1.f, 1.f, 1.f, 1.f};
+    if (kScaled) { vst[0] = vs[t].x; vst[1] = vs[t].y; vst[2] = vs[t].z; vst[3] = vs[t].w; }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const float pv = __builtin_amdgcn_exp2f(sc[t][v] - m_new);
+      float pv = __builtin_amdgcn_exp2f(sc[t][v] - m_new);
       a.l += pv;
+      // (a slot without a token may hold any scale: its weight is zero, keep it zero)
+      if (kScaled) pv = (mine >> v) & 1u ? pv * vst[v] : 0.f;
       hi[v] = __float_as_uint(pv) & 0xffff0000u;
       lo[v] = __float_as_uint(pv - __uint_as_float(hi[v]));
     }
     const short4_t ph = as_short4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
     const short4_t pl = as_short4((lo[0] >> 16) | (lo[1] & 0xffff0000u),
                                   (lo[2] >> 16) | (lo[3] & 0xffff0000u));
-    const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       uint32_t v0 = f.v[t][cb].x, v1 = f.v[t][cb].y;
-      if (partial) {  // slots that hold no token may hold anything: zero them
+      if (partial && !kScaled) {  // slots that hold no token may hold anything: zero them
         if (!(mine & 1u)) v0 &= 0xffff0000u;
         if (!(mine & 2u)) v0 &= 0x0000ffffu;
         if (!(mine & 4u)) v1 &= 0xffff0000u;
@@ -309,12 +439,17 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 // below); with false the refill past the end of the list is skipped instead,
 // which suits bandwidth-bound launches with thousands of units.
 // kPatch: a token appended in the same launch may have to be spliced in (nt).
-template <int D, int S, bool kBranchless, bool kPatch, typename SelAt, typename PhysAt>
+// kInt8: the cache holds int8 keys / values with per-token scales.
+template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, typename SelAt, typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
                                              PhysAt phys_at, float* lds) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
+  static_assert(!(kPatch && kInt8), "no in-register append for the INT8 cache");
+  using Frag = std::conditional_t<kInt8, PageFrag8<D, F>, PageFrag<D, F>>;
+  const uint8_t* k_pool8 = reinterpret_cast<const uint8_t*>(p.k_pool);
+  const uint8_t* v_pool8 = reinterpret_cast<const uint8_t*>(p.v_pool);
   const int lane = lane_id(), wave = wave_id();
   const int head = lane & 15, kb = lane >> 4;
   const int G = p.G;
@@ -361,7 +496,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     // A ring of NBUF fragment buffers: up to NBUF fragments of this wave are in
     // flight (2 KiB - 8 KiB each) before the first is consumed.
     constexpr int NBUF = (D * F <= 1024) ? 4 : ((D == 64 && D * F <= 2048) ? 3 : 2);
-    PageFrag<D, F> f[NBUF];
+    Frag f[NBUF];
     uint32_t vmask[NBUF];
     int item[NBUF];
     // No branch around the loads (a load under a branch makes the compiler
@@ -369,7 +504,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     // would drain before the first fragment is used): a slot past the end of
     // the list, or one whose page id is out of range, re-reads a page that is
     // certainly mapped (a single cache line of it) and has no valid token.
-    auto issue = [&](PageFrag<D, F>& fr, int& it, int x) -> uint32_t {
+    auto issue = [&](Frag& fr, int& it, int x) -> uint32_t {
       const int xc = min(x, n - 1);
       it = batch + xc * kWaves;
       if constexpr (S >= 16) {
@@ -378,11 +513,17 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
         const int hoff = NH > 1 ? (it % NH) * F : 0;
         const bool good = x < n && phys >= 0 && phys < p.n_phys;
         const size_t tile = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
-        load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile, hoff, good ? 1 : 0);
+        if constexpr (kInt8) {
+          const size_t so = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)S;
+          load_page8<D, S>(fr, k_pool8 + tile, v_pool8 + tile, p.k_scale + so, p.v_scale + so, hoff,
+                           good ? 1 : 0);
+        } else {
+          load_page<D, S>(fr, p.k_pool + tile, p.v_pool + tile, hoff, good ? 1 : 0);
+        }
         const int valid = good ? max(0, min(F, L - j * S - hoff)) : 0;
         return valid >= 32 ? 0xffffffffu : (1u << valid) - 1u;
       } else {
-        size_t toff[NS];
+        size_t toff[NS], soff[NS];
         uint32_t m = 0;
         bool any = false;
 #pragma unroll
@@ -391,11 +532,16 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
           const int phys = __builtin_amdgcn_readlane(my_phys[s], xc);
           const bool good = x < n && phys >= 0 && phys < p.n_phys;
           toff[s] = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride;
+          soff[s] = ((size_t)(good ? phys : 0) * p.Hkv + h) * (size_t)S;
           const int valid = good ? max(0, min(S, L - j * S)) : 0;
           m |= ((1u << valid) - 1u) << (s * S);
           any = any || good;
         }
-        load_small_pages<D, S>(fr, p.k_pool, p.v_pool, toff, any ? 1 : 0);
+        if constexpr (kInt8)
+          load_small_pages8<D, S>(fr, k_pool8, v_pool8, p.k_scale, p.v_scale, toff, soff,
+                                  any ? 1 : 0);
+        else
+          load_small_pages<D, S>(fr, p.k_pool, p.v_pool, toff, any ? 1 : 0);
         return m;
       }
     };
@@ -406,8 +552,14 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
         if (x0 + i < n) {
-          if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
-          attend_page<D, F>(f[i], qf, vmask[i], p.scale_log2, acc);
+          if constexpr (kInt8) {
+            PageFrag<D, F> fx;
+            expand_frag<D, F>(f[i], fx);
+            attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs);
+          } else {
+            if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
+            attend_page<D, F>(f[i], qf, vmask[i], p.scale_log2, acc);
+          }
         }
         if (kBranchless || x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
       }

@@ -13,6 +13,8 @@ struct MetaParams {
   uint16_t* page_min;
   uint16_t* page_max;
   int B, Hkv, S, Pmax, n_phys, tile_stride;
+  float* k_scale;   // INT8 cache only: fp32 [n_phys][Hkv][S]
+  float* v_scale;
 };
 
 // One wavefront summarises one (sequence, KV head, logical page): the S x D
@@ -126,6 +128,130 @@ __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams 
   }
   const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
   __syncthreads();
+  if (ok && advance && threadIdx.x == 0) p.seq_lens[b] = L + 1;
+}
+
+// ---------------------------------------------------------------------------
+// INT8 cache.  The key of a token is code * scale (one fp32 scale per token and
+// KV head) as a real number; a page's box has to contain those numbers for
+// Eq. 2 to remain an upper bound, so the minimum is rounded DOWN to bf16 and
+// the maximum UP.  int8 x fp32 is exact in fp64.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint16_t bf16_directed(double x, bool up) {
+  float f = static_cast<float>(x);   // nearest; then moved to the right side of x
+  uint32_t b = __float_as_uint(f);
+  if (up ? static_cast<double>(f) < x : static_cast<double>(f) > x) {
+    const bool away = up ? !(b >> 31) : (b >> 31) != 0;   // a step away from zero
+    if ((b & 0x7fffffffu) == 0u) b = up ? 0x00000001u : 0x80000001u;
+    else b = away ? b + 1u : b - 1u;
+  }
+  uint16_t hi = static_cast<uint16_t>(b >> 16);
+  if ((b & 0xffffu) != 0u) {
+    // dropping the low bits moves towards zero: down for positive values, up for negative
+    const bool negative = (b >> 31) != 0;
+    if (negative ? !up : up) hi = static_cast<uint16_t>(hi + 1);
+  }
+  return hi;
+}
+
+// One thread per (page, channel): kThreads / D pages per workgroup.  Set-up
+// work (a page is summarised once; appends keep it current), kept plain.
+template <int D>
+__global__ __launch_bounds__(kThreads) void build_page_meta_i8_kernel(MetaParams p) {
+  constexpr int PPB = kThreads / D;
+  const int c = threadIdx.x % D;
+  const int j = blockIdx.x * PPB + threadIdx.x / D;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int L = p.seq_lens[b];
+  const int Pb = (L + p.S - 1) / p.S;
+  if (j >= Pb || j >= p.Pmax) return;
+  const int phys = p.block_table[(size_t)b * p.Pmax + j];
+  if (phys < 0 || phys >= p.n_phys) return;
+  const int valid = min(p.S, L - j * p.S);
+  const int8_t* tile = reinterpret_cast<const int8_t*>(p.k_pool) +
+                       ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
+  const float* sc = p.k_scale + ((size_t)phys * p.Hkv + h) * (size_t)p.S;
+  double lo = INFINITY, hi = -INFINITY;
+  for (int t = 0; t < valid; ++t) {
+    const double k = static_cast<double>(tile[(size_t)t * D + c]) * static_cast<double>(sc[t]);
+    lo = fmin(lo, k);
+    hi = fmax(hi, k);
+  }
+  const size_t row = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + c;
+  p.page_min[row] = bf16_directed(lo, false);
+  p.page_max[row] = bf16_directed(hi, true);
+}
+
+// Append to the INT8 cache: one workgroup per sequence, a wave per KV head at a
+// time.  The bf16 key and value are quantised (scale = max |x| / 127, 1 for a
+// zero vector; code = x / scale rounded half to even, in fp32 with correctly
+// rounded division), stored with their scales when v_new is given, and the
+// page's box is opened / widened with the dequantised key rounded outwards.
+__global__ __launch_bounds__(kThreads) void append_token_i8_kernel(MetaParams p, int D,
+                                                                   const uint16_t* k_new,
+                                                                   const uint16_t* v_new,
+                                                                   int advance) {
+  const int b = blockIdx.x, lane = lane_id();
+  const int L = p.seq_lens[b];
+  const int sh = __builtin_ctz(p.S);
+  const int j = L >> sh, slot = L & (p.S - 1);
+  const bool fits = j < p.Pmax;
+  const int phys = p.block_table[(size_t)b * p.Pmax + (fits ? j : 0)];
+  const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
+  if (ok) {
+    for (int h = wave_id(); h < p.Hkv; h += kWaves) {
+      const uint16_t* kr = k_new + ((size_t)b * p.Hkv + h) * D;
+      const uint16_t* vr = (v_new ? v_new : k_new) + ((size_t)b * p.Hkv + h) * D;
+      float kv[2], vv[2], ka = 0.f, va = 0.f;   // channels lane, lane + 64
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int c = lane + 64 * i;
+        kv[i] = c < D ? bf16_to_f32(kr[c]) : 0.f;
+        vv[i] = c < D ? bf16_to_f32(vr[c]) : 0.f;
+        ka = fmaxf(ka, fabsf(kv[i]));
+        va = fmaxf(va, fabsf(vv[i]));
+      }
+#pragma unroll
+      for (int m = 1; m < kWave; m <<= 1) {
+        ka = fmaxf(ka, shfl_xor_f(ka, m));
+        va = fmaxf(va, shfl_xor_f(va, m));
+      }
+      const float ksc = ka > 0.f ? __fdiv_rn(ka, 127.0f) : 1.0f;
+      const float vsc = va > 0.f ? __fdiv_rn(va, 127.0f) : 1.0f;
+      const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
+      int8_t* k8 = reinterpret_cast<int8_t*>(p.k_pool_w);
+      int8_t* v8 = reinterpret_cast<int8_t*>(p.v_pool_w);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int c = lane + 64 * i;
+        if (c < D) {
+          const float kq = fminf(fmaxf(rintf(__fdiv_rn(kv[i], ksc)), -127.f), 127.f);
+          const float vq = fminf(fmaxf(rintf(__fdiv_rn(vv[i], vsc)), -127.f), 127.f);
+          if (v_new != nullptr) {
+            k8[tile + (size_t)slot * D + c] = static_cast<int8_t>(kq);
+            v8[tile + (size_t)c * p.S + slot] = static_cast<int8_t>(vq);
+          }
+          // (through the integer: a code that rounded to -0.0f must give +0, as the stored byte does)
+          const double kd = static_cast<double>(static_cast<int>(kq)) * static_cast<double>(ksc);
+          const uint16_t lo = bf16_directed(kd, false), hi = bf16_directed(kd, true);
+          const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + c;
+          if (slot == 0) {
+            p.page_min[m] = lo;
+            p.page_max[m] = hi;
+          } else {
+            if (bf16_to_f32(lo) < bf16_to_f32(p.page_min[m])) p.page_min[m] = lo;
+            if (bf16_to_f32(hi) > bf16_to_f32(p.page_max[m])) p.page_max[m] = hi;
+          }
+        }
+      }
+      if (v_new != nullptr && lane == 0) {
+        const size_t so = ((size_t)phys * p.Hkv + h) * (size_t)p.S + slot;
+        p.k_scale[so] = ksc;
+        p.v_scale[so] = vsc;
+      }
+    }
+  }
+  __syncthreads();   // every thread has read seq_lens[b]
   if (ok && advance && threadIdx.x == 0) p.seq_lens[b] = L + 1;
 }
 

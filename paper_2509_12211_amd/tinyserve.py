@@ -24,6 +24,8 @@ TS_ERR_LAUNCH = -5
 TS_ERR_DEVICE = -6
 TS_OUT_F32 = 0
 TS_OUT_BF16 = 1
+TS_KV_BF16 = 0
+TS_KV_INT8 = 1
 
 EXPORTS = [
     "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
@@ -43,7 +45,8 @@ class TsLayout(ctypes.Structure):
         ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
         ("page_min", ctypes.c_void_p), ("page_max", ctypes.c_void_p),
         ("keep_first_pages", ctypes.c_int32), ("keep_last_pages", ctypes.c_int32),
-        ("out_format", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("out_format", ctypes.c_int32), ("kv_format", ctypes.c_int32),
+        ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -108,8 +111,10 @@ def _check(status, where):
 
 
 def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, page_min,
-                page_max, keep_first_pages=0, keep_last_pages=0, out_format=TS_OUT_F32) -> TsLayout:
-    """Fill the C struct; tensors must stay alive while calls using it are in flight."""
+                page_max, keep_first_pages=0, keep_last_pages=0, out_format=TS_OUT_F32,
+                k_scale=None, v_scale=None) -> TsLayout:
+    """Fill the C struct; tensors must stay alive while calls using it are in flight.
+    int8 pools (with k_scale / v_scale) select the INT8 cache format."""
     n_phys = 0 if k_pool is None else k_pool.shape[0]
     tile_stride = 0
     if k_pool is not None and Hkv > 1:
@@ -126,7 +131,10 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                    None if seq_lens is None else seq_lens.data_ptr(),
                    None if page_min is None else page_min.data_ptr(),
                    None if page_max is None else page_max.data_ptr(),
-                   int(keep_first_pages), int(keep_last_pages), int(out_format), 0)
+                   int(keep_first_pages), int(keep_last_pages), int(out_format),
+                   TS_KV_INT8 if (k_pool is not None and k_pool.dtype == torch.int8) else TS_KV_BF16,
+                   None if k_scale is None else k_scale.data_ptr(),
+                   None if v_scale is None else v_scale.data_ptr())
     return lay
 
 

@@ -41,6 +41,7 @@ class WorkloadSpec:
     L_min: int = 0             # ragged: lengths uniform in [L_min, L]; 0 = all equal L
     budget_frac: float = 0.0   # ragged: K_b = ceil(budget_frac * P_b)
     headroom: int = 64         # tokens of append room per sequence
+    kv: str = "bf16"           # "bf16" | "int8" (int8 codes + one fp32 scale per token and head)
 
 
 SPECS = {
@@ -72,12 +73,14 @@ class Workload:
     topk: int
     topk_per_seq: Optional[torch.Tensor]   # int32 [B] or None
     num_phys_pages: int
-    k_pool: torch.Tensor          # bf16 [n_phys][Hkv][S][d]
-    v_pool: torch.Tensor          # bf16 [n_phys][Hkv][d][S]
+    k_pool: torch.Tensor          # bf16 (or int8) [n_phys][Hkv][S][d]
+    v_pool: torch.Tensor          # bf16 (or int8) [n_phys][Hkv][d][S]
     block_table: torch.Tensor     # int32 [B][P_max]
     q: torch.Tensor               # bf16 [n_q][B][Hq][d]
     k_new: torch.Tensor           # bf16 [n_new][B][Hkv][d]
     v_new: torch.Tensor           # bf16 [n_new][B][Hkv][d]
+    k_scale: Optional[torch.Tensor] = None   # int8 cache: fp32 [n_phys][Hkv][S]
+    v_scale: Optional[torch.Tensor] = None
 
     @property
     def device(self):
@@ -138,27 +141,53 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
         block_table[b, :n] = perm[start:start + n].to(torch.int32)
         start += n
 
+    int8 = spec.kv == "int8"
+    dt = torch.int8 if int8 else torch.bfloat16
+    fill = -128 if int8 else poison          # code -128 is never generated
     if interleave:
-        kv = torch.full((n_phys, Hkv, 2, S * d), poison, dtype=torch.bfloat16, device=device)
+        kv = torch.full((n_phys, Hkv, 2, S * d), fill, dtype=dt, device=device)
         k_pool = kv[:, :, 0].view(n_phys, Hkv, S, d)
         v_pool = kv[:, :, 1].view(n_phys, Hkv, d, S)
     else:
-        k_pool = torch.full((n_phys, Hkv, S, d), poison, dtype=torch.bfloat16, device=device)
-        v_pool = torch.full((n_phys, Hkv, d, S), poison, dtype=torch.bfloat16, device=device)
+        k_pool = torch.full((n_phys, Hkv, S, d), fill, dtype=dt, device=device)
+        v_pool = torch.full((n_phys, Hkv, d, S), fill, dtype=dt, device=device)
+    k_scale = v_scale = None
+    if int8:
+        k_scale = torch.full((n_phys, Hkv, S), poison, dtype=torch.float32, device=device)
+        v_scale = torch.full((n_phys, Hkv, S), poison, dtype=torch.float32, device=device)
     g = _gen(device, seed)
     offset = torch.randn((Hkv, d), generator=g, device=device, dtype=torch.float32) * 2.0
     bt_dev = block_table.to(device)
+
+    def codes_of(x):
+        """int8 codes and per-token scales carrying the structure of the fp32 draw x
+        [Hkv][L][d].  (A way to get int8 data of the workload's shape; it is not the
+        library's quantiser, which only ts_append_token_meta exercises.)"""
+        jitter = 1.0 + 0.05 * torch.rand(x.shape[:2], generator=g, device=device)
+        sc = (x.abs().amax(dim=-1).clamp_(min=1e-6) / 120.0) * jitter
+        return torch.round(x / sc[..., None]).clamp_(-127, 127).to(torch.int8), sc
+
     for b in range(B):
         L = int(lens[b])
         Pb = (L + S - 1) // S
-        k = _draw_keys(spec, g, Hkv, L, d, device, offset).to(torch.bfloat16)
-        v = torch.randn((Hkv, L, d), generator=g, device=device,
-                        dtype=torch.float32).to(torch.bfloat16)
-        kp = torch.full((Hkv, Pb * S, d), poison, dtype=torch.bfloat16, device=device)
-        vp = torch.full((Hkv, Pb * S, d), poison, dtype=torch.bfloat16, device=device)
+        k = _draw_keys(spec, g, Hkv, L, d, device, offset)
+        v = torch.randn((Hkv, L, d), generator=g, device=device, dtype=torch.float32)
+        phys = bt_dev[b, :Pb].to(torch.int64)
+        if int8:
+            k, ks = codes_of(k)
+            v, vs = codes_of(v)
+            ksp = torch.full((Hkv, Pb * S), poison, dtype=torch.float32, device=device)
+            vsp = torch.full((Hkv, Pb * S), poison, dtype=torch.float32, device=device)
+            ksp[:, :L] = ks
+            vsp[:, :L] = vs
+            k_scale[phys] = ksp.view(Hkv, Pb, S).permute(1, 0, 2)
+            v_scale[phys] = vsp.view(Hkv, Pb, S).permute(1, 0, 2)
+        else:
+            k, v = k.to(torch.bfloat16), v.to(torch.bfloat16)
+        kp = torch.full((Hkv, Pb * S, d), fill, dtype=dt, device=device)
+        vp = torch.full((Hkv, Pb * S, d), fill, dtype=dt, device=device)
         kp[:, :L] = k
         vp[:, :L] = v
-        phys = bt_dev[b, :Pb].to(torch.int64)
         k_pool[phys] = kp.view(Hkv, Pb, S, d).permute(1, 0, 2, 3)
         v_pool[phys] = vp.view(Hkv, Pb, S, d).permute(1, 0, 3, 2)
         del k, v, kp, vp
@@ -182,7 +211,7 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
         K_max = spec.topk
         topk = spec.topk
     return Workload(spec, seq_lens, P_max, K_max, topk, tps, n_phys, k_pool, v_pool, bt_dev, q,
-                    k_new, v_new)
+                    k_new, v_new, k_scale, v_scale)
 
 
 def logical_kv(w: Workload, seqs=None, heads=None, seq_lens=None):
@@ -212,6 +241,35 @@ def logical_kv(w: Workload, seqs=None, heads=None, seq_lens=None):
     return K, V
 
 
+def logical_kv_i8(w: Workload, seqs=None, heads=None, seq_lens=None):
+    """INT8 cache: logical codes [n][nh][Lmax][d] (int8, zero padded) and scales
+    [n][nh][Lmax] (fp32, one padded) of keys and values: (Kq, ks, Vq, vs)."""
+    spec = w.spec
+    S, d = spec.S, spec.d
+    lens = (w.seq_lens if seq_lens is None else seq_lens).to("cpu", torch.int64)
+    seqs = list(range(spec.B)) if seqs is None else list(seqs)
+    heads = list(range(spec.Hkv)) if heads is None else list(heads)
+    Lmax = max(max(int(lens[b]) for b in seqs), 1)
+    hidx = torch.tensor(heads, dtype=torch.int64, device=w.device)
+    Kq = torch.zeros((len(seqs), len(heads), Lmax, d), dtype=torch.int8, device=w.device)
+    Vq = torch.zeros_like(Kq)
+    ks = torch.ones((len(seqs), len(heads), Lmax), dtype=torch.float32, device=w.device)
+    vs = torch.ones_like(ks)
+    for i, b in enumerate(seqs):
+        L = int(lens[b])
+        Pb = (L + S - 1) // S
+        if Pb == 0:
+            continue
+        phys = w.block_table[b, :Pb].to(torch.int64)
+        kp = w.k_pool[phys][:, hidx]
+        vp = w.v_pool[phys][:, hidx]
+        Kq[i, :, :L] = kp.permute(1, 0, 2, 3).reshape(len(heads), Pb * S, d)[:, :L]
+        Vq[i, :, :L] = vp.permute(1, 0, 3, 2).reshape(len(heads), Pb * S, d)[:, :L]
+        ks[i, :, :L] = w.k_scale[phys][:, hidx].permute(1, 0, 2).reshape(len(heads), Pb * S)[:, :L]
+        vs[i, :, :L] = w.v_scale[phys][:, hidx].permute(1, 0, 2).reshape(len(heads), Pb * S)[:, :L]
+    return Kq, ks, Vq, vs
+
+
 def bits(t: torch.Tensor):
     """bf16 tensor -> numpy uint16 bit patterns (host copy)."""
     import numpy as np
@@ -235,7 +293,8 @@ def algorithmic_bytes(spec: WorkloadSpec, seq_lens, topk_per_seq=None) -> dict:
         Kb = torch.minimum(topk_per_seq.to("cpu", torch.int64), P)
     else:
         Kb = torch.clamp(P, max=spec.topk)
+    tok = 2 * spec.d * 2 if spec.kv == "bf16" else 2 * spec.d + 8   # K + V (+ two scales) per token
     meta = int(P.sum()) * spec.Hkv * 2 * spec.d * 2
-    kv = int(Kb.sum()) * spec.Hkv * spec.S * 2 * spec.d * 2
-    dense = int((P * spec.S).sum()) * spec.Hkv * 2 * spec.d * 2
+    kv = int(Kb.sum()) * spec.Hkv * spec.S * tok
+    dense = int((P * spec.S).sum()) * spec.Hkv * tok
     return {"meta": meta, "kv": kv, "total": meta + kv, "dense": dense}
