@@ -48,9 +48,35 @@ static double bf16_to_double(uint16_t bits) {
   return (double)f;
 }
 
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits), decoded by its definition. */
+static double half_to_double(uint16_t bits) {
+  int sign = bits >> 15, e = (bits >> 10) & 31, m = bits & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)m, -24);                 /* zero and subnormals: m * 2^-24 */
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+  return sign ? -v : v;
+}
+
+/* Element format of the 16-bit inputs (queries, keys, values, metadata) of the
+ * functions of the paper's path: 0 = bf16 (the default), 1 = IEEE half, the
+ * "FP16" the paper's experiments run in (Section 4, experimental set-up).
+ * Nothing else changes with it: every value is decoded exactly to double.  The
+ * INT8 cache functions at the end of this file always take bf16 queries. */
+static int g_elem_half = 0;
+void tso_set_element_format(int half) { g_elem_half = half ? 1 : 0; }
+
+static double elem_to_double(uint16_t bits) {
+  return g_elem_half ? half_to_double(bits) : bf16_to_double(bits);
+}
+
+void tso_decode_elements(const uint16_t* bits, int n, double* out) {
+  for (int i = 0; i < n; ++i) out[i] = elem_to_double(bits[i]);
+}
+
 static int pages_of(int len, int S) { return (len + S - 1) / S; }
 
-int tso_version(void) { return 3; }
+int tso_version(void) { return 4; }
 
 int tso_max_threads(void) {
 #ifdef _OPENMP
@@ -79,8 +105,8 @@ void tso_build_page_meta(const uint16_t* K, const int32_t* seq_lens, int B, int 
           uint16_t lo = Kbh[(size_t)t0 * d + c], hi = lo;
           for (int t = t0 + 1; t < t1; ++t) {
             uint16_t x = Kbh[(size_t)t * d + c];
-            if (bf16_to_double(x) < bf16_to_double(lo)) lo = x;
-            if (bf16_to_double(x) > bf16_to_double(hi)) hi = x;
+            if (elem_to_double(x) < elem_to_double(lo)) lo = x;
+            if (elem_to_double(x) > elem_to_double(hi)) hi = x;
           }
           mrow[c] = lo;
           Mrow[c] = hi;
@@ -110,8 +136,8 @@ void tso_append_token_meta(const uint16_t* k_new /*[B][Hkv][d]*/, const int32_t*
           mrow[c] = k[c];
           Mrow[c] = k[c];
         } else {
-          if (bf16_to_double(k[c]) < bf16_to_double(mrow[c])) mrow[c] = k[c];
-          if (bf16_to_double(k[c]) > bf16_to_double(Mrow[c])) Mrow[c] = k[c];
+          if (elem_to_double(k[c]) < elem_to_double(mrow[c])) mrow[c] = k[c];
+          if (elem_to_double(k[c]) > elem_to_double(Mrow[c])) Mrow[c] = k[c];
         }
       }
     }
@@ -142,8 +168,8 @@ void tso_score_pages(const uint16_t* q, const uint16_t* page_min, const uint16_t
         for (int g = 0; g < G; ++g) {
           const uint16_t* qg = q + ((size_t)b * Hq + (size_t)h * G + g) * d;
           for (int c = 0; c < d; ++c) {
-            double qc = bf16_to_double(qg[c]);
-            double lo = bf16_to_double(mrow[c]), hi = bf16_to_double(Mrow[c]);
+            double qc = elem_to_double(qg[c]);
+            double lo = elem_to_double(mrow[c]), hi = elem_to_double(Mrow[c]);
             if (form == 1) {
               double a = qc * lo, bb = qc * hi;
               s += a > bb ? a : bb;
@@ -264,7 +290,7 @@ void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uin
       for (int t = j * S; t < (j + 1) * S && t < L; ++t) {
         double dot = 0.0;
         for (int c = 0; c < d; ++c)
-          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+          dot += elem_to_double(qg[c]) * elem_to_double(Kbh[(size_t)t * d + c]);
         a[cnt] = scale * dot;
         tok[cnt] = t;
         if (a[cnt] > amax) amax = a[cnt];
@@ -279,7 +305,7 @@ void tso_sparse_decode_attention(const uint16_t* q, const uint16_t* K, const uin
     }
     for (int i = 0; i < cnt; ++i) {
       double w = a[i] / denom;
-      for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)tok[i] * d + c]);
+      for (int c = 0; c < d; ++c) o[c] += w * elem_to_double(Vbh[(size_t)tok[i] * d + c]);
     }
     if (lse) lse[(size_t)b * Hq + g] = cnt > 0 ? amax + log(denom) : -INFINITY;
     free(a);
@@ -306,7 +332,7 @@ void tso_dense_decode_attention(const uint16_t* q, const uint16_t* K, const uint
       for (int t = 0; t < L; ++t) {
         double dot = 0.0;
         for (int c = 0; c < d; ++c)
-          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+          dot += elem_to_double(qg[c]) * elem_to_double(Kbh[(size_t)t * d + c]);
         a[t] = scale * dot;
         if (a[t] > amax) amax = a[t];
       }
@@ -318,7 +344,7 @@ void tso_dense_decode_attention(const uint16_t* q, const uint16_t* K, const uint
       for (int c = 0; c < d; ++c) o[c] = 0.0;
       for (int t = 0; t < L; ++t) {
         double w = a[t] / denom;
-        for (int c = 0; c < d; ++c) o[c] += w * bf16_to_double(Vbh[(size_t)t * d + c]);
+        for (int c = 0; c < d; ++c) o[c] += w * elem_to_double(Vbh[(size_t)t * d + c]);
       }
       if (lse) lse[(size_t)b * Hq + g] = L > 0 ? amax + log(denom) : -INFINITY;
       free(a);
@@ -359,7 +385,7 @@ void tso_true_page_max(const uint16_t* q, const uint16_t* K, const int32_t* seq_
       for (int t = 0; t < L; ++t) {
         double dot = 0.0;
         for (int c = 0; c < d; ++c)
-          dot += bf16_to_double(qg[c]) * bf16_to_double(Kbh[(size_t)t * d + c]);
+          dot += elem_to_double(qg[c]) * elem_to_double(Kbh[(size_t)t * d + c]);
         if (t / S < Pmax && dot > row[t / S]) row[t / S] = dot;
       }
     }

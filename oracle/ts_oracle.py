@@ -43,6 +43,28 @@ def _load():
     return _lib
 
 
+import contextlib
+
+
+@contextlib.contextmanager
+def element_format(fmt: str):
+    """fmt = "bf16" (default) or "fp16": how the 16-bit inputs of the functions of the
+    paper's path are decoded inside the block."""
+    assert fmt in ("bf16", "fp16")
+    _load().tso_set_element_format(1 if fmt == "fp16" else 0)
+    try:
+        yield
+    finally:
+        _load().tso_set_element_format(0)
+
+
+def decode_elements(bits):
+    bits = _u16(bits)
+    out = np.empty(bits.shape, dtype=np.float64)
+    _load().tso_decode_elements(_p(bits), bits.size, _p(out))
+    return out
+
+
 def max_threads() -> int:
     return int(_load().tso_max_threads())
 

@@ -364,6 +364,58 @@ def test_always_kept_pages(oracle, seed):
 
 
 # ----------------------------------------------------------------------------
+# IEEE half inputs (the paper's experiments run in FP16)
+# ----------------------------------------------------------------------------
+def test_fp16_decoder_against_numpy(oracle):
+    """Every one of the 65536 bit patterns decodes as numpy's float16 does."""
+    bits = np.arange(65536, dtype=np.uint16)
+    with oracle.element_format("fp16"):
+        got = oracle.decode_elements(bits)
+    ref = bits.view(np.float16).astype(np.float64)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))
+    # and the default is untouched afterwards
+    assert oracle.decode_elements(bf16_bits([1.5, -2.0])).tolist() == [1.5, -2.0]
+
+
+def test_fp16_all_pages_equals_dense_library(oracle):
+    """The whole step in fp16 mode: metadata, Eq. 2 against a direct evaluation, and
+    K = P against torch's attention on the same half-precision values."""
+    rng = np.random.default_rng(21)
+    B, Hq, Hkv, d, S = 2, 4, 2, 16, 8
+    lens = np.array([37, 24], dtype=np.int32)
+    Lmax, Pmax = 40, 5
+
+    def h16(x):
+        return np.asarray(x, dtype=np.float16).view(np.uint16)
+
+    K, V = h16(rng.standard_normal((B, Hkv, Lmax, d))), h16(rng.standard_normal((B, Hkv, Lmax, d)))
+    q = h16(rng.standard_normal((B, Hq, d)) * 0.5)
+    Kf, Vf, qf = (x.view(np.float16).astype(np.float64) for x in (K, V, q))
+    with oracle.element_format("fp16"):
+        pmin, pmax = oracle.build_page_meta(K, lens, S, Pmax)
+        r = oracle.query_aware_decode(q, K, V, pmin, pmax, lens, S, 99, Pmax, 0.25)
+    G = Hq // Hkv
+    for b in range(B):
+        L = int(lens[b])
+        for h in range(Hkv):
+            for j in range(-(-L // S)):
+                blk = Kf[b, h, j * S:min((j + 1) * S, L)]
+                assert np.array_equal(pmin[b, h, j].view(np.float16).astype(np.float64), blk.min(0))
+                assert np.array_equal(pmax[b, h, j].view(np.float16).astype(np.float64), blk.max(0))
+                want = sum(max(qf[b, g, c] * blk[:, c].min(), qf[b, g, c] * blk[:, c].max())
+                           for g in range(h * G, (h + 1) * G) for c in range(d))
+                assert r["scores"][b, h, j] == pytest.approx(want, rel=1e-13, abs=1e-13)
+        kk = torch.from_numpy(Kf[b, :, :L]).repeat_interleave(G, dim=0)
+        vv = torch.from_numpy(Vf[b, :, :L]).repeat_interleave(G, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qf[b])[:, None, :], kk, vv, scale=0.25)[:, 0]
+        np.testing.assert_allclose(r["out"][b], ref.numpy(), rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
 # INT8 KV cache (an extension; format in oracle/ts_oracle.c)
 # ----------------------------------------------------------------------------
 def test_i8_quantisation_hand_worked(oracle):
