@@ -52,7 +52,8 @@ class Layer:
     def __init__(self, ts, wl, spec, seed, dev, n_q):
         import torch
         self.w = w = wl.make_workload(spec, dev, seed=seed, n_q=n_q, n_new=1, poison=0.0)
-        self.page_min = torch.zeros((spec.B, spec.Hkv, w.P_max, spec.d), dtype=torch.bfloat16,
+        self.page_min = torch.zeros((spec.B, spec.Hkv, w.P_max, spec.d),
+                                    dtype=torch.float16 if spec.kv == "fp16" else torch.bfloat16,
                                     device=dev)
         self.page_max = torch.zeros_like(self.page_min)
         self.seq_lens = w.seq_lens.clone()
@@ -162,8 +163,9 @@ def cpu_baseline(spec, layer, wl, budget_s=20.0):
         Kb, Vb = wl.bits(K), wl.bits(V)
 
         def step():
-            oracle.query_aware_decode(qb, Kb, Vb, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
-                                      topk_per_seq=tps)
+            with oracle.element_format(spec.kv):
+                oracle.query_aware_decode(qb, Kb, Vb, pmin, pmax, L, spec.S, w.topk, w.K_max, scale,
+                                          topk_per_seq=tps)
     times = []
     t_start = time.perf_counter()
     while True:
@@ -195,8 +197,9 @@ def main():
     ap.add_argument("--step", default="one_launch", choices=["one_launch", "separate"],
                     help="one_launch: ts_append_and_decode; separate: ts_append_token_meta + "
                          "ts_query_aware_decode")
-    ap.add_argument("--kv-format", default="bf16", choices=["bf16", "int8"],
-                    help="format of the KV pool (int8: codes + one fp32 scale per token and head)")
+    ap.add_argument("--kv-format", default="bf16", choices=["bf16", "fp16", "int8"],
+                    help="format of the cache (fp16: every 16-bit tensor IEEE half; int8: codes + "
+                         "one fp32 scale per token and head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip timing the dense (whole-cache) attention beside the step")
@@ -423,13 +426,14 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if args.kv_format == "bf16" else "int8 KV expanded to bf16 for the MFMA",
+        "dtype": {"bf16": "bf16", "fp16": "fp16",
+                  "int8": "int8 KV expanded to bf16 for the MFMA"}[args.kv_format],
         "data": "synthetic",
         "effective_GBps": round(by["total"] / (us_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100.0 * by["total"] / (us_step * 1e-6) / HBM_PEAK, 2),
         "config": {
-            "workload": WORKLOAD_DESC[args.workload] + ("" if args.kv_format == "bf16"
-                                                          else ", INT8 KV pool"),
+            "workload": WORKLOAD_DESC[args.workload] + {"bf16": "", "fp16": ", FP16 tensors",
+                                                          "int8": ", INT8 KV pool"}[args.kv_format],
             "step": ("ts_append_and_decode (append + score + select + attend in one launch), one layer"
                      if single_kernel else
                      "ts_append_and_decode (large batch: append kernel + fused decode kernel), one layer"

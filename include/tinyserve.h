@@ -48,7 +48,7 @@ extern "C" {
 #define TS_MAX_PAGES_PER_SEQ 16384
 
 enum { TS_OUT_F32 = 0, TS_OUT_BF16 = 1 };
-enum { TS_KV_BF16 = 0, TS_KV_INT8 = 1 };
+enum { TS_KV_BF16 = 0, TS_KV_INT8 = 1, TS_KV_FP16 = 2 };
 
 typedef enum ts_status {
   TS_OK = 0,
@@ -105,7 +105,10 @@ typedef struct ts_layout {
    * default) fp32 [B][Hq][d]; TS_OUT_BF16: the same values rounded to bf16
    * (nearest even), `out` then points to 16-bit elements. */
   int32_t out_format;
-  /* Format of the KV pool: TS_KV_BF16 (0, the default) as described above, or
+  /* Format of the KV pool: TS_KV_BF16 (0, the default) as described above;
+   * TS_KV_FP16: every 16-bit tensor of the interface (k_pool, v_pool, page_min,
+   * page_max, q, k_new, v_new) holds IEEE half instead of bf16 (the paper's
+   * experiments run in FP16), nothing else changes; or
    * TS_KV_INT8 (Section 3.1 names INT8 KV support and gives no format; this one
    * is this library's):
    *   k_pool int8 [num_phys_pages][Hkv][S][d], v_pool int8 [num_phys_pages][Hkv][d][S]

@@ -138,16 +138,16 @@ __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) /
 // Staged kernels
 // ---------------------------------------------------------------------------
 // grid (gx, units): workgroup x scores every gx-th group of pages of its unit.
-template <int D>
+template <int D, bool kHalf>
 __global__ __launch_bounds__(kThreads) void score_pages_kernel(const uint16_t* q,
                                                                const uint16_t* page_min,
                                                                const uint16_t* page_max,
                                                                const int32_t* seq_lens, float* scores,
                                                                int Hq, int Hkv, int S, int Pmax) {
-  __shared__ __align__(16) unsigned char q_stage[ScoreLanes<D>::query_stage_bytes(16)];
+  __shared__ __align__(16) unsigned char q_stage[ScoreLanes<D, kHalf>::query_stage_bytes(16)];
   const int u = blockIdx.y, b = u / Hkv, h = u % Hkv, G = Hq / Hkv;
   float* srow = scores + (size_t)u * Pmax;
-  score_pages_waves<D>(
+  score_pages_waves<D, kHalf>(
       page_min + (size_t)u * Pmax * D, page_max + (size_t)u * Pmax * D,
       q + ((size_t)b * Hq + (size_t)h * G) * D, G, Pmax, blockIdx.x * kWaves + wave_id(),
       gridDim.x * kWaves, q_stage, [] {}, [&] { return min(pages_of(seq_lens[b], S), Pmax); },
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
 
 // grid (g, units).  The last workgroup of a unit to deposit its partial merges
 // them (unit_done counts arrivals and is left at zero again).
-template <int D, int S, bool kInt8>
+template <int D, int S, bool kInt8, bool kHalf>
 __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams p,
                                                                     const int32_t* sel,
                                                                     const int32_t* sel_count,
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
   const int32_t* sel_row = sel ? sel + (size_t)u * p.Kmax + c0 : nullptr;
   const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
   const NewToken none{-1, 0, p.q, p.q};
-  attend_split<D, S, true, false, kInt8>(
+  attend_split<D, S, true, false, kInt8, kHalf>(
       p, b, h, split, count, p.seq_lens[b], none,
       [&](int i) { return sel_row ? sel_row[i] : c0 + i; },
       [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 //
 // kApp = true is the build that first appends one token per sequence
 // (ts_append_and_decode); the plain build carries none of its registers.
-template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false>
+template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false, bool kHalf = false>
 __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParams p) {
   static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
   static_assert(!(kInt8 && kApp), "the INT8 cache is appended to by a kernel of its own");
@@ -304,19 +304,19 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
   // end of the unit before.  What they fetch is only looked at inside the loop.
   constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
   int L_raw, K_raw, epoch_raw, bt_regs[kBtRegs];
-  ScanRegs<D> scan;
+  ScanRegs<D, kHalf> scan;
   // Append mode: the new token's key / value rows of this unit, as the 16-byte
   // chunk (channels 8 * (lane % (D/8)) .. + 7) every lane needs for the box update
   // and the pool write.
   constexpr bool app = kApp;
-  constexpr int LPR = ScoreLanes<D>::LPR;
+  constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
   uint4 kn16 = make_uint4(0, 0, 0, 0), vn16 = make_uint4(0, 0, 0, 0);
   auto issue_unit = [&](int uu) {
     const int b = uu / at.Hkv, h = uu % at.Hkv;
     epoch_raw = p.ctrl[kCtrlEpoch];
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
-    scan_issue_query<D>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
+    scan_issue_query<D, kHalf>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
     if (app) {  // behind the query (needed first), ahead of the metadata (needed with it)
       const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
       kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 #pragma unroll
     for (int k = 0; k < kBtRegs; ++k)   // no branch around the loads
       bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
-    scan_issue_tile<D>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
+    scan_issue_tile<D, kHalf>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
                        Pmax, member * kWaves + wave_id());
   };
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
-    scan_finish<D, !kLoop>(
+    scan_finish<D, !kLoop, kHalf>(
         scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
         member * kWaves + wave_id(), g * kWaves, q_stage,
         [&] {
@@ -386,8 +386,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           // the wave: all the others jump over the block instead of executing
           // it with every lane masked off)
           if (__ballot(pg == j_new) != 0ull && pg == j_new) {
-            mn = slot_new == 0 ? kn16 : widen_box(mn, kn16, true);
-            mx = slot_new == 0 ? kn16 : widen_box(mx, kn16, false);
+            mn = slot_new == 0 ? kn16 : widen_box<kHalf>(mn, kn16, true);
+            mx = slot_new == 0 ? kn16 : widen_box<kHalf>(mx, kn16, false);
             const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
             *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_min) + row) = mn;
             *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_max) + row) = mx;
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     const size_t new_row = ((size_t)b * at.Hkv + h) * D;
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
-    attend_split<D, S, !kLoop, kApp, kInt8>(
+    attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
     TS_MARK(6);
@@ -586,7 +586,8 @@ static int check_layout(const ts_layout* L) {
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
   if (L->keep_first_pages < 0 || L->keep_last_pages < 0) return TS_ERR_SHAPE;
   if (L->out_format != TS_OUT_F32 && L->out_format != TS_OUT_BF16) return TS_ERR_UNSUPPORTED;
-  if (L->kv_format != TS_KV_BF16 && L->kv_format != TS_KV_INT8) return TS_ERR_UNSUPPORTED;
+  if (L->kv_format != TS_KV_BF16 && L->kv_format != TS_KV_INT8 && L->kv_format != TS_KV_FP16)
+    return TS_ERR_UNSUPPORTED;
   if (L->kv_format == TS_KV_INT8 && L->kv_tile_stride % 16 != 0) return TS_ERR_SHAPE;
   return TS_OK;
 }
@@ -713,14 +714,15 @@ using namespace ts;
 // it, and against hundreds of microseconds the extra launch does not count.
 // The INT8 cache is always appended to by its own kernel.
 // max_resident: workgroups the launch may count on being resident together.
-template <int D, int S, bool kInt8>
+template <int D, int S, int kFmt>
 static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Plan& pl,
                               const void* k_new, const void* v_new, int max_resident,
                               void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8>;
-  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8>;
-  auto app_kernel = query_aware_decode_kernel<D, S, false, !kInt8, kInt8>;   // == one_kernel for INT8
+  constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
+  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8, kHalf>;
+  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8, kHalf>;
+  auto app_kernel = query_aware_decode_kernel<D, S, false, !kInt8, kInt8, kHalf>;   // == one_kernel for INT8
   int st;
   if ((st = allow_lds(loop_kernel, pl.lds_fused)) != TS_OK ||
       (st = allow_lds(one_kernel, pl.lds_fused)) != TS_OK ||
@@ -791,10 +793,15 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   const int D = layout->head_dim, S = layout->page_size;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
   st = TS_ERR_UNSUPPORTED;
-#define TS_LAUNCH_FUSED(DD, SS)                                                                 \
-  st = layout->kv_format == TS_KV_INT8                                                          \
-           ? launch_fused_shape<DD, SS, true>(layout, p, pl, k_new, v_new, cus * per_cu, stream) \
-           : launch_fused_shape<DD, SS, false>(layout, p, pl, k_new, v_new, cus * per_cu, stream)
+#define TS_LAUNCH_FUSED(DD, SS)                                                                  \
+  st = layout->kv_format == TS_KV_INT8                                                           \
+           ? launch_fused_shape<DD, SS, TS_KV_INT8>(layout, p, pl, k_new, v_new, cus * per_cu,   \
+                                                    stream)                                      \
+       : layout->kv_format == TS_KV_FP16                                                         \
+           ? launch_fused_shape<DD, SS, TS_KV_FP16>(layout, p, pl, k_new, v_new, cus * per_cu,   \
+                                                    stream)                                      \
+           : launch_fused_shape<DD, SS, TS_KV_BF16>(layout, p, pl, k_new, v_new, cus * per_cu,   \
+                                                    stream)
   TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_FUSED);
 #undef TS_LAUNCH_FUSED
   if (st != TS_OK) return st;
@@ -879,10 +886,15 @@ int ts_build_page_meta(const ts_layout* layout, void* stream) {
     return launch_status();
   }
   dim3 grid((p.Pmax + kWaves - 1) / kWaves, p.Hkv, p.B);
-  if (layout->head_dim == 64)
-    build_page_meta_kernel<64><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
+  const bool half = layout->kv_format == TS_KV_FP16;
+  if (layout->head_dim == 64 && !half)
+    build_page_meta_kernel<64, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
+  else if (layout->head_dim == 64)
+    build_page_meta_kernel<64, true><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
+  else if (!half)
+    build_page_meta_kernel<128, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
   else
-    build_page_meta_kernel<128><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
+    build_page_meta_kernel<128, true><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
   return launch_status();
 }
 
@@ -902,7 +914,7 @@ int ts_append_token_meta(const ts_layout* layout, const void* k_new, const void*
   }
   append_token_meta_kernel<<<p.B, kThreads, 0, (hipStream_t)stream>>>(
       p, layout->head_dim, static_cast<const uint16_t*>(k_new),
-      static_cast<const uint16_t*>(v_new), advance_seq_lens);
+      static_cast<const uint16_t*>(v_new), advance_seq_lens, layout->kv_format == TS_KV_FP16);
   return launch_status();
 }
 
@@ -921,14 +933,16 @@ int ts_score_pages(const ts_layout* layout, const void* q, float* scores, void* 
   dim3 grid(gx, units);
   const uint16_t* pmin = static_cast<const uint16_t*>(layout->page_min);
   const uint16_t* pmax = static_cast<const uint16_t*>(layout->page_max);
-  if (layout->head_dim == 64)
-    score_pages_kernel<64><<<grid, kThreads, 0, (hipStream_t)stream>>>(
-        static_cast<const uint16_t*>(q), pmin, pmax, layout->seq_lens, scores, layout->num_q_heads,
-        layout->num_kv_heads, layout->page_size, Pmax);
-  else
-    score_pages_kernel<128><<<grid, kThreads, 0, (hipStream_t)stream>>>(
-        static_cast<const uint16_t*>(q), pmin, pmax, layout->seq_lens, scores, layout->num_q_heads,
-        layout->num_kv_heads, layout->page_size, Pmax);
+  const bool half = layout->kv_format == TS_KV_FP16;
+#define TS_LAUNCH_SCORE(DD, HH)                                                                   \
+  score_pages_kernel<DD, HH><<<grid, kThreads, 0, (hipStream_t)stream>>>(                          \
+      static_cast<const uint16_t*>(q), pmin, pmax, layout->seq_lens, scores, layout->num_q_heads, \
+      layout->num_kv_heads, layout->page_size, Pmax)
+  if (layout->head_dim == 64 && !half) TS_LAUNCH_SCORE(64, false);
+  else if (layout->head_dim == 64) TS_LAUNCH_SCORE(64, true);
+  else if (!half) TS_LAUNCH_SCORE(128, false);
+  else TS_LAUNCH_SCORE(128, true);
+#undef TS_LAUNCH_SCORE
   return launch_status();
 }
 
@@ -964,10 +978,13 @@ static int launch_attention(const ts_layout* layout, const Plan& pl, const void*
 #define TS_LAUNCH_ATTENTION(DD, SS)                                                               \
   do {                                                                                            \
     if (layout->kv_format == TS_KV_INT8)                                                          \
-      sparse_attention_kernel<DD, SS, true>                                                       \
+      sparse_attention_kernel<DD, SS, true, false>                                                \
+          <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride);                 \
+    else if (layout->kv_format == TS_KV_FP16)                                                     \
+      sparse_attention_kernel<DD, SS, false, true>                                                \
           <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride);                 \
     else                                                                                          \
-      sparse_attention_kernel<DD, SS, false>                                                      \
+      sparse_attention_kernel<DD, SS, false, false>                                               \
           <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride);                 \
   } while (0)
   TS_DISPATCH_SHAPE(D, S, TS_LAUNCH_ATTENTION);
@@ -1020,8 +1037,11 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
   const int D = layout->head_dim, S = layout->page_size;
   int cap1 = 0;
-#define TS_CAPACITY(DD, SS) \
-  cap1 = resident_capacity(query_aware_decode_kernel<DD, SS, false, true>, pl.lds_fused)
+#define TS_CAPACITY(DD, SS)                                                                      \
+  cap1 = layout->kv_format == TS_KV_FP16                                                         \
+             ? resident_capacity(query_aware_decode_kernel<DD, SS, false, true, false, true>,    \
+                                 pl.lds_fused)                                                   \
+             : resident_capacity(query_aware_decode_kernel<DD, SS, false, true>, pl.lds_fused)
   TS_DISPATCH_SHAPE(D, S, TS_CAPACITY);
 #undef TS_CAPACITY
   if (cap1 <= 0) return TS_ERR_DEVICE;

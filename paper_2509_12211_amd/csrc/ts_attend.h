@@ -32,8 +32,40 @@ __device__ __forceinline__ short4_t as_short4(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(short4_t, w);
 }
 
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
+// 16x16x16 product of 16-bit operands (bf16, or IEEE half for the FP16 cache), fp32 accumulate.
+template <bool kHalf = false>
 __device__ __forceinline__ float4_t mfma16(short4_t a, short4_t b, float4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+  if constexpr (kHalf)
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a),
+                                                 __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+}
+
+// Four softmax weights as two 16-bit operand sets whose sum carries ~16 (bf16) or
+// ~21 (half) significant bits of each weight: a truncated high part and the remainder.
+template <bool kHalf>
+__device__ __forceinline__ void split_weights(const float (&pv)[4], short4_t& ph, short4_t& pl) {
+  if constexpr (kHalf) {
+    typedef __fp16 h2_t __attribute__((ext_vector_type(2)));
+    const h2_t h01 = __builtin_amdgcn_cvt_pkrtz(pv[0], pv[1]);
+    const h2_t h23 = __builtin_amdgcn_cvt_pkrtz(pv[2], pv[3]);
+    const h2_t l01 = __builtin_amdgcn_cvt_pkrtz(pv[0] - (float)h01[0], pv[1] - (float)h01[1]);
+    const h2_t l23 = __builtin_amdgcn_cvt_pkrtz(pv[2] - (float)h23[0], pv[3] - (float)h23[1]);
+    ph = as_short4(__builtin_bit_cast(uint32_t, h01), __builtin_bit_cast(uint32_t, h23));
+    pl = as_short4(__builtin_bit_cast(uint32_t, l01), __builtin_bit_cast(uint32_t, l23));
+  } else {
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      hi[v] = __float_as_uint(pv[v]) & 0xffff0000u;
+      lo[v] = __float_as_uint(pv[v] - __uint_as_float(hi[v]));
+    }
+    ph = as_short4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+    pl = as_short4((lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u));
+  }
 }
 
 struct AttendParams {
@@ -355,7 +387,7 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
 // kScaled (INT8 cache): ks[t] / vs[t] hold the scales of this lane's four tokens of
 // tile t; a logit is multiplied by its token's key scale, and a softmax weight by
 // its token's value scale on its way into the P.V product (not in the running sum).
-template <int D, int F, bool kScaled = false>
+template <int D, int F, bool kScaled = false, bool kHalf = false>
 __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short4_t (&qf)[D / 16],
                                             uint32_t vmask, float scale_log2, WaveAcc<D>& a,
                                             const float4* ks = nullptr, const float4* vs = nullptr) {
@@ -368,8 +400,8 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
     sc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < D / 32; ++i) {
-      sc[t] = mfma16(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
-      sc[t] = mfma16(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
+      sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
+      sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
     }
     const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
     float kst[4] = {1.f, 1.f, 1.f, 1.f};
@@ -394,22 +426,20 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   for (int t = 0; t < NT; ++t) {
     // softmax weights split into two bf16 terms (truncated high part + remainder)
     // so the P.V product keeps ~16 significant bits of each weight
-    uint32_t hi[4], lo[4];
     const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);
     float vst[4] = {1.f, 1.f, 1.f, 1.f};
     if (kScaled) { vst[0] = vs[t].x; vst[1] = vs[t].y; vst[2] = vs[t].z; vst[3] = vs[t].w; }
+    float pw[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       float pv = __builtin_amdgcn_exp2f(sc[t][v] - m_new);
       a.l += pv;
       // (a slot without a token may hold any scale: its weight is zero, keep it zero)
       if (kScaled) pv = (mine >> v) & 1u ? pv * vst[v] : 0.f;
-      hi[v] = __float_as_uint(pv) & 0xffff0000u;
-      lo[v] = __float_as_uint(pv - __uint_as_float(hi[v]));
+      pw[v] = pv;
     }
-    const short4_t ph = as_short4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
-    const short4_t pl = as_short4((lo[0] >> 16) | (lo[1] & 0xffff0000u),
-                                  (lo[2] >> 16) | (lo[3] & 0xffff0000u));
+    short4_t ph, pl;
+    split_weights<kHalf>(pw, ph, pl);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       uint32_t v0 = f.v[t][cb].x, v1 = f.v[t][cb].y;
@@ -420,8 +450,8 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
         if (!(mine & 8u)) v1 &= 0x0000ffffu;
       }
       const short4_t vf = as_short4(v0, v1);
-      a.o[cb] = mfma16(vf, ph, a.o[cb]);
-      a.o[cb] = mfma16(vf, pl, a.o[cb]);
+      a.o[cb] = mfma16<kHalf>(vf, ph, a.o[cb]);
+      a.o[cb] = mfma16<kHalf>(vf, pl, a.o[cb]);
     }
   }
 }
@@ -440,13 +470,16 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 // which suits bandwidth-bound launches with thousands of units.
 // kPatch: a token appended in the same launch may have to be spliced in (nt).
 // kInt8: the cache holds int8 keys / values with per-token scales.
-template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, typename SelAt, typename PhysAt>
+// kHalf: queries, keys and values are IEEE half instead of bf16.
+template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, bool kHalf, typename SelAt,
+          typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
                                              PhysAt phys_at, float* lds) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
   static_assert(!(kPatch && kInt8), "no in-register append for the INT8 cache");
+  static_assert(!(kHalf && kInt8), "the INT8 cache goes with bf16 queries");
   using Frag = std::conditional_t<kInt8, PageFrag8<D, F>, PageFrag<D, F>>;
   const uint8_t* k_pool8 = reinterpret_cast<const uint8_t*>(p.k_pool);
   const uint8_t* v_pool8 = reinterpret_cast<const uint8_t*>(p.v_pool);
@@ -558,7 +591,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
             attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs);
           } else {
             if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
-            attend_page<D, F>(f[i], qf, vmask[i], p.scale_log2, acc);
+            attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
           }
         }
         if (kBranchless || x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);

@@ -26,6 +26,33 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rn(float f) {
   if ((b & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((b >> 16) | 0x0040u);
   return (uint16_t)((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
 }
+// The same for IEEE half (the FP16 cache format).
+__device__ __forceinline__ float half_to_f32(uint16_t x) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, x));
+}
+__device__ __forceinline__ uint16_t f32_to_half(float f) {   // exact for values that are halves
+  return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+// 16-bit element -> fp32 in either format
+template <bool kHalf>
+__device__ __forceinline__ float elem_to_f32(uint16_t x) {
+  return kHalf ? half_to_f32(x) : bf16_to_f32(x);
+}
+template <bool kHalf>
+__device__ __forceinline__ float elem_lo(uint32_t w) {
+  return kHalf ? half_to_f32(static_cast<uint16_t>(w)) : bf16_lo(w);
+}
+template <bool kHalf>
+__device__ __forceinline__ float elem_hi(uint32_t w) {
+  return kHalf ? half_to_f32(static_cast<uint16_t>(w >> 16)) : bf16_hi(w);
+}
+template <bool kHalf>
+__device__ __forceinline__ void unpack8e(const uint4& w, float (&f)[8]) {
+  f[0] = elem_lo<kHalf>(w.x); f[1] = elem_hi<kHalf>(w.x);
+  f[2] = elem_lo<kHalf>(w.y); f[3] = elem_hi<kHalf>(w.y);
+  f[4] = elem_lo<kHalf>(w.z); f[5] = elem_hi<kHalf>(w.z);
+  f[6] = elem_lo<kHalf>(w.w); f[7] = elem_hi<kHalf>(w.w);
+}
 __device__ __forceinline__ void unpack8(const uint4& w, float (&f)[8]) {
   f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
   f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);

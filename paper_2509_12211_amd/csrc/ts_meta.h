@@ -21,7 +21,7 @@ struct MetaParams {
 // bf16 tile is contiguous, so the wave reads it as 16-byte chunks (lane ->
 // token lane / (D/8), channels 8 * (lane % (D/8)) ..+7), takes the channel-wise
 // min / max over its tokens, then folds the lanes that share a channel group.
-template <int D>
+template <int D, bool kHalf>
 __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p) {
   constexpr int LPR = D / 8;        // lanes per token row
   constexpr int TPW = kWave / LPR;  // token rows per wave-wide load
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
   for (int t = lane / LPR; t < valid; t += TPW) {
     const uint4 w = *reinterpret_cast<const uint4*>(tile + (size_t)t * D + cg * 8);
     float f[8];
-    unpack8(w, f);
+    unpack8e<kHalf>(w, f);
 #pragma unroll
     for (int i = 0; i < 8; ++i) { lo[i] = fminf(lo[i], f[i]); hi[i] = fmaxf(hi[i], f[i]); }
   }
@@ -56,15 +56,16 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
   }
   if (lane < LPR) {
     const size_t row = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + cg * 8;
-    uint4 a, c;
-    a.x = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xffff0000u);
-    a.y = (__float_as_uint(lo[2]) >> 16) | (__float_as_uint(lo[3]) & 0xffff0000u);
-    a.z = (__float_as_uint(lo[4]) >> 16) | (__float_as_uint(lo[5]) & 0xffff0000u);
-    a.w = (__float_as_uint(lo[6]) >> 16) | (__float_as_uint(lo[7]) & 0xffff0000u);
-    c.x = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xffff0000u);
-    c.y = (__float_as_uint(hi[2]) >> 16) | (__float_as_uint(hi[3]) & 0xffff0000u);
-    c.z = (__float_as_uint(hi[4]) >> 16) | (__float_as_uint(hi[5]) & 0xffff0000u);
-    c.w = (__float_as_uint(hi[6]) >> 16) | (__float_as_uint(hi[7]) & 0xffff0000u);
+    // back to 16-bit elements: the values are elements of the cache, so this is exact
+    // (bf16: the upper half of the fp32 pattern)
+    auto pack = [](float x, float y) -> uint32_t {
+      if (kHalf) return (uint32_t)f32_to_half(x) | ((uint32_t)f32_to_half(y) << 16);
+      return (__float_as_uint(x) >> 16) | (__float_as_uint(y) & 0xffff0000u);
+    };
+    const uint4 a = make_uint4(pack(lo[0], lo[1]), pack(lo[2], lo[3]), pack(lo[4], lo[5]),
+                               pack(lo[6], lo[7]));
+    const uint4 c = make_uint4(pack(hi[0], hi[1]), pack(hi[2], hi[3]), pack(hi[4], hi[5]),
+                               pack(hi[6], hi[7]));
     *reinterpret_cast<uint4*>(p.page_min + row) = a;
     *reinterpret_cast<uint4*>(p.page_max + row) = c;
   }
@@ -72,14 +73,17 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p)
 
 // Element-wise box update of eight packed bf16: lo = k where k < lo, hi = k
 // where k > hi (strict, as the stand-alone append kernel does it).
+template <bool kHalf = false>
 __device__ __forceinline__ uint32_t widen_pair(uint32_t box, uint32_t k, bool is_min) {
-  const float bl = bf16_lo(box), bh = bf16_hi(box), kl = bf16_lo(k), kh = bf16_hi(k);
+  const float bl = elem_lo<kHalf>(box), bh = elem_hi<kHalf>(box), kl = elem_lo<kHalf>(k),
+              kh = elem_hi<kHalf>(k);
   const bool tl = is_min ? kl < bl : kl > bl, th = is_min ? kh < bh : kh > bh;
   return ((tl ? k : box) & 0x0000ffffu) | ((th ? k : box) & 0xffff0000u);
 }
+template <bool kHalf = false>
 __device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, bool is_min) {
-  return make_uint4(widen_pair(box.x, k.x, is_min), widen_pair(box.y, k.y, is_min),
-                    widen_pair(box.z, k.z, is_min), widen_pair(box.w, k.w, is_min));
+  return make_uint4(widen_pair<kHalf>(box.x, k.x, is_min), widen_pair<kHalf>(box.y, k.y, is_min),
+                    widen_pair<kHalf>(box.z, k.z, is_min), widen_pair<kHalf>(box.w, k.w, is_min));
 }
 
 // One workgroup per sequence.  A thread takes eight channels of one KV head at a
@@ -90,10 +94,11 @@ __device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, boo
 // the token's values (which do not depend on the length) go out together with
 // the length, then the block-table entry and the old box together.  All threads
 // read seq_lens[b] before the barrier; thread 0 advances it after.
+// half: the cache holds IEEE half (the comparison is the only thing that differs).
 __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams p, int D,
                                                                       const uint16_t* k_new,
                                                                       const uint16_t* v_new,
-                                                                      int advance) {
+                                                                      int advance, int half) {
   const int b = blockIdx.x, n8 = p.Hkv * D / 8, cpr = D / 8;   // chunks, chunks per head row
   const uint4* k_src = reinterpret_cast<const uint4*>(k_new + (size_t)b * p.Hkv * D);
   const uint4* v_src = reinterpret_cast<const uint4*>((v_new ? v_new : k_new) + (size_t)b * p.Hkv * D);
@@ -114,8 +119,10 @@ __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams 
     const uint4 vn = i0 == (int)threadIdx.x ? v0 : v_src[i0];
     const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
     if (ok) {
-      *reinterpret_cast<uint4*>(p.page_min + m) = slot == 0 ? kn : widen_box(lo, kn, true);
-      *reinterpret_cast<uint4*>(p.page_max + m) = slot == 0 ? kn : widen_box(hi, kn, false);
+      const uint4 wlo = half ? widen_box<true>(lo, kn, true) : widen_box<false>(lo, kn, true);
+      const uint4 whi = half ? widen_box<true>(hi, kn, false) : widen_box<false>(hi, kn, false);
+      *reinterpret_cast<uint4*>(p.page_min + m) = slot == 0 ? kn : wlo;
+      *reinterpret_cast<uint4*>(p.page_max + m) = slot == 0 ? kn : whi;
       if (v_new != nullptr) {
         const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
         *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot * D + c8) = kn;

@@ -19,7 +19,7 @@ namespace ts {
 // Lane layout: a metadata row (D bf16) is read as D/8 chunks of 16 bytes, so
 // one wave-wide 16-byte load covers 64 / (D/8) consecutive pages; each lane
 // keeps Qp / Qn for its 8 channels.
-template <int D>
+template <int D, bool kHalf = false>
 struct ScoreLanes {
   static constexpr int LPR = D / 8;         // lanes per metadata row
   static constexpr int PPW = kWave / LPR;   // pages per wave-wide load
@@ -67,7 +67,7 @@ struct ScoreLanes {
       const uint16_t* col = reinterpret_cast<const uint16_t*>(stage) + threadIdx.x;
       double p = 0.0, n = 0.0;
       for (int g = 0; g < G; ++g) {
-        const float f = bf16_to_f32(col[g * D]);
+        const float f = elem_to_f32<kHalf>(col[g * D]);
         p += static_cast<double>(fmaxf(f, 0.f));
         n += static_cast<double>(fminf(f, 0.f));
       }
@@ -82,8 +82,8 @@ struct ScoreLanes {
 
   __device__ __forceinline__ double row_partial(const uint4& mn, const uint4& mx) const {
     float lo[8], hi[8];
-    unpack8(mn, lo);
-    unpack8(mx, hi);
+    unpack8e<kHalf>(mn, lo);
+    unpack8e<kHalf>(mx, hi);
     double s = 0.0;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -95,16 +95,16 @@ struct ScoreLanes {
 // The metadata rows one wave has in flight: U wave-wide loads of min and of max
 // covering pages [base, base + PPI).  Rows up to Pmax are always readable
 // (whatever they hold), so the loads do not wait for the sequence length.
-template <int D>
+template <int D, bool kHalf = false>
 struct MetaTile {
-  static constexpr int U = ScoreLanes<D>::U;
+  static constexpr int U = ScoreLanes<D, kHalf>::U;
   uint4 mn[U], mx[U];
 
   // Plimit >= 1.  Pages at or past Plimit read row Plimit - 1 instead (no branch
   // around the loads); reduce() never reports them.
   __device__ __forceinline__ void load(const uint16_t* pmin_u, const uint16_t* pmax_u, int base,
                                        int Plimit) {
-    constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
+    constexpr int LPR = ScoreLanes<D, kHalf>::LPR, PPW = ScoreLanes<D, kHalf>::PPW;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -118,9 +118,9 @@ struct MetaTile {
   // get -inf.  patch(min_row, max_row, page) may first amend the row chunks this
   // lane holds (a token appended in the same launch).
   template <typename Patch, typename Sink>
-  __device__ __forceinline__ void reduce(const ScoreLanes<D>& ql, int base, int Pb, int Pmax,
+  __device__ __forceinline__ void reduce(const ScoreLanes<D, kHalf>& ql, int base, int Pb, int Pmax,
                                          Patch patch, Sink sink) {
-    constexpr int LPR = ScoreLanes<D>::LPR, PPW = ScoreLanes<D>::PPW;
+    constexpr int LPR = ScoreLanes<D, kHalf>::LPR, PPW = ScoreLanes<D, kHalf>::PPW;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -136,22 +136,22 @@ struct MetaTile {
 // first loads of a unit as early as it likes (before unrelated set-up work):
 // scan_issue sends out the query rows and the wave's first metadata tile,
 // scan_finish does everything else.  A wave's iterations are it = first_iter,
-// first_iter + iter_stride, ..., each covering ScoreLanes<D>::PPI consecutive
+// first_iter + iter_stride, ..., each covering ScoreLanes<D, kHalf>::PPI consecutive
 // pages.
-template <int D>
+template <int D, bool kHalf = false>
 struct ScanRegs {
-  typename ScoreLanes<D>::QueryRegs q;
-  MetaTile<D> tile;
+  typename ScoreLanes<D, kHalf>::QueryRegs q;
+  MetaTile<D, kHalf> tile;
 };
 
-template <int D>
-__device__ __forceinline__ void scan_issue_query(ScanRegs<D>& r, const uint16_t* q_group, int G) {
-  ScoreLanes<D>::issue_query(r.q, q_group, G);
+template <int D, bool kHalf>
+__device__ __forceinline__ void scan_issue_query(ScanRegs<D, kHalf>& r, const uint16_t* q_group, int G) {
+  ScoreLanes<D, kHalf>::issue_query(r.q, q_group, G);
 }
-template <int D>
-__device__ __forceinline__ void scan_issue_tile(ScanRegs<D>& r, const uint16_t* pmin_u,
+template <int D, bool kHalf>
+__device__ __forceinline__ void scan_issue_tile(ScanRegs<D, kHalf>& r, const uint16_t* pmin_u,
                                                 const uint16_t* pmax_u, int Pmax, int first_iter) {
-  r.tile.load(pmin_u, pmax_u, first_iter * ScoreLanes<D>::PPI, Pmax);
+  r.tile.load(pmin_u, pmax_u, first_iter * ScoreLanes<D, kHalf>::PPI, Pmax);
 }
 
 // `after_query` runs once the query is in registers and returns Pb.  Must be
@@ -164,14 +164,14 @@ __device__ __forceinline__ void scan_issue_tile(ScanRegs<D>& r, const uint16_t* 
 // of the current tile.  That is what a latency-bound launch wants; a launch with
 // thousands of units is bound by bandwidth and overlaps across workgroups, and
 // there the plain branch is a little cheaper.
-template <int D, bool kBranchless, typename AfterQuery, typename Patch, typename Sink>
-__device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin_u,
+template <int D, bool kBranchless, bool kHalf, typename AfterQuery, typename Patch, typename Sink>
+__device__ __forceinline__ void scan_finish(ScanRegs<D, kHalf>& r, const uint16_t* pmin_u,
                                             const uint16_t* pmax_u, int G, int Pmax, int first_iter,
                                             int iter_stride, unsigned char* q_stage,
                                             AfterQuery after_query, Patch patch, Sink sink) {
-  constexpr int PPI = ScoreLanes<D>::PPI;
+  constexpr int PPI = ScoreLanes<D, kHalf>::PPI;
   TS_MARK(19);
-  ScoreLanes<D> ql;
+  ScoreLanes<D, kHalf> ql;
   ql.finish_query(r.q, G, q_stage);
   TS_MARK(16);
   const int Pb = after_query();
@@ -180,7 +180,7 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin
   int base = first_iter * PPI;
   while (base < Pmax) {
     const int next = base + iter_stride * PPI;
-    MetaTile<D> cur = r.tile;
+    MetaTile<D, kHalf> cur = r.tile;
     if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
     else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb);
     cur.reduce(ql, base, Pb, Pmax, patch, sink);
@@ -191,17 +191,17 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D>& r, const uint16_t* pmin
 // Both halves back to back.  Loads go out in the order their data is needed:
 // the query rows, then whatever `issue_extra` loads, then the first metadata
 // tile; only then is anything waited for.
-template <int D, typename IssueExtra, typename AfterQuery, typename Sink>
+template <int D, bool kHalf, typename IssueExtra, typename AfterQuery, typename Sink>
 __device__ __forceinline__ void score_pages_waves(const uint16_t* pmin_u, const uint16_t* pmax_u,
                                                   const uint16_t* q_group, int G, int Pmax,
                                                   int first_iter, int iter_stride,
                                                   unsigned char* q_stage, IssueExtra issue_extra,
                                                   AfterQuery after_query, Sink sink) {
-  ScanRegs<D> r;
-  scan_issue_query<D>(r, q_group, G);
+  ScanRegs<D, kHalf> r;
+  scan_issue_query<D, kHalf>(r, q_group, G);
   issue_extra();
-  scan_issue_tile<D>(r, pmin_u, pmax_u, Pmax, first_iter);
-  scan_finish<D, true>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query,
+  scan_issue_tile<D, kHalf>(r, pmin_u, pmax_u, Pmax, first_iter);
+  scan_finish<D, true, kHalf>(r, pmin_u, pmax_u, G, Pmax, first_iter, iter_stride, q_stage, after_query,
                        [](uint4&, uint4&, int) {}, sink);
 }
 

@@ -26,6 +26,7 @@ TS_OUT_F32 = 0
 TS_OUT_BF16 = 1
 TS_KV_BF16 = 0
 TS_KV_INT8 = 1
+TS_KV_FP16 = 2
 
 EXPORTS = [
     "ts_build_page_meta", "ts_append_token_meta", "ts_score_pages", "ts_select_topk_pages",
@@ -114,7 +115,8 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                 page_max, keep_first_pages=0, keep_last_pages=0, out_format=TS_OUT_F32,
                 k_scale=None, v_scale=None) -> TsLayout:
     """Fill the C struct; tensors must stay alive while calls using it are in flight.
-    int8 pools (with k_scale / v_scale) select the INT8 cache format."""
+    int8 pools (with k_scale / v_scale) select the INT8 cache format, float16 pools the
+    FP16 one (q, new tokens and metadata must then be float16 too)."""
     n_phys = 0 if k_pool is None else k_pool.shape[0]
     tile_stride = 0
     if k_pool is not None and Hkv > 1:
@@ -132,7 +134,8 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                    None if page_min is None else page_min.data_ptr(),
                    None if page_max is None else page_max.data_ptr(),
                    int(keep_first_pages), int(keep_last_pages), int(out_format),
-                   TS_KV_INT8 if (k_pool is not None and k_pool.dtype == torch.int8) else TS_KV_BF16,
+                   (TS_KV_BF16 if k_pool is None else
+                    {torch.int8: TS_KV_INT8, torch.float16: TS_KV_FP16}.get(k_pool.dtype, TS_KV_BF16)),
                    None if k_scale is None else k_scale.data_ptr(),
                    None if v_scale is None else v_scale.data_ptr())
     return lay

@@ -41,7 +41,8 @@ class WorkloadSpec:
     L_min: int = 0             # ragged: lengths uniform in [L_min, L]; 0 = all equal L
     budget_frac: float = 0.0   # ragged: K_b = ceil(budget_frac * P_b)
     headroom: int = 64         # tokens of append room per sequence
-    kv: str = "bf16"           # "bf16" | "int8" (int8 codes + one fp32 scale per token and head)
+    kv: str = "bf16"           # "bf16" | "fp16" (every 16-bit tensor IEEE half) |
+                               # "int8" (int8 codes + one fp32 scale per token and head)
 
 
 SPECS = {
@@ -142,7 +143,8 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
         start += n
 
     int8 = spec.kv == "int8"
-    dt = torch.int8 if int8 else torch.bfloat16
+    e16 = torch.float16 if spec.kv == "fp16" else torch.bfloat16     # 16-bit element type
+    dt = torch.int8 if int8 else e16
     fill = -128 if int8 else poison          # code -128 is never generated
     if interleave:
         kv = torch.full((n_phys, Hkv, 2, S * d), fill, dtype=dt, device=device)
@@ -183,7 +185,7 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
             k_scale[phys] = ksp.view(Hkv, Pb, S).permute(1, 0, 2)
             v_scale[phys] = vsp.view(Hkv, Pb, S).permute(1, 0, 2)
         else:
-            k, v = k.to(torch.bfloat16), v.to(torch.bfloat16)
+            k, v = k.to(e16), v.to(e16)
         kp = torch.full((Hkv, Pb * S, d), fill, dtype=dt, device=device)
         vp = torch.full((Hkv, Pb * S, d), fill, dtype=dt, device=device)
         kp[:, :L] = k
@@ -192,13 +194,13 @@ def make_workload(spec: WorkloadSpec, device="cpu", seed=1000, n_q=1, n_new=1,
         v_pool[phys] = vp.view(Hkv, Pb, S, d).permute(1, 0, 3, 2)
         del k, v, kp, vp
     q = torch.randn((n_q, B, Hq, d), generator=g, device=device,
-                    dtype=torch.float32).to(torch.bfloat16)
+                    dtype=torch.float32).to(e16)
     k_new = torch.randn((n_new, B, Hkv, d), generator=g, device=device, dtype=torch.float32)
     if spec.keys == "offset":
         k_new += offset[None, None]
-    k_new = k_new.to(torch.bfloat16)
+    k_new = k_new.to(e16)
     v_new = torch.randn((n_new, B, Hkv, d), generator=g, device=device,
-                        dtype=torch.float32).to(torch.bfloat16)
+                        dtype=torch.float32).to(e16)
 
     seq_lens = lens.to(torch.int32).to(device)
     if spec.budget_frac > 0:
@@ -226,7 +228,7 @@ def logical_kv(w: Workload, seqs=None, heads=None, seq_lens=None):
     Lmax = max(int(lens[b]) for b in seqs)
     Lmax = max(Lmax, 1)
     hidx = torch.tensor(heads, dtype=torch.int64, device=w.device)
-    K = torch.zeros((len(seqs), len(heads), Lmax, d), dtype=torch.bfloat16, device=w.device)
+    K = torch.zeros((len(seqs), len(heads), Lmax, d), dtype=w.k_pool.dtype, device=w.device)
     V = torch.zeros_like(K)
     for i, b in enumerate(seqs):
         L = int(lens[b])
@@ -271,16 +273,15 @@ def logical_kv_i8(w: Workload, seqs=None, heads=None, seq_lens=None):
 
 
 def bits(t: torch.Tensor):
-    """bf16 tensor -> numpy uint16 bit patterns (host copy)."""
+    """bf16 (or float16) tensor -> numpy uint16 bit patterns (host copy)."""
     import numpy as np
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def from_bits(a, device="cpu") -> torch.Tensor:
-    """numpy uint16 bit patterns -> bf16 tensor."""
+def from_bits(a, device="cpu", dtype=torch.bfloat16) -> torch.Tensor:
+    """numpy uint16 bit patterns -> bf16 (or float16) tensor."""
     import numpy as np
-    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).copy()).view(
-        torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).copy()).view(dtype).to(device)
 
 
 def algorithmic_bytes(spec: WorkloadSpec, seq_lens, topk_per_seq=None) -> dict:
@@ -293,7 +294,7 @@ def algorithmic_bytes(spec: WorkloadSpec, seq_lens, topk_per_seq=None) -> dict:
         Kb = torch.minimum(topk_per_seq.to("cpu", torch.int64), P)
     else:
         Kb = torch.clamp(P, max=spec.topk)
-    tok = 2 * spec.d * 2 if spec.kv == "bf16" else 2 * spec.d + 8   # K + V (+ two scales) per token
+    tok = 2 * spec.d + 8 if spec.kv == "int8" else 2 * spec.d * 2   # K + V (+ two scales) per token
     meta = int(P.sum()) * spec.Hkv * 2 * spec.d * 2
     kv = int(Kb.sum()) * spec.Hkv * spec.S * tok
     dense = int((P * spec.S).sum()) * spec.Hkv * tok

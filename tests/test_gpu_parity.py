@@ -27,7 +27,7 @@ class Session:
         self.keep = keep      # pages kept whatever their score: (first, last)
         sp = w.spec
         fill = float("nan") if poison_meta else 0.0
-        self.page_min = torch.full((sp.B, sp.Hkv, w.P_max, sp.d), fill, dtype=torch.bfloat16,
+        self.page_min = torch.full((sp.B, sp.Hkv, w.P_max, sp.d), fill, dtype=w.k_pool.dtype,
                                    device=DEV)
         self.page_max = torch.full_like(self.page_min, fill)
         self.seq_lens = w.seq_lens.clone()
@@ -71,12 +71,22 @@ def compare_units(oracle, sess, units, scale, q_idx=0, what=""):
     out = sess.out.cpu().numpy()
     lens = sess.seq_lens.cpu()
     worst = 0.0
+    mdt = sess.page_min.dtype
+    with oracle.element_format(sp.kv):
+        worst = _compare_units(oracle, sess, units, scale, q_idx, what, w, sp, G, scores, sel, cnt,
+                               out, lens, mdt)
+    return worst
+
+
+def _compare_units(oracle, sess, units, scale, q_idx, what, w, sp, G, scores, sel, cnt, out, lens,
+                   mdt):
+    worst = 0.0
     for (b, h) in units:
         tag = f"{what} unit(b={b},h={h})"
         r = oracle_unit(oracle, w, b, h, scale, q_idx=q_idx, seq_lens=lens, keep=sess.keep)
         Pb = int(oracle.num_pages(int(lens[b]), sp.S))
-        omin = wl.from_bits(r["pmin"]).to(torch.float64).numpy()[0, 0]
-        omax = wl.from_bits(r["pmax"]).to(torch.float64).numpy()[0, 0]
+        omin = wl.from_bits(r["pmin"], dtype=mdt).to(torch.float64).numpy()[0, 0]
+        omax = wl.from_bits(r["pmax"], dtype=mdt).to(torch.float64).numpy()[0, 0]
         gmin = sess.page_min[b, h, :Pb].to(torch.float64).cpu().numpy()
         gmax = sess.page_max[b, h, :Pb].to(torch.float64).cpu().numpy()
         assert np.array_equal(gmin, omin[:Pb]), f"{tag}: page_min"
@@ -129,12 +139,16 @@ def splits(request):
     ts.set_tuning(0, 0, 0)
 
 
+FORMATS = ["bf16", "fp16"]    # 16-bit element formats of the cache (the INT8 one has its own file)
+
+
 @pytest.mark.parametrize("name", list(REDUCED))
 @pytest.mark.parametrize("scale_mode,splits", [("rsqrt_d", 0), ("one", 3), ("rsqrt_d", 8)],
                          indirect=["splits"])
-def test_reduced_all_units(oracle, built, name, scale_mode, splits):
-    spec = REDUCED[name]
-    print(f"[case] reduced {name} scale={scale_mode} splits={splits}", flush=True)
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_reduced_all_units(oracle, built, name, scale_mode, splits, fmt):
+    spec = wl.scaled(REDUCED[name], kv=fmt)
+    print(f"[case] reduced {name} {fmt} scale={scale_mode} splits={splits}", flush=True)
     # paper-literal scale runs on two dense pools, the usual one on the interleaved K|V pool
     w = wl.make_workload(spec, DEV, seed=2000 + len(name), n_q=2,
                          interleave=(scale_mode == "rsqrt_d"))
@@ -307,12 +321,13 @@ def _bits_equal(a, b):
 
 @pytest.mark.parametrize("name", list(APPEND_FUSED))
 @pytest.mark.parametrize("splits", [0, 2, 5], indirect=True)
-def test_append_and_decode_equals_separate_calls(oracle, built, name, splits):
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_append_and_decode_equals_separate_calls(oracle, built, name, splits, fmt):
     """ts_append_and_decode == ts_append_token_meta followed by ts_query_aware_decode:
     same outputs, same metadata, same pool contents, same lengths, step after step
     across page boundaries, including a sequence that runs out of room."""
-    spec = APPEND_FUSED[name]
-    print(f"[case] append+decode {name} splits={splits}", flush=True)
+    spec = wl.scaled(APPEND_FUSED[name], kv=fmt)
+    print(f"[case] append+decode {name} {fmt} splits={splits}", flush=True)
     n_new = 36
     scale = 1.0 / math.sqrt(spec.d)
     sessions = []
@@ -371,9 +386,10 @@ MANY_UNITS = {
 
 
 @pytest.mark.parametrize("name", list(MANY_UNITS))
-def test_many_units_loop_build(oracle, built, name):
-    spec = MANY_UNITS[name]
-    print(f"[case] many units {name}", flush=True)
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_many_units_loop_build(oracle, built, name, fmt):
+    spec = wl.scaled(MANY_UNITS[name], kv=fmt)
+    print(f"[case] many units {name} {fmt}", flush=True)
     w = wl.make_workload(spec, DEV, seed=404, n_q=3, n_new=3)
     sess = Session(w)
     ts.build_page_meta(sess.layout)
@@ -430,12 +446,13 @@ LSE_ATOL = 2e-3   # log of the softmax denominator, absolute (fp32 sums of bf16 
 @pytest.mark.parametrize("name", ["mha_d64_s16", "gqa8_d64_s32_walk", "mha_d128_s16_ragged",
                                   "gqa4_d128_s32", "k_exceeds_p", "gqa8_d64_s4", "mha_d128_s8",
                                   "gqa4_d64_s64", "mha_d128_s64"])
-def test_dense_baseline_matches_oracle(oracle, built, name):
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_dense_baseline_matches_oracle(oracle, built, name, fmt):
     """ts_dense_decode_attention (attention over the whole cache, the comparison the
     paper measures against) against the oracle's dense softmax attention, output and
     log-denominator."""
-    spec = REDUCED[name]
-    print(f"[case] dense {name}", flush=True)
+    spec = wl.scaled(REDUCED[name], kv=fmt)
+    print(f"[case] dense {name} {fmt}", flush=True)
     w = wl.make_workload(spec, DEV, seed=11, n_q=1)
     sess = Session(w)
     scale = 1.0 / math.sqrt(spec.d)
@@ -444,8 +461,10 @@ def test_dense_baseline_matches_oracle(oracle, built, name):
     ts.dense_decode_attention(sess.layout, w.q[0], scale, sess.out, ws, lse_out=lse)
     torch.cuda.synchronize()
     K, V = wl.logical_kv(w)
-    ref, ref_lse = oracle.dense_decode_attention(wl.bits(w.q[0]), wl.bits(K), wl.bits(V),
-                                                 w.seq_lens.cpu().numpy(), scale, return_lse=True)
+    with oracle.element_format(fmt):
+        ref, ref_lse = oracle.dense_decode_attention(wl.bits(w.q[0]), wl.bits(K), wl.bits(V),
+                                                     w.seq_lens.cpu().numpy(), scale,
+                                                     return_lse=True)
     err = np.abs(sess.out.cpu().numpy().astype(np.float64) - ref).max()
     assert err <= 2e-3, f"dense attention off by {err}"
     err = np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max()
@@ -613,6 +632,22 @@ def test_full_size_other_page_sizes(oracle, built, S):
                          sess.out, sess.ws, scores_out=sess.scores, sel_out=sess.sel,
                          sel_count_out=sess.sel_count)
     compare_units(oracle, sess, units, scale, q_idx=0, what=f"full/S{S}/append")
+
+
+@pytest.mark.parametrize("name", ["tinyllama", "ragged"])
+def test_full_size_fp16(oracle, built, name):
+    """Benchmark workloads at full size with IEEE-half tensors, default launch shapes: one
+    step through ts_append_and_decode, sampled units."""
+    spec = wl.scaled(wl.SPECS[name], kv="fp16")
+    print(f"[case] full fp16 {name}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=1700, n_q=2, n_new=1)
+    sess = Session(w, poison_meta=(name != "ragged"))
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[1], w.topk, w.K_max, scale,
+                         sess.out, sess.ws, topk_per_seq=w.topk_per_seq, scores_out=sess.scores,
+                         sel_out=sess.sel, sel_count_out=sess.sel_count)
+    compare_units(oracle, sess, unit_samples(w, 6, seed=3), scale, q_idx=1, what=f"full fp16/{name}")
 
 
 FULL = ["tiny", "gpt2_345m", "tinyllama", "longctx", "ragged"]
