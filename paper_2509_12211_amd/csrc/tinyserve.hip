@@ -186,10 +186,9 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
       const int j = j0 + i * kThreads;
       if (j < Pb) {
         const uint32_t k = score_key(v[i]);
-        const bool forced = fp.has(j);
-        L.keys[kl.at(j)] = forced ? kForcedKey : k;
-        tmin = forced ? tmin : min(tmin, k);
-        tmax = forced ? tmax : max(tmax, k);
+        L.keys[kl.at(j)] = k;
+        tmin = min(tmin, k);
+        tmax = max(tmax, k);
       }
     }
   }
@@ -347,7 +346,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
 
     // 1. score my share of the pages; the unit's block-table row is parked in LDS
     KeyLayout kl;
-    ForcedPages fp;
     int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
@@ -377,7 +375,6 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           }
           pb_scan = uniform(min(pages_of(L_unit, S), Pmax));
           kl = KeyLayout::make(pb_scan);
-          fp = ForcedPages::make(p.keep_first, p.keep_last, pb_scan);
           return pb_scan;
         },
         [&](uint4& mn, uint4& mx, int pg) {
@@ -398,10 +395,9 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
             store_agent_tagged(srow + pg, s, tag);
           } else if (pg < pb_scan) {
             const uint32_t k = score_key(s);
-            const bool forced = fp.has(pg);
-            sl.keys[kl.at(pg)] = forced ? kForcedKey : k;
-            tmin = forced ? tmin : min(tmin, k);
-            tmax = forced ? tmax : max(tmax, k);
+            sl.keys[kl.at(pg)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
           }
           if (srow_out) srow_out[pg] = s;
         });
@@ -441,10 +437,9 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
           const int j = j0 + i * kThreads;
           if (j < Pb) {
             const uint32_t k = score_key(__uint_as_float((uint32_t)v[i]));
-            const bool forced = fp.has(j);
-            sl.keys[kl.at(j)] = forced ? kForcedKey : k;
-            tmin = forced ? tmin : min(tmin, k);
-            tmax = forced ? tmax : max(tmax, k);
+            sl.keys[kl.at(j)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
           }
         }
       }
@@ -486,7 +481,8 @@ __global__ __launch_bounds__(kThreads) void query_aware_decode_kernel(FusedParam
     if (sel_row)
       for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
     if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
-    select_topk_lds(sl, kl, Pb, Kb, fp, [&](int rank, int page) {
+    select_topk_lds(sl, kl, Pb, Kb, ForcedPages::make(p.keep_first, p.keep_last, Pb),
+                    [&](int rank, int page) {
       if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
       if (sel_row) sel_row[rank] = page;
     });

@@ -73,17 +73,18 @@ struct AttendParams {
   const uint16_t* k_pool;      // [n_phys][Hkv] tiles of [S][D], tile_stride apart
   const uint16_t* v_pool;      // [n_phys][Hkv] tiles of [D][S], tile_stride apart
                                // (INT8 cache: the same shapes in int8, stride in bytes)
-  const float* k_scale;        // INT8 cache only: fp32 [n_phys][Hkv][S], one scale per token
-  const float* v_scale;
   const int32_t* block_table;  // [B][Pmax]
   const int32_t* seq_lens;     // [B]
   float* out;                  // [B][Hq][D] fp32, or bf16 when out_bf16 != 0
-  float* lse;                  // nullable [B][Hq]: log of the softmax denominator
   float* partials;             // [B*Hkv][n_split][G][D+2]
   int Hq, Hkv, G, Pmax, Kmax, n_phys, n_split, chunk;
   int tile_stride;             // elements between consecutive (page, head) tiles
   float scale_log2;            // softmax_scale * log2(e)
+  // (rarely used fields last: the kernels fetch their arguments front to back)
   int out_bf16;                // the final output is rounded to bf16 (nearest even)
+  float* lse;                  // nullable [B][Hq]: log of the softmax denominator
+  const float* k_scale;        // INT8 cache only: fp32 [n_phys][Hkv][S], one scale per token
+  const float* v_scale;
 };
 
 // Element idx of the output, in the caller's format.
@@ -395,6 +396,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   const int kb = lane_id() >> 4;
   float4_t sc[NT];
   float mx = -INFINITY;
+  const bool partial = vmask != (F == 32 ? 0xffffffffu : 0xffffu);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     sc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -403,16 +405,19 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
       sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
       sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
     }
-    const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
     float kst[4] = {1.f, 1.f, 1.f, 1.f};
     if (kScaled) { kst[0] = ks[t].x; kst[1] = ks[t].y; kst[2] = ks[t].z; kst[3] = ks[t].w; }
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const float raw = kScaled ? sc[t][v] * kst[v] : sc[t][v];
-      const float x = (mine >> v) & 1u ? raw * scale_log2 : -INFINITY;
-      sc[t][v] = x;
-      mx = fmaxf(mx, x);
+    for (int v = 0; v < 4; ++v)
+      sc[t][v] = (kScaled ? sc[t][v] * kst[v] : sc[t][v]) * scale_log2;
+    if (partial) {   // (uniform) a fragment with all its tokens, the common case, masks nothing
+      const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (!((mine >> v) & 1u)) sc[t][v] = -INFINITY;
     }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) mx = fmaxf(mx, sc[t][v]);
   }
   mx = rows_max_f32(mx);
   const float m_new = fmaxf(a.m, mx);
@@ -421,7 +426,6 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   a.l *= alpha;
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) a.o[cb] *= alpha;
-  const bool partial = vmask != (F == 32 ? 0xffffffffu : 0xffffu);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     // softmax weights split into two bf16 terms (truncated high part + remainder)

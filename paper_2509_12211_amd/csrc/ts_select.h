@@ -25,10 +25,12 @@ __device__ __forceinline__ float key_score(uint32_t k) {
 }
 
 // Pages kept whatever their score (an option outside the paper: the first pages
-// of a sequence as attention sinks, its last pages as the newest tokens).  They
-// carry the key kForcedKey, above every score's key, so they rank ahead of all
-// other pages and among themselves by page id; callers leave them out of the key
-// range they hand to select_begin.
+// of a sequence as attention sinks, its last pages as the newest tokens).  The
+// selection gives them the key kForcedKey, above every score's key, so they rank
+// ahead of all other pages and among themselves by page id.  Callers fill the
+// keys from the scores as if there were no such pages; select_topk_lds
+// overwrites the few keys concerned, so a selection without them pays one
+// scalar branch.
 constexpr uint32_t kForcedKey = 0xffffffffu;
 struct ForcedPages {
   int first;       // pages [0, first) are kept
@@ -40,11 +42,6 @@ struct ForcedPages {
     f.last_begin = max(f.first, Pb - max(keep_last, 0));
     f.count = f.first + Pb - f.last_begin;
     return f;
-  }
-  __device__ __forceinline__ bool has(int page) const { return page < first || page >= last_begin; }
-  // key of a page's score for the selection
-  __device__ __forceinline__ uint32_t key(int page, uint32_t score_key_of_page) const {
-    return has(page) ? kForcedKey : score_key_of_page;
   }
 };
 
@@ -136,7 +133,7 @@ __device__ __forceinline__ void select_begin(const SelectLds& L, uint32_t tmin, 
 // more than kMaxCandidates pages (heavy ties) goes through exact radix passes
 // on the integer keys instead.
 //
-// fp: the always-kept pages (their keys are kForcedKey: linear_slot puts them
+// fp: the always-kept pages (their keys become kForcedKey: linear_slot puts them
 // into the top bin, everything after that works on the integer keys).
 template <typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLayout& kl, int Pb,
@@ -154,6 +151,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   if (fp.count >= Kb) {  // the always-kept pages fill the budget: the Kb lowest ids of them
     for (int r = tid; r < Kb; r += kThreads) emit(r, r < fp.first ? r : fp.last_begin + (r - fp.first));
     return;
+  }
+  const bool any_forced = uniform(fp.count) != 0;
+  if (any_forced) {   // (uniform) the keys of the always-kept pages, over what the caller wrote
+    for (int j = tid; j < fp.first; j += kThreads) L.keys[kl.at(j)] = kForcedKey;
+    for (int j = fp.last_begin + tid; j < Pb; j += kThreads) L.keys[kl.at(j)] = kForcedKey;
+    __syncthreads();
   }
   const int C = kl.C;
   const int my_first = tid * C;                       // first page of this thread's chunk
@@ -225,8 +228,9 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const float smin = key_score(kmin);
   const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
   auto linear_slot = [&](uint32_t k) {   // 0 = highest scores (and the always-kept pages)
-    const int s = kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
-    return k == kForcedKey ? 0 : s;
+    int s = kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
+    if (any_forced) s = k == kForcedKey ? 0 : s;
+    return s;
   };
   int need = Kb, cut_slot = 0;
   // how the pages at the cut are told apart from those above it
