@@ -33,8 +33,8 @@ HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
 # 256 MiB copy: x1.9997 and x1.0000).  Counters cannot be read from inside this process, so the
 # figures are carried here from the committed summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "tinyllama": int((26737.8 * 1.9997 + 1628.1) * 1024),
-    "longctx": int((19718.8 * 1.9997 + 1479.1) * 1024),
+    "tinyllama": int((26772.0 * 1.9997 + 1628.1) * 1024),
+    "longctx": int((19791.5 * 1.9997 + 1479.1) * 1024),
 }
 
 WORKLOAD_DESC = {

@@ -914,9 +914,14 @@ int ts_append_token_meta(const ts_layout* layout, const void* k_new, const void*
         static_cast<const uint16_t*>(v_new), advance_seq_lens);
     return launch_status();
   }
-  append_token_meta_kernel<<<p.B, kThreads, 0, (hipStream_t)stream>>>(
-      p, layout->head_dim, static_cast<const uint16_t*>(k_new),
-      static_cast<const uint16_t*>(v_new), advance_seq_lens, layout->kv_format == TS_KV_FP16);
+  if (layout->kv_format == TS_KV_FP16)
+    append_token_meta_kernel<true><<<p.B, kThreads, 0, (hipStream_t)stream>>>(
+        p, layout->head_dim, static_cast<const uint16_t*>(k_new),
+        static_cast<const uint16_t*>(v_new), advance_seq_lens);
+  else
+    append_token_meta_kernel<false><<<p.B, kThreads, 0, (hipStream_t)stream>>>(
+        p, layout->head_dim, static_cast<const uint16_t*>(k_new),
+        static_cast<const uint16_t*>(v_new), advance_seq_lens);
   return launch_status();
 }
 

@@ -94,11 +94,12 @@ __device__ __forceinline__ uint4 widen_box(const uint4& box, const uint4& k, boo
 // the token's values (which do not depend on the length) go out together with
 // the length, then the block-table entry and the old box together.  All threads
 // read seq_lens[b] before the barrier; thread 0 advances it after.
-// half: the cache holds IEEE half (the comparison is the only thing that differs).
+// kHalf: the cache holds IEEE half (the comparison is the only thing that differs).
+template <bool kHalf>
 __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams p, int D,
                                                                       const uint16_t* k_new,
                                                                       const uint16_t* v_new,
-                                                                      int advance, int half) {
+                                                                      int advance) {
   const int b = blockIdx.x, n8 = p.Hkv * D / 8, cpr = D / 8;   // chunks, chunks per head row
   const uint4* k_src = reinterpret_cast<const uint4*>(k_new + (size_t)b * p.Hkv * D);
   const uint4* v_src = reinterpret_cast<const uint4*>((v_new ? v_new : k_new) + (size_t)b * p.Hkv * D);
@@ -119,10 +120,8 @@ __global__ __launch_bounds__(kThreads) void append_token_meta_kernel(MetaParams 
     const uint4 vn = i0 == (int)threadIdx.x ? v0 : v_src[i0];
     const bool ok = fits && (v_new == nullptr || (phys >= 0 && phys < p.n_phys));
     if (ok) {
-      const uint4 wlo = half ? widen_box<true>(lo, kn, true) : widen_box<false>(lo, kn, true);
-      const uint4 whi = half ? widen_box<true>(hi, kn, false) : widen_box<false>(hi, kn, false);
-      *reinterpret_cast<uint4*>(p.page_min + m) = slot == 0 ? kn : wlo;
-      *reinterpret_cast<uint4*>(p.page_max + m) = slot == 0 ? kn : whi;
+      *reinterpret_cast<uint4*>(p.page_min + m) = slot == 0 ? kn : widen_box<kHalf>(lo, kn, true);
+      *reinterpret_cast<uint4*>(p.page_max + m) = slot == 0 ? kn : widen_box<kHalf>(hi, kn, false);
       if (v_new != nullptr) {
         const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
         *reinterpret_cast<uint4*>(p.k_pool_w + tile + (size_t)slot * D + c8) = kn;
