@@ -1,9 +1,10 @@
 // Sparse single-query attention over the selected pages (Section 3.5 SparseAttn;
-// steps 3-4 of Algorithm 1) with bf16 MFMA and an online softmax, split over
+// steps 3-4 of Algorithm 1) with 16-bit MFMA (bf16, or IEEE half for the FP16
+// cache; the INT8 cache is expanded to bf16) and an online softmax, split over
 // workgroups (flash-decoding style partial softmax + combine).
 //
 // One wavefront processes whole pages.  Per 16-token tile it computes
-//   St[token][head] = K_tile[token][:] . Q^T[:][head]        (v_mfma_f32_16x16x16_bf16)
+//   St[token][head] = K_tile[token][:] . Q^T[:][head]        (v_mfma_f32_16x16x16_bf16 / _f16)
 //   Ot[chan ][head] += V_tile^T[chan][token] . P^T[token][head]
 // The accumulator layout of the first product (lane -> head lane%16, tokens
 // 4*(lane/16)..+3) is exactly the B-operand layout of the second, so the
@@ -463,7 +464,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 // The workgroup attends `count` selected pages of unit (b, h): entry i of its
 // list is page sel_at(i), stored in physical page phys_at(page).  The list is
 // cut into fragments (PageGeom<S>); wave w takes fragments w, w + kWaves, ...
-// The four wave states are merged through LDS
+// The waves' states are merged through LDS
 // (lds: kWaves * G * (D + 2) floats).  With n_split == 1 the normalised result
 // goes to `out`; otherwise the unnormalised partial (o[D], m, l per head) is
 // handed to the combining workgroup through agent-scope stores.

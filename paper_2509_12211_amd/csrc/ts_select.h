@@ -3,8 +3,8 @@
 // compaction that emits the kept page ids in ascending order and resolves
 // equal scores in favour of the lower page id.
 //
-// A lone wave issues roughly one instruction every 6-8 cycles, so with four
-// waves per workgroup this step is bound by its instruction count, not by LDS
+// A lone wave issues roughly one instruction every 6-8 cycles, so with two
+// waves per SIMD this step is bound by its instruction count, not by LDS
 // bandwidth: the keys are passed over as few times as possible (range while
 // loading, one histogram pass, one compaction pass), every LDS read of a pass
 // is issued before the first is used, and nothing goes through ds_bpermute.

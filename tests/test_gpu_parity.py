@@ -689,3 +689,19 @@ def test_full_size_sampled(oracle, built, name):
     torch.cuda.synchronize()
     assert torch.equal(sess.sel, fused_sel)
     assert (sess.out - fused_out).abs().max().item() <= 1e-6
+    # the step bench.py times: one call of ts_append_and_decode (for the small batches a
+    # single launch of the kernel build with the append folded in), first with the
+    # reporting buffers for the comparison, then as bench.py calls it (outputs only)
+    if name != "ragged":       # (ragged has already appended its one spare token above)
+        args = (sess.layout, w.k_new[0], w.v_new[0], w.q[0], w.topk, w.K_max, scale, sess.out,
+                sess.ws)
+        ts.append_and_decode(*args, topk_per_seq=w.topk_per_seq, scores_out=sess.scores,
+                             sel_out=sess.sel, sel_count_out=sess.sel_count)
+        compare_units(oracle, sess, units, scale, q_idx=0, what=f"full/{name}/append+decode")
+        reported = sess.out.clone()
+        sess.seq_lens.sub_(1)                       # the same step again, nothing reported
+        sess.out.fill_(float("nan"))
+        ts.append_and_decode(*args, topk_per_seq=w.topk_per_seq)
+        torch.cuda.synchronize()
+        assert ts.workspace_status(sess.ws) == 0
+        assert torch.equal(sess.out, reported)
