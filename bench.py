@@ -35,6 +35,9 @@ HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
 MEASURED_TRAFFIC_BYTES = {
     "tinyllama": int((26772.0 * 1.9997 + 1628.1) * 1024),
     "longctx": int((19791.5 * 1.9997 + 1479.1) * 1024),
+    "gpt2_345m": int((24943.3 * 1.9997 + 340.1) * 1024),
+    "tiny": int((128.0 * 1.9997 + 2.7) * 1024),
+    "ragged": int((2383591.8 * 1.9997 + 1104.1) * 1024),
 }
 
 WORKLOAD_DESC = {
@@ -178,7 +181,17 @@ def cpu_baseline(spec, layer, wl, budget_s=20.0):
             break
     med = sorted(times)[len(times) // 2]
     us_step = med * 1e6 * spec.B / n_seq
-    return {"value": round(us_step, 1), "unit": "us/step", "cores": oracle.max_threads(),
+    cores = oracle.max_threads()
+    # the same on one thread (a few runs, at most a fifth of the budget again)
+    oracle.set_num_threads(1)
+    single, t_start = [], time.perf_counter()
+    while len(single) < 3 and (not single or time.perf_counter() - t_start < 0.2 * budget_s):
+        t0 = time.perf_counter()
+        step()
+        single.append(time.perf_counter() - t0)
+    oracle.set_num_threads(0)
+    return {"value": round(us_step, 1), "unit": "us/step", "cores": cores,
+            "single_thread_value": round(sorted(single)[len(single) // 2] * 1e6 * spec.B / n_seq, 1),
             "kind": "oracle",
             "sample": f"{n_seq} of {spec.B} sequences (all KV heads), score+select+attend (the append "
                       f"of one token, microseconds on a CPU, is not in the timed loop), "

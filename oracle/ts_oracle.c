@@ -86,6 +86,18 @@ int tso_max_threads(void) {
 #endif
 }
 
+/* Threads the one OpenMP loop of this file (the attention over query heads) may
+ * use from now on; n <= 0 restores the default.  For timing only. */
+void tso_set_num_threads(int n) {
+#ifdef _OPENMP
+  static int initial = 0;
+  if (initial == 0) initial = omp_get_max_threads();
+  omp_set_num_threads(n > 0 ? n : initial);
+#else
+  (void)n;
+#endif
+}
+
 /* Section 3.4 / Eq. 1: phi(K_j) = (m_j, M_j), the channel-wise min and max of
  * the keys stored in page j.  Only tokens t < seq_lens[b] exist; a partly
  * filled last page is summarised over the tokens it holds.  Rows of pages

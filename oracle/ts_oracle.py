@@ -69,6 +69,11 @@ def max_threads() -> int:
     return int(_load().tso_max_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads for the OpenMP attention loop (n <= 0: the default again).  Timing only."""
+    _load().tso_set_num_threads(int(n))
+
+
 def _u16(a):
     a = np.ascontiguousarray(a)
     assert a.dtype == np.uint16, a.dtype
