@@ -209,7 +209,9 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
 // workgroup records the constant-rate 100 MHz clock at numbered points.  The
 // buffer address is parked in LDS once (TS_MARK_INIT at kernel entry) so that a
 // mark costs an LDS read and a store, and waits for no memory load in flight.
-// Compiled out of the product library.
+// Compiled out of the product library.  A tuning build is one translation unit
+// (a file that includes every .hip file of this directory), since the buffer
+// pointer below is one device variable.
 #ifdef TS_PROFILE
 __device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][32]
 __device__ __forceinline__ unsigned long long** profile_slot() {

@@ -1,0 +1,611 @@
+// The kernels that depend on the cache format (attention over the selected
+// pages, and Algorithm 1 in one launch) and their host-side launch logic.  Each
+// format is compiled in a file of its own (fmt_*.hip instantiate
+// launch_fused_format / launch_attention_format / append_capacity_format for
+// one format each); tinyserve.hip holds the entry points and everything that
+// does not depend on the format.
+#pragma once
+#include "../../include/tinyserve.h"
+
+#include <hip/hip_runtime.h>
+
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "ts_attend.h"
+#include "ts_device.h"
+#include "ts_meta.h"
+#include "ts_score.h"
+#include "ts_select.h"
+
+namespace ts {
+
+
+// ---------------------------------------------------------------------------
+// Work decomposition shared by host and device
+// ---------------------------------------------------------------------------
+// A unit is one (sequence, KV head).  A unit is worked on by a cluster of g
+// workgroups: each scores 1/g of the unit's pages and attends 1/g of its
+// selected pages.  g is chosen so that units * g is about one workgroup (eight
+// waves) per compute unit; with thousands of units g = 1 and nothing is exchanged
+// between workgroups at all.
+constexpr int kCtrlWords = 64;   // control words at the head of the workspace
+constexpr int kCtrlTicket = 0;   // next unit (fused kernel, g == 1, more units than workgroups)
+constexpr int kCtrlExit = 1;     // workgroups that have finished taking tickets
+constexpr int kCtrlError = 2;    // sticky: a bounded wait expired
+constexpr int kCtrlEpoch = 16;   // launches of the fused kernel with clusters so far (own 64-byte line)
+constexpr int kCtrlArrive = 32;  // workgroups of the current launch that have read the epoch (own line)
+constexpr int kSpinLimit = 1 << 20;  // polls (a few hundred ns each) before a wait gives up
+constexpr int kTargetWorkgroups = 256;
+constexpr int kMaxCluster = 64;
+// Per-unit counters are bumped by every member of a cluster at about the same
+// time.  Each gets a 256-byte slot of its own while the batch is small: sixteen
+// units' counters packed into one 64-byte line made every workgroup of the
+// launch hammer the same line (measured: 6 us of waiting with 16 x 16
+// workgroups).  Only clusters (g > 1, at most a few hundred units) use the
+// counters, so large batches keep them packed.
+constexpr int kCounterPadUnits = 512;
+constexpr int kCounterPadStride = 64;   // int32 words
+
+struct Plan {
+  int units;          // B * Hkv
+  int g;              // workgroups per unit (= attention splits = score slices)
+  int chunk;          // selected pages per workgroup
+  size_t off_unit;    // int32 [2][units * cstride]: arrival counters of the fused / the staged attention
+  int cstride;        // words between the counters of consecutive units
+  size_t off_scores;  // {fp32 score, uint32 launch tag} [units][Pmax]
+  size_t off_part;    // fp32 [units][g][G][d+2]
+  size_t total;
+  size_t lds_fused;   // dynamic LDS of the fused kernel
+};
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct FusedParams {
+  AttendParams at;
+  const uint16_t* page_min;
+  const uint16_t* page_max;
+  uint64_t* scores;     // [units][Pmax] exchange buffer (workspace): score | launch tag << 32
+  float* scores_out;    // nullable, caller's
+  int32_t* sel_out;     // nullable [units][Kmax]
+  int32_t* sel_count;   // nullable [B]
+  const int32_t* topk_per_seq;
+  int32_t* ctrl;        // control words
+  int32_t* attend_done; // [units * cstride]
+  // One token per sequence appended by the same launch (k_new == nullptr: none).
+  // (the pool, the metadata and the lengths are then written through the
+  // pointers above: the caller's buffers are writable, the const is this
+  // library's view of them in the calls that only read)
+  const uint16_t* k_new;   // [B][Hkv][D]
+  const uint16_t* v_new;
+  int topk, S, units, g, cstride, B;
+  int keep_first, keep_last;   // pages kept whatever their score (0, 0: the paper's selection)
+};
+
+__device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
+
+// grid (g, units).  The last workgroup of a unit to deposit its partial merges
+// them (unit_done counts arrivals and is left at zero again).
+template <int D, int S, bool kInt8, bool kHalf>
+__global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams p,
+                                                                    const int32_t* sel,
+                                                                    const int32_t* sel_count,
+                                                                    int32_t* unit_done,
+                                                                    int cstride) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_last;
+  const int u = blockIdx.y, b = u / p.Hkv, h = u % p.Hkv, split = blockIdx.x;
+  // sel == nullptr: the dense baseline, every page of the sequence in order
+  const int all = sel ? 0 : min((p.seq_lens[b] + S - 1) / S, p.Kmax);
+  const int Kb = uniform(sel ? max(0, min(sel_count[b], p.Kmax)) : all);
+  const int c0 = min(split * p.chunk, Kb), count = min(c0 + p.chunk, Kb) - c0;
+  const int32_t* sel_row = sel ? sel + (size_t)u * p.Kmax + c0 : nullptr;
+  const int32_t* bt_row = p.block_table + (size_t)b * p.Pmax;
+  const NewToken none{-1, 0, p.q, p.q};
+  attend_split<D, S, true, false, kInt8, kHalf>(
+      p, b, h, split, count, p.seq_lens[b], none,
+      [&](int i) { return sel_row ? sel_row[i] : c0 + i; },
+      [&](int j) { return bt_row[j]; }, reinterpret_cast<float*>(smem));
+  if (p.n_split == 1) return;
+  stores_complete();
+  __syncthreads();
+  if (threadIdx.x == 0) s_last = atomic_add_agent(&unit_done[u * cstride], 1) == p.n_split - 1;
+  __syncthreads();
+  if (!uniform(s_last)) return;
+  combine_splits<D>(p, b, h);
+  if (threadIdx.x == 0) atomic_store_agent(&unit_done[u * cstride], 0);
+}
+
+// ---------------------------------------------------------------------------
+// Fused kernel (Algorithm 1 in one launch).
+//
+// Workgroup w belongs to cluster w / g as member w % g; a cluster takes units
+// cluster, cluster + n_clusters, ...  For each unit a member
+//   1. scores every g-th group of the unit's pages (metadata loads are issued
+//      before anything else; the unit's block-table row is copied to LDS
+//      meanwhile),
+//   2. g > 1: publishes its scores with agent-scope stores, bumps the unit's
+//      scan counter, waits (bounded) until all g members have, and reads the
+//      whole score row back;  g == 1: the scores never leave LDS,
+//   3. runs the top-K selection itself (every member computes the same list),
+//   4. attends its own 1/g of the selected pages,
+//   5. g > 1: publishes its partial softmax state, bumps the unit's attention
+//      counter; the member that arrives last merges the g partials.
+// Members only ever wait for members of their own cluster, all of which are
+// resident: the host launches at most as many workgroups as fit on the device
+// at once.  Every wait is bounded and raises the workspace's error word.
+//
+// Every thread-0-only block sits between two barriers and every value that
+// steers a branch around a barrier is pinned uniform.
+// ---------------------------------------------------------------------------
+//
+// kLoop = false is the build for launches in which every cluster has exactly one
+// unit (units * g workgroups all resident: every latency-bound shape).  Without
+// the loop around the body the compiler has nothing to hoist: with it, every
+// unit-independent value of the whole body (several hundred instructions, most
+// of them spilled at once) is computed ahead of the first unit, that is ahead of
+// the first load.
+//
+// kApp = true is the build that first appends one token per sequence
+// (ts_append_and_decode); the plain build carries none of its registers.
+//
+// The host launches at most one workgroup (eight waves) per compute unit, that is
+// two waves per SIMD: saying so lets the compiler schedule for latency with the
+// registers of that occupancy instead of saving registers for waves that never
+// come (measured: 0.5 us of 26 on the 16-sequence configuration).
+template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false, bool kHalf = false>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
+query_aware_decode_kernel(FusedParams p) {
+  static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
+  static_assert(!(kInt8 && kApp), "the INT8 cache is appended to by a kernel of its own");
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_flag;
+  TS_MARK_INIT();
+  TS_MARK(22);
+  const AttendParams& at = p.at;
+  const int g = p.g, G = at.G, Pmax = at.Pmax;
+  const int member = blockIdx.x % g;
+  const int n_clusters = gridDim.x / g;
+  const SelectLds sl = carve_select(smem, Pmax);
+  const size_t sel_bytes = select_lds_bytes(Pmax);
+  const size_t att_bytes = (size_t)kWaves * G * (D + 2) * 4;
+  int32_t* bt_lds = reinterpret_cast<int32_t*>(smem + (sel_bytes > att_bytes ? sel_bytes : att_bytes));
+  int32_t* my_sel = bt_lds + Pmax;  // [chunk]
+  unsigned char* q_stage = reinterpret_cast<unsigned char*>(bt_lds) +
+                           ((size_t)Pmax * 4 + (size_t)at.chunk * 4 + 15) / 16 * 16;
+  const bool exchange = g > 1;
+  // With one workgroup per unit and more units than workgroups (long ragged
+  // batches) the units are handed out from a counter as workgroups become
+  // free: a unit then takes tens of microseconds, so the counter is not
+  // contended, and the spread of sequence lengths no longer decides the finish
+  // time.  Nothing ever waits on a ticket holder.
+  const bool dynamic = kLoop && !exchange && p.units > (int)gridDim.x;
+  int u = blockIdx.x / g;
+  if (dynamic) {
+    if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
+    __syncthreads();
+    u = uniform(s_flag);
+    __syncthreads();
+  }
+
+  // The first loads of a unit (sequence length, K, query rows, block-table row,
+  // first metadata tile) are sent out ahead of everything else: for the first
+  // unit right here, before the set-up work that follows, for later units at the
+  // end of the unit before.  What they fetch is only looked at inside the loop.
+  constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
+  int L_raw, K_raw, epoch_raw, bt_regs[kBtRegs];
+  ScanRegs<D, kHalf> scan;
+  // Append mode: the new token's key / value rows of this unit, as the 16-byte
+  // chunk (channels 8 * (lane % (D/8)) .. + 7) every lane needs for the box update
+  // and the pool write.
+  constexpr bool app = kApp;
+  constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
+  uint4 kn16 = make_uint4(0, 0, 0, 0), vn16 = make_uint4(0, 0, 0, 0);
+  auto issue_unit = [&](int uu) {
+    const int b = uu / at.Hkv, h = uu % at.Hkv;
+    epoch_raw = p.ctrl[kCtrlEpoch];
+    L_raw = at.seq_lens[b];
+    K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
+    scan_issue_query<D, kHalf>(scan, at.q + ((size_t)b * at.Hq + (size_t)h * G) * D, G);
+    if (app) {  // behind the query (needed first), ahead of the metadata (needed with it)
+      const size_t row = ((size_t)b * at.Hkv + h) * D + (lane_id() % LPR) * 8;
+      kn16 = *reinterpret_cast<const uint4*>(p.k_new + row);
+      vn16 = *reinterpret_cast<const uint4*>(p.v_new + row);
+    }
+    const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
+#pragma unroll
+    for (int k = 0; k < kBtRegs; ++k)   // no branch around the loads
+      bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
+    scan_issue_tile<D, kHalf>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
+                       Pmax, member * kWaves + wave_id());
+  };
+  if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
+  TS_MARK(23);
+
+  // Launch tag of the score exchange.  The epoch word is read by every
+  // workgroup before it counts itself in; the workgroup that counts in last
+  // (every other one has read the word by then) advances it for the next launch
+  // on its way out.
+  uint32_t tag = 0;
+  int arrived = -1;
+  while (kLoop ? u < p.units : true) {
+    TS_MARK(0);
+    const int b = u / at.Hkv, h = u % at.Hkv;
+    const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
+    uint64_t* srow = p.scores + (size_t)u * Pmax;
+    float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
+
+    // 1. score my share of the pages; the unit's block-table row is parked in LDS
+    KeyLayout kl;
+    int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
+    int pb_scan = 0;                         // the unit's page count, known once the scan runs
+    uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
+    scan_finish<D, !kLoop, kHalf>(
+        scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
+        member * kWaves + wave_id(), g * kWaves, q_stage,
+        [&] {
+#pragma unroll
+          for (int k = 0; k < kBtRegs; ++k) {
+            const int j = threadIdx.x + k * kThreads;
+            if (j < Pmax) bt_lds[j] = bt_regs[k];
+          }
+          for (int j = threadIdx.x + kBtRegs * kThreads; j < Pmax; j += kThreads)
+            bt_lds[j] = bt_row[j];
+          // (the empty asm pins the first use of the two values to this point:
+          // using them earlier would put a memory round trip in front of the scan)
+          asm volatile("" : "+v"(L_raw), "+v"(K_raw), "+v"(epoch_raw));
+          // the tag is fixed by the first unit: the epoch word may already have
+          // been advanced (by the workgroup that counted itself in last) when a
+          // later unit's loads go out
+          if (tag == 0u) tag = (uint32_t)uniform(epoch_raw) + 1u;
+          L_unit = uniform(L_raw);
+          if (app && L_unit / S < Pmax) {  // a sequence with no room left is not extended
+            j_new = L_unit / S;
+            slot_new = L_unit % S;
+            L_unit += 1;
+          }
+          pb_scan = uniform(min(pages_of(L_unit, S), Pmax));
+          kl = KeyLayout::make(pb_scan);
+          return pb_scan;
+        },
+        [&](uint4& mn, uint4& mx, int pg) {
+          // the wave that scores the new token's page first widens (or opens)
+          // its box, in registers and in memory (the outer test is uniform over
+          // the wave: all the others jump over the block instead of executing
+          // it with every lane masked off)
+          if (__ballot(pg == j_new) != 0ull && pg == j_new) {
+            mn = slot_new == 0 ? kn16 : widen_box<kHalf>(mn, kn16, true);
+            mx = slot_new == 0 ? kn16 : widen_box<kHalf>(mx, kn16, false);
+            const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
+            *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_min) + row) = mn;
+            *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_max) + row) = mx;
+          }
+        },
+        [&](int pg, float s) {
+          if (exchange) {
+            store_agent_tagged(srow + pg, s, tag);
+          } else if (pg < pb_scan) {
+            const uint32_t k = score_key(s);
+            sl.keys[kl.at(pg)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
+          }
+          if (srow_out) srow_out[pg] = s;
+        });
+    const int L = uniform(L_unit);
+    const int Pb = uniform(min(pages_of(L, S), Pmax));
+    const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
+
+    // count this workgroup in (once): it has read the epoch and, in append mode,
+    // the sequence length
+    if (!kLoop || exchange) {
+      if (arrived == -1 && threadIdx.x == 0 && (exchange || app))
+        arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
+    }
+
+    // 2. exchange the scores inside the cluster
+    TS_MARK(1);
+    if (exchange) {
+      // every thread polls its own entries of the row until all carry this
+      // launch's tag (all loads of a round in flight together; bounded)
+      bool expired = false;
+      int spins = 0;
+      for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
+        uint64_t v[8];
+        for (;;) {
+          bool all = true;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
+            all = all && (uint32_t)(v[i] >> 32) == tag;
+          }
+          if (all) break;
+          if (++spins > kSpinLimit) { expired = true; break; }
+          __builtin_amdgcn_s_sleep(1);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int j = j0 + i * kThreads;
+          if (j < Pb) {
+            const uint32_t k = score_key(__uint_as_float((uint32_t)v[i]));
+            sl.keys[kl.at(j)] = k;
+            tmin = min(tmin, k);
+            tmax = max(tmax, k);
+          }
+        }
+      }
+      if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
+      TS_MARK(3);
+    }
+    select_begin(sl, tmin, tmax);
+    __syncthreads();
+    TS_MARK(4);
+    // The new token lands in its pool slot (one member's first lanes; the
+    // block-table row is complete in LDS once the barrier above is passed).
+    // Nothing in this launch reads it from there: the attention splices it in
+    // from the caller's arrays.  It is done now rather than at the end (stores
+    // issued last would hold up the completion of the kernel), by the first
+    // lanes of the last wave (the first wave carries the workgroup's atomics).
+    auto store_new_token = [&] {
+      const int t = (int)threadIdx.x - (kThreads - kWave);
+      if (j_new >= 0 && member == 0 && t >= 0 && t < LPR) {
+        const int phys = bt_lds[j_new];
+        if (phys >= 0 && phys < at.n_phys) {
+          const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
+          uint16_t* k_pool_w = const_cast<uint16_t*>(at.k_pool);
+          uint16_t* v_pool_w = const_cast<uint16_t*>(at.v_pool);
+          *reinterpret_cast<uint4*>(k_pool_w + tile + (size_t)slot_new * D + t * 8) = kn16;
+          const uint32_t vw[4] = {vn16.x, vn16.y, vn16.z, vn16.w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            v_pool_w[tile + (size_t)(t * 8 + i) * S + slot_new] =
+                (uint16_t)(vw[i >> 1] >> (16 * (i & 1)));
+        }
+      }
+    };
+
+    if (kApp) store_new_token();
+
+    // 3. select; keep my own chunk of the ascending list
+    const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
+    int32_t* sel_row = (p.sel_out && member == 0) ? p.sel_out + (size_t)u * at.Kmax : nullptr;
+    if (sel_row)
+      for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
+    if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
+    select_topk_lds(sl, kl, Pb, Kb, ForcedPages::make(p.keep_first, p.keep_last, Pb),
+                    [&](int rank, int page) {
+      if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
+      if (sel_row) sel_row[rank] = page;
+    });
+    __syncthreads();
+    TS_MARK(5);
+    // The workgroup that counted itself in last knows that every other one has
+    // read the epoch word and, with one unit per workgroup, its sequence length:
+    // its first wave re-arms the count, advances the epoch and (append mode)
+    // the lengths, here where the count's return has long arrived and nothing
+    // waits for the few stores.
+    if (wave_id() == 0 && uniform(arrived) == (int)gridDim.x - 1) {
+      arrived = -2;
+      if (lane_id() == 0) {
+        atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
+        if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+      }
+      if (app) {
+        int32_t* seq_lens_w = const_cast<int32_t*>(at.seq_lens);
+        for (int i = lane_id(); i < p.B; i += kWave) {
+          const int len = seq_lens_w[i];
+          if (len / S < Pmax) seq_lens_w[i] = len + 1;
+        }
+      }
+    }
+
+    // 4. attend my chunk (the wave-merge area reuses the select scratch)
+    const size_t new_row = ((size_t)b * at.Hkv + h) * D;
+    const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
+    attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
+        at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
+        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
+    TS_MARK(6);
+
+    // 5. merge the cluster's partials
+    if (exchange) {
+      stores_complete();
+      __syncthreads();
+      TS_MARK(7);
+      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u * p.cstride], 1) == g - 1;
+      __syncthreads();
+      const int last = uniform(s_flag);
+      TS_MARK(8);
+      if (last) combine_splits<D>(at, b, h);
+      __syncthreads();
+      TS_MARK(9);
+      if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
+        atomic_store_agent(&p.attend_done[u * p.cstride], 0);
+      }
+      __syncthreads();
+    }
+    if (!kLoop) break;
+    if (dynamic) {
+      __syncthreads();
+      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
+      __syncthreads();
+      u = uniform(s_flag);
+      __syncthreads();
+    } else {
+      u += n_clusters;
+    }
+    if (u >= p.units) break;
+    issue_unit(u);
+  }
+  if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
+    __syncthreads();
+    if (threadIdx.x == 0 && atomic_add_agent(&p.ctrl[kCtrlExit], 1) == (int)gridDim.x - 1) {
+      atomic_store_agent(&p.ctrl[kCtrlTicket], 0);
+      atomic_store_agent(&p.ctrl[kCtrlExit], 0);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+static int launch_status() { return hipGetLastError() == hipSuccess ? TS_OK : TS_ERR_LAUNCH; }
+
+static int num_compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    cus = n;
+  }
+  return cus;
+}
+
+template <typename KernelT>
+static int allow_lds(KernelT kernel, size_t bytes) {
+  if (bytes <= 64 * 1024) return TS_OK;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes) == hipSuccess
+             ? TS_OK
+             : TS_ERR_LAUNCH;
+}
+
+// Workgroups of `kernel` that can be resident on the whole device at once.  The
+// runtime's answer is remembered per (kernel, LDS size): the query costs more
+// host time than the launch itself.
+template <typename KernelT>
+static int resident_capacity(KernelT kernel, size_t lds) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, size_t>, int> known;
+  const std::pair<const void*, size_t> key(reinterpret_cast<const void*>(kernel), lds);
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = known.find(key);
+  if (it != known.end()) return it->second;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, lds) != hipSuccess)
+    return 0;
+  const int cap = per_cu * num_compute_units();
+  if (cap > 0) known[key] = cap;
+  return cap;
+}
+
+// CALL(D, S) for the layout's head_dim / page_size (check_layout has admitted them).
+#define TS_DISPATCH_PAGE(DD, S, CALL) \
+  switch (S) {                        \
+    case 4: CALL(DD, 4); break;       \
+    case 8: CALL(DD, 8); break;       \
+    case 16: CALL(DD, 16); break;     \
+    case 32: CALL(DD, 32); break;     \
+    default: CALL(DD, 64); break;     \
+  }
+#define TS_DISPATCH_SHAPE(D, S, CALL)   \
+  do {                                  \
+    if ((D) == 64) {                    \
+      TS_DISPATCH_PAGE(64, S, CALL)     \
+    } else {                            \
+      TS_DISPATCH_PAGE(128, S, CALL)    \
+    }                                   \
+  } while (0)
+
+// One unit per cluster and everything resident: the loop-free build, which for
+// the bf16 cache also exists with the append folded in.  Otherwise (thousands of
+// units, bound by bandwidth) the looping build; an append then runs as a launch
+// of its own in front of it: the looping build has no registers to spare for
+// it, and against hundreds of microseconds the extra launch does not count.
+// The INT8 cache is always appended to by its own kernel.
+// max_resident: workgroups the launch may count on being resident together.
+template <int D, int S, int kFmt>
+static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Plan& pl,
+                              const void* k_new, const void* v_new, int max_resident,
+                              void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
+  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8, kHalf>;
+  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8, kHalf>;
+  auto app_kernel = query_aware_decode_kernel<D, S, false, !kInt8, kInt8, kHalf>;   // == one_kernel for INT8
+  int st;
+  if ((st = allow_lds(loop_kernel, pl.lds_fused)) != TS_OK ||
+      (st = allow_lds(one_kernel, pl.lds_fused)) != TS_OK ||
+      (st = allow_lds(app_kernel, pl.lds_fused)) != TS_OK)
+    return st;
+  const bool fold_append = k_new && !kInt8;
+  int cap1 = resident_capacity(fold_append ? app_kernel : one_kernel, pl.lds_fused);
+  if (cap1 > max_resident) cap1 = max_resident;
+  const bool one_unit_each = pl.units * pl.g <= cap1;
+  if (k_new && !(one_unit_each && fold_append)) {
+    if ((st = ts_append_token_meta(layout, k_new, v_new, 1, stream)) != TS_OK) return st;
+    p.k_new = p.v_new = nullptr;
+  }
+  if (one_unit_each) {
+    const unsigned grid = (unsigned)(pl.units * pl.g);
+    if (p.k_new)
+      app_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
+    else
+      one_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
+    return TS_OK;
+  }
+  int cap = resident_capacity(loop_kernel, pl.lds_fused);
+  if (cap > max_resident) cap = max_resident;
+  int clusters = cap / pl.g;
+  if (clusters < 1) return TS_ERR_DEVICE;   // a cluster must be co-resident
+  if (clusters > pl.units) clusters = pl.units;
+  loop_kernel<<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);
+  return TS_OK;
+}
+
+// The fused launch for the layout's head_dim / page_size in one cache format.
+template <int kFmt>
+int launch_fused_format(const ts_layout* layout, FusedParams& p, const Plan& pl, const void* k_new,
+                        const void* v_new, int max_resident, void* stream) {
+  int st = TS_ERR_UNSUPPORTED;
+#define TS_LAUNCH_FUSED(DD, SS) \
+  st = launch_fused_shape<DD, SS, kFmt>(layout, p, pl, k_new, v_new, max_resident, stream)
+  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_LAUNCH_FUSED);
+#undef TS_LAUNCH_FUSED
+  return st;
+}
+
+// The staged attention kernel (grid (g, units)); sel == nullptr: every page.
+template <int kFmt>
+int launch_attention_format(const ts_layout* layout, const AttendParams& a, const Plan& pl,
+                            const int32_t* sel, const int32_t* sel_count, int32_t* unit_done,
+                            void* stream) {
+  constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
+  const size_t lds = (size_t)kWaves * a.G * (layout->head_dim + 2) * 4;
+  dim3 grid(pl.g, pl.units);
+  hipStream_t s = (hipStream_t)stream;
+#define TS_LAUNCH_ATTENTION(DD, SS)              \
+  sparse_attention_kernel<DD, SS, kInt8, kHalf> \
+      <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride)
+  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_LAUNCH_ATTENTION);
+#undef TS_LAUNCH_ATTENTION
+  return launch_status();
+}
+
+// Workgroups of the loop-free build with the append folded in that can be
+// resident at once (0: that build does not exist for the format).
+template <int kFmt>
+int append_capacity_format(const ts_layout* layout, const Plan& pl) {
+  constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
+  if (kInt8) return 0;
+  int cap = 0;
+#define TS_CAPACITY(DD, SS) \
+  cap = resident_capacity(query_aware_decode_kernel<DD, SS, false, !kInt8, kInt8, kHalf>, pl.lds_fused)
+  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_CAPACITY);
+#undef TS_CAPACITY
+  return cap;
+}
+
+// Instantiated once per format, each in its own file.
+#define TS_FORMAT_FUNCTIONS(LINKAGE, FMT)                                                          \
+  LINKAGE template int launch_fused_format<FMT>(const ts_layout*, FusedParams&, const Plan&,       \
+                                                const void*, const void*, int, void*);             \
+  LINKAGE template int launch_attention_format<FMT>(const ts_layout*, const AttendParams&,         \
+                                                    const Plan&, const int32_t*, const int32_t*,   \
+                                                    int32_t*, void*);                              \
+  LINKAGE template int append_capacity_format<FMT>(const ts_layout*, const Plan&);
+
+}  // namespace ts

@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void build_page_meta_i8_kernel(MetaParams
 // zero vector; code = x / scale rounded half to even, in fp32 with correctly
 // rounded division), stored with their scales when v_new is given, and the
 // page's box is opened / widened with the dequantised key rounded outwards.
-__global__ __launch_bounds__(kThreads) void append_token_i8_kernel(MetaParams p, int D,
+static __global__ __launch_bounds__(kThreads) void append_token_i8_kernel(MetaParams p, int D,
                                                                    const uint16_t* k_new,
                                                                    const uint16_t* v_new,
                                                                    int advance) {
