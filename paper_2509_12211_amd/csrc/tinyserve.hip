@@ -49,7 +49,7 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   pl.off_scores = off;
   off = align_up(off + (size_t)pl.units * Pmax * sizeof(uint64_t), 256);
   pl.off_part = off;
-  off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(float), 256);
+  off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(uint64_t), 256);
   pl.total = off;
   // fused kernel LDS: select scratch (keys, bins), the unit's block-table row,
   // this workgroup's selected pages; the wave-merge area aliases the keys
@@ -243,7 +243,6 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.sel_count = sel_count_out;
   p.topk_per_seq = topk_per_seq;
   p.ctrl = reinterpret_cast<int32_t*>(ws);
-  p.attend_done = reinterpret_cast<int32_t*>(ws + pl.off_unit);
   p.cstride = pl.cstride;
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);

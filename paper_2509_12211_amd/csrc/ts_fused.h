@@ -55,7 +55,7 @@ struct Plan {
   size_t off_unit;    // int32 [2][units * cstride]: arrival counters of the fused / the staged attention
   int cstride;        // words between the counters of consecutive units
   size_t off_scores;  // {fp32 score, uint32 launch tag} [units][Pmax]
-  size_t off_part;    // fp32 [units][g][G][d+2]
+  size_t off_part;    // [units][g][G][d+2]: {fp32, launch tag} words (fused) or fp32 (staged attention)
   size_t total;
   size_t lds_fused;   // dynamic LDS of the fused kernel
 };
@@ -72,7 +72,6 @@ struct FusedParams {
   int32_t* sel_count;   // nullable [B]
   const int32_t* topk_per_seq;
   int32_t* ctrl;        // control words
-  int32_t* attend_done; // [units * cstride]
   // One token per sequence appended by the same launch (k_new == nullptr: none).
   // (the pool, the metadata and the lengths are then written through the
   // pointers above: the caller's buffers are writable, the const is this
@@ -130,8 +129,9 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 //      whole score row back;  g == 1: the scores never leave LDS,
 //   3. runs the top-K selection itself (every member computes the same list),
 //   4. attends its own 1/g of the selected pages,
-//   5. g > 1: publishes its partial softmax state, bumps the unit's attention
-//      counter; the member that arrives last merges the g partials.
+//   5. g > 1: hands its partial softmax state on as words tagged with the launch
+//      tag; the cluster's last member polls for all g partials (data and flag
+//      arrive together) and merges them.
 // Members only ever wait for members of their own cluster, all of which are
 // resident: the host launches at most as many workgroups as fit on the device
 // at once.  Every wait is bounded and raises the workspace's error word.
@@ -405,25 +405,16 @@ query_aware_decode_kernel(FusedParams p) {
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
     attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
-        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem));
+        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u);
     TS_MARK(6);
 
-    // 5. merge the cluster's partials
-    if (exchange) {
-      stores_complete();
-      __syncthreads();
-      TS_MARK(7);
-      if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.attend_done[u * p.cstride], 1) == g - 1;
-      __syncthreads();
-      const int last = uniform(s_flag);
+    // 5. merge the cluster's partials: they were handed on as tagged words; the
+    // cluster's last member (its chunk of the list is the one that can be short)
+    // polls for all of them and writes the output.  Nobody else waits for anything.
+    if (exchange && member == g - 1) {
       TS_MARK(8);
-      if (last) combine_splits<D>(at, b, h);
-      __syncthreads();
+      if (!combine_tagged<D>(at, b, h, tag, kSpinLimit)) atomic_store_agent(&p.ctrl[kCtrlError], 1);
       TS_MARK(9);
-      if (last && threadIdx.x == 0) {  // every member has passed its wait on this unit
-        atomic_store_agent(&p.attend_done[u * p.cstride], 0);
-      }
-      __syncthreads();
     }
     if (!kLoop) break;
     if (dynamic) {
