@@ -97,8 +97,9 @@ __device__ __forceinline__ SelectLds carve_select(unsigned char* smem, int Pmax)
 // scans slots 32 l .. 32 l + 31; they are laid out so that the lanes' 16-byte
 // reads of a round fall on consecutive addresses.
 __device__ __forceinline__ int bin_slot_index(int k) {
-  const int l = k >> 5, j = k & 31;
-  return (j >> 2) * 256 + l * 4 + (j & 3);
+  // k = l * 32 + j  ->  (j >> 2) * 256 + l * 4 + (j & 3): three bit fields moved
+  const uint32_t u = (uint32_t)k;
+  return (int)((u & 3u) | ((u >> 5) << 2) | (((u >> 2) & 7u) << 8));
 }
 static_assert(kRadixBins == 64 * 32, "slot layout written for 64 lanes x 32 slots");
 
@@ -181,8 +182,18 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     hi = (uint32_t)uniform((int)b);
   };
   // fn(key, i) for each of this thread's keys, kBatch LDS reads in flight at a time
+  // A wave all of whose lanes hold a whole batch runs it without per-key tests
+  // (all but the wave at the end of the page range do).
   auto for_my_keys = [&](auto fn) {
-    for (int i0 = 0; i0 < my_n; i0 += kBatch) {
+    int i0 = 0;
+    for (; i0 + kBatch <= C && __ballot(my_n < i0 + kBatch) == 0ull; i0 += kBatch) {
+      uint32_t k[kBatch];
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) k[i] = my_keys[i0 + i];
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) fn(k[i], i0 + i);
+    }
+    for (; i0 < C; i0 += kBatch) {
       uint32_t k[kBatch];
 #pragma unroll
       for (int i = 0; i < kBatch; ++i) k[i] = i0 + i < my_n ? my_keys[i0 + i] : 0u;
@@ -227,10 +238,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   TS_MARK(10);
   const float smin = key_score(kmin);
   const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
-  auto linear_slot = [&](uint32_t k) {   // 0 = highest scores (and the always-kept pages)
-    int s = kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
-    if (any_forced) s = k == kForcedKey ? 0 : s;
-    return s;
+  // 0 = highest scores.  kForcedKey decodes to a quiet NaN, which fminf drops in
+  // favour of 2047 (IEEE minNum, v_min_f32 in the kernels' IEEE mode): the
+  // always-kept pages land in slot 0 with no test of their own (the parity tests
+  // with such pages cover it).
+  auto linear_slot = [&](uint32_t k) {
+    return kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
   };
   int need = Kb, cut_slot = 0;
   // how the pages at the cut are told apart from those above it
@@ -344,13 +357,14 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   }
   TS_MARK(14);
   const int excl = incl - packed;
-  int goff = excl & 0xffff, eoff = excl >> 16;
-  for (int i = 0; i < my_n; ++i) {
-    const bool g = (gbits >> i) & 1, e = (ebits >> i) & 1;
-    if (g) emit(goff + min(eoff, need), my_first + i);
-    else if (e && eoff < need) emit(goff + eoff, my_first + i);
-    goff += g;
-    eoff += e;
+  const int goff = excl & 0xffff, eoff = excl >> 16;
+  // only the marked pages are visited (few threads hold any when K << P)
+  for (uint64_t todo = gbits | ebits; todo != 0; todo &= todo - 1) {
+    const int i = __builtin_ctzll(todo);
+    const uint64_t below = (1ull << i) - 1;
+    const int gb = goff + __popcll(gbits & below), eb = eoff + __popcll(ebits & below);
+    if ((gbits >> i) & 1) emit(gb + min(eb, need), my_first + i);
+    else if (eb < need) emit(gb + eb, my_first + i);
   }
 }
 
