@@ -374,9 +374,11 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
   const int lane = lane_id(), head = lane & 15, kb = lane >> 4;
 #pragma unroll
   for (int i = 0; i < D / 32; ++i) {
-    // heads past G re-read head G - 1 (no branch around the load) and are zeroed
-    uint4 w = *reinterpret_cast<const uint4*>(q_group + (size_t)min(head, G - 1) * D + kb * (D / 4) + i * 8);
-    if (head >= G) w = make_uint4(0, 0, 0, 0);
+    // MFMA columns past G re-read head G - 1 (no branch around the load) and compute
+    // a redundant copy of it that nobody reads.  They are deliberately NOT zeroed:
+    // overwriting the destination of a load in flight makes the wave wait for it,
+    // two serial memory round trips at the start of every attention phase.
+    const uint4 w = *reinterpret_cast<const uint4*>(q_group + (size_t)min(head, G - 1) * D + kb * (D / 4) + i * 8);
     qf[2 * i] = as_short4(w.x, w.y);
     qf[2 * i + 1] = as_short4(w.z, w.w);
   }
@@ -476,6 +478,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 // kPatch: a token appended in the same launch may have to be spliced in (nt).
 // kInt8: the cache holds int8 keys / values with per-token scales.
 // kHalf: queries, keys and values are IEEE half instead of bf16.
+// q_rows: see below.
 // tag != 0 (n_split > 1): the partial is handed on as 8-byte words {value, tag}
 // (see combine_tagged), so the caller neither waits for the stores nor counts
 // an arrival; the partial area then holds uint64 [.][n_split][G][D + 2].
@@ -483,7 +486,8 @@ template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, bool kHalf, t
           typename PhysAt>
 __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
-                                             PhysAt phys_at, float* lds, uint32_t tag = 0u) {
+                                             PhysAt phys_at, float* lds, uint32_t tag = 0u,
+                                             const uint16_t* q_rows = nullptr) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
   static_assert(!(kPatch && kInt8), "no in-register append for the INT8 cache");
@@ -499,7 +503,9 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   const int n_items = Geo::items(count);
 
   short4_t qf[D / 16];
-  load_q_frag<D>(qf, p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  // q_rows: the unit's G query rows where the caller already holds them (the fused
+  // kernel: in LDS, staged by the scoring phase); nullptr: fetched from memory
+  load_q_frag<D>(qf, q_rows ? q_rows : p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
   // The new token's page is the sequence's last, so in the ascending list it can
   // only be the very last entry: one wave of one workgroup ever needs the token.
   // splice_item: the fragment it falls into, splice_x: its position there.

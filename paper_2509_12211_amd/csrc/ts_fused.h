@@ -405,7 +405,8 @@ query_aware_decode_kernel(FusedParams p) {
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
     attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
-        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u);
+        [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u,
+        reinterpret_cast<const uint16_t*>(q_stage));   // the raw rows head the staging area
     TS_MARK(6);
 
     // 5. merge the cluster's partials: they were handed on as tagged words; the
