@@ -120,8 +120,8 @@ typedef struct ts_layout {
    * dequantised keys and Eq. 2 remains an upper bound.  ts_append_token_meta
    * quantises the bf16 token: scale = max_c |x_c| / 127 (1 for a zero vector),
    * code = x_c / scale rounded half to even, all in fp32; with v_new == NULL only
-   * the box is widened, by the key so quantised.  ts_append_and_decode runs the
-   * append as a kernel of its own in front of the fused kernel. */
+   * the box is widened, by the key so quantised.  ts_append_and_decode does the
+   * same quantisation inside its launch. */
   int32_t kv_format;
   float* k_scale;
   float* v_scale;

@@ -489,9 +489,9 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
   const int cus = num_compute_units();
   if (cus <= 0) return TS_ERR_DEVICE;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-  if (layout->kv_format == TS_KV_INT8) return 2;   // always appended to by a kernel of its own
-  int cap1 = layout->kv_format == TS_KV_FP16 ? append_capacity_format<TS_KV_FP16>(layout, pl)
-                                             : append_capacity_format<TS_KV_BF16>(layout, pl);
+  int cap1 = layout->kv_format == TS_KV_FP16   ? append_capacity_format<TS_KV_FP16>(layout, pl)
+             : layout->kv_format == TS_KV_INT8 ? append_capacity_format<TS_KV_INT8>(layout, pl)
+                                               : append_capacity_format<TS_KV_BF16>(layout, pl);
   if (cap1 <= 0) return TS_ERR_DEVICE;
   if (cap1 > cus * per_cu) cap1 = cus * per_cu;
   return pl.units * pl.g <= cap1 ? 1 : 2;

@@ -349,6 +349,58 @@ struct TokenPatch {
   }
 };
 
+// The same for the INT8 cache: the rows are quantised here (scale = max |x| / 127
+// over the row, code = x / scale rounded half to even), the codes spliced in as
+// the bf16 integers the expanded fragments hold and the two scales put where the
+// fragment keeps the token's.  To be called by a whole wave.
+template <int D, int F>
+struct TokenPatch8 : TokenPatch<D, F> {
+  float ksc, vsc;
+  __device__ __forceinline__ static uint32_t code_bf16(float x, float scale) {
+    return __float_as_uint(static_cast<float>(i8_code(x, scale))) >> 16;   // exact: |code| <= 127
+  }
+  __device__ __forceinline__ void load(const NewToken& nt) {
+    TokenPatch<D, F>::load(nt);
+    float ka = 0.f, va = 0.f;
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i) ka = fmaxf(ka, chunk_amax_bf16(this->k[i]));
+#pragma unroll
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) va = fmaxf(va, fabsf(bf16_lo(this->v[cb])));
+    // a lane holds a quarter of the key row (the quarters sit 16 lanes apart) and
+    // every 16th channel of the value row (lane % 16 picks which)
+    ka = fmaxf(ka, shfl_xor_f(ka, 16));
+    ka = fmaxf(ka, shfl_xor_f(ka, 32));
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) va = fmaxf(va, shfl_xor_f(va, m));
+    ksc = i8_row_scale(ka);
+    vsc = i8_row_scale(va);
+#pragma unroll
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i) {
+      const uint32_t w[4] = {this->k[i].x, this->k[i].y, this->k[i].z, this->k[i].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        o[e] = code_bf16(bf16_lo(w[e]), ksc) | (code_bf16(bf16_hi(w[e]), ksc) << 16);
+      this->k[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+#pragma unroll
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) this->v[cb] = code_bf16(bf16_lo(this->v[cb]), vsc);
+  }
+  // the token's scales, where the fragment holds them (x as in apply)
+  __device__ __forceinline__ void apply_scales(float4 (&ks)[PageFrag<D, F>::NT],
+                                               float4 (&vs)[PageFrag<D, F>::NT], int x) const {
+    const int kb = lane_id() >> 4;
+#pragma unroll
+    for (int t = 0; t < PageFrag<D, F>::NT; ++t) {
+      const int e = x - tile_token<F>(t, 4 * kb);
+      if (e == 0) { ks[t].x = ksc; vs[t].x = vsc; }
+      if (e == 1) { ks[t].y = ksc; vs[t].y = vsc; }
+      if (e == 2) { ks[t].z = ksc; vs[t].z = vsc; }
+      if (e == 3) { ks[t].w = ksc; vs[t].w = vsc; }
+    }
+  }
+};
+
 // Natural log of sum_t exp(scale * q.k_t) from the running maximum m (log2
 // domain) and the sum l of exp2(logit - m); -inf when no token was attended.
 __device__ __forceinline__ float log_sum_exp(float m, float l) {
@@ -490,7 +542,6 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
                                              const uint16_t* q_rows = nullptr) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
-  static_assert(!(kPatch && kInt8), "no in-register append for the INT8 cache");
   static_assert(!(kHalf && kInt8), "the INT8 cache goes with bf16 queries");
   using Frag = std::conditional_t<kInt8, PageFrag8<D, F>, PageFrag<D, F>>;
   const uint8_t* k_pool8 = reinterpret_cast<const uint8_t*>(p.k_pool);
@@ -509,7 +560,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   // The new token's page is the sequence's last, so in the ascending list it can
   // only be the very last entry: one wave of one workgroup ever needs the token.
   // splice_item: the fragment it falls into, splice_x: its position there.
-  TokenPatch<D, F> patch;
+  std::conditional_t<kInt8, TokenPatch8<D, F>, TokenPatch<D, F>> patch;
   int splice_item = -1, splice_x = 0;
   if (kPatch && nt.j >= 0 && count > 0 && uniform(sel_at(count - 1)) == nt.j) {
     if (S < 16) {
@@ -602,6 +653,12 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
           if constexpr (kInt8) {
             PageFrag<D, F> fx;
             expand_frag<D, F>(f[i], fx);
+            if constexpr (kPatch) {
+              if (splice && item[i] == splice_item) {
+                patch.apply(fx, splice_x);
+                patch.apply_scales(f[i].ks, f[i].vs, splice_x);
+              }
+            }
             attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs);
           } else {
             if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);

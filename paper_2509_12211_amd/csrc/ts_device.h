@@ -60,6 +60,25 @@ __device__ __forceinline__ void unpack8(const uint4& w, float (&f)[8]) {
   f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
 }
 
+// INT8 cache: quantisation of one token's key or value row.  scale = max |x| / 127
+// (1 for a zero row), code = x / scale rounded half to even and clamped to
+// +-127, in fp32 with correctly rounded division.
+__device__ __forceinline__ float i8_row_scale(float amax) {
+  return amax > 0.f ? __fdiv_rn(amax, 127.0f) : 1.0f;
+}
+__device__ __forceinline__ int i8_code(float x, float scale) {
+  // (through the integer: a code that rounded to -0.0f is 0, as the stored byte is)
+  return static_cast<int>(fminf(fmaxf(rintf(__fdiv_rn(x, scale)), -127.f), 127.f));
+}
+// Largest magnitude among the eight bf16 values of a 16-byte chunk.
+__device__ __forceinline__ float chunk_amax_bf16(const uint4& c) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a = fmaxf(a, fmaxf(fabsf(bf16_lo(w[i])), fabsf(bf16_hi(w[i]))));
+  return a;
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // Values that are the same in every lane of a wavefront must be KNOWN to be so

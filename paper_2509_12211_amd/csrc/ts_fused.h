@@ -148,7 +148,10 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 // the first load.
 //
 // kApp = true is the build that first appends one token per sequence
-// (ts_append_and_decode); the plain build carries none of its registers.
+// (ts_append_and_decode); the plain build carries none of its registers.  With
+// the INT8 cache the token's bf16 rows are quantised in the launch, by the few
+// waves that need the codes (the one that scores the token's page, the one that
+// writes the pool, the one that attends the page).
 //
 // The host launches at most one workgroup (eight waves) per compute unit, that is
 // two waves per SIMD: saying so lets the compiler schedule for latency with the
@@ -158,7 +161,6 @@ template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false, bool kHalf = 
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 query_aware_decode_kernel(FusedParams p) {
   static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
-  static_assert(!(kInt8 && kApp), "the INT8 cache is appended to by a kernel of its own");
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_flag;
   TS_MARK_INIT();
@@ -198,7 +200,7 @@ query_aware_decode_kernel(FusedParams p) {
   ScanRegs<D, kHalf> scan;
   // Append mode: the new token's key / value rows of this unit, as the 16-byte
   // chunk (channels 8 * (lane % (D/8)) .. + 7) every lane needs for the box update
-  // and the pool write.
+  // and the pool write (bf16 also for the INT8 cache, which quantises them).
   constexpr bool app = kApp;
   constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
   uint4 kn16 = make_uint4(0, 0, 0, 0), vn16 = make_uint4(0, 0, 0, 0);
@@ -274,7 +276,25 @@ query_aware_decode_kernel(FusedParams p) {
           // its box, in registers and in memory (the outer test is uniform over
           // the wave: all the others jump over the block instead of executing
           // it with every lane masked off)
-          if (__ballot(pg == j_new) != 0ull && pg == j_new) {
+          if constexpr (kInt8) {
+            // INT8 cache: the box takes the dequantised key rounded outwards; the
+            // whole wave works out the row's scale (the LPR lanes of a row each
+            // hold one chunk of it), the page's lanes do the rest
+            if (kApp && __ballot(pg == j_new) != 0ull) {
+              float amax = chunk_amax_bf16(kn16);
+#pragma unroll
+              for (int m = 1; m < LPR; m <<= 1) amax = fmaxf(amax, shfl_xor_f(amax, m));
+              if (pg == j_new) {
+                uint4 lo, hi;
+                i8_chunk_box(kn16, i8_row_scale(amax), lo, hi);
+                mn = slot_new == 0 ? lo : widen_box<false>(mn, lo, true);
+                mx = slot_new == 0 ? hi : widen_box<false>(mx, hi, false);
+                const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
+                *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_min) + row) = mn;
+                *reinterpret_cast<uint4*>(const_cast<uint16_t*>(p.page_max) + row) = mx;
+              }
+            }
+          } else if (__ballot(pg == j_new) != 0ull && pg == j_new) {
             mn = slot_new == 0 ? kn16 : widen_box<kHalf>(mn, kn16, true);
             mx = slot_new == 0 ? kn16 : widen_box<kHalf>(mx, kn16, false);
             const size_t row = ((size_t)u * Pmax + pg) * D + (lane_id() % LPR) * 8;
@@ -349,6 +369,35 @@ query_aware_decode_kernel(FusedParams p) {
     // lanes of the last wave (the first wave carries the workgroup's atomics).
     auto store_new_token = [&] {
       const int t = (int)threadIdx.x - (kThreads - kWave);
+      if constexpr (kInt8) {
+        if (j_new >= 0 && member == 0 && wave_id() == kWaves - 1) {   // (uniform) the whole last wave
+          float ka = chunk_amax_bf16(kn16), va = chunk_amax_bf16(vn16);
+#pragma unroll
+          for (int m = 1; m < LPR; m <<= 1) {
+            ka = fmaxf(ka, shfl_xor_f(ka, m));
+            va = fmaxf(va, shfl_xor_f(va, m));
+          }
+          const int phys = bt_lds[j_new];
+          if (t < LPR && phys >= 0 && phys < at.n_phys) {
+            const float ksc = i8_row_scale(ka), vsc = i8_row_scale(va);
+            const size_t tile = ((size_t)phys * at.Hkv + h) * (size_t)at.tile_stride;
+            uint8_t* k8 = reinterpret_cast<uint8_t*>(const_cast<uint16_t*>(at.k_pool));
+            uint8_t* v8 = reinterpret_cast<uint8_t*>(const_cast<uint16_t*>(at.v_pool));
+            *reinterpret_cast<uint2*>(k8 + tile + (size_t)slot_new * D + t * 8) = i8_chunk_codes(kn16, ksc);
+            const uint2 vc = i8_chunk_codes(vn16, vsc);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              v8[tile + (size_t)(t * 8 + i) * S + slot_new] =
+                  (uint8_t)((i < 4 ? vc.x : vc.y) >> (8 * (i & 3)));
+            if (t == 0) {
+              const size_t so = ((size_t)phys * at.Hkv + h) * (size_t)S + slot_new;
+              const_cast<float*>(at.k_scale)[so] = ksc;
+              const_cast<float*>(at.v_scale)[so] = vsc;
+            }
+          }
+        }
+        return;
+      }
       if (j_new >= 0 && member == 0 && t >= 0 && t < LPR) {
         const int phys = bt_lds[j_new];
         if (phys >= 0 && phys < at.n_phys) {
@@ -502,12 +551,11 @@ static int resident_capacity(KernelT kernel, size_t lds) {
     }                                   \
   } while (0)
 
-// One unit per cluster and everything resident: the loop-free build, which for
-// the bf16 cache also exists with the append folded in.  Otherwise (thousands of
+// One unit per cluster and everything resident: the loop-free build, which
+// also exists with the append folded in.  Otherwise (thousands of
 // units, bound by bandwidth) the looping build; an append then runs as a launch
 // of its own in front of it: the looping build has no registers to spare for
 // it, and against hundreds of microseconds the extra launch does not count.
-// The INT8 cache is always appended to by its own kernel.
 // max_resident: workgroups the launch may count on being resident together.
 template <int D, int S, int kFmt>
 static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Plan& pl,
@@ -517,13 +565,13 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
   constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
   auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8, kHalf>;
   auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8, kHalf>;
-  auto app_kernel = query_aware_decode_kernel<D, S, false, !kInt8, kInt8, kHalf>;   // == one_kernel for INT8
+  auto app_kernel = query_aware_decode_kernel<D, S, false, true, kInt8, kHalf>;
   int st;
   if ((st = allow_lds(loop_kernel, pl.lds_fused)) != TS_OK ||
       (st = allow_lds(one_kernel, pl.lds_fused)) != TS_OK ||
       (st = allow_lds(app_kernel, pl.lds_fused)) != TS_OK)
     return st;
-  const bool fold_append = k_new && !kInt8;
+  const bool fold_append = k_new != nullptr;
   int cap1 = resident_capacity(fold_append ? app_kernel : one_kernel, pl.lds_fused);
   if (cap1 > max_resident) cap1 = max_resident;
   const bool one_unit_each = pl.units * pl.g <= cap1;
@@ -578,14 +626,13 @@ int launch_attention_format(const ts_layout* layout, const AttendParams& a, cons
 }
 
 // Workgroups of the loop-free build with the append folded in that can be
-// resident at once (0: that build does not exist for the format).
+// resident at once.
 template <int kFmt>
 int append_capacity_format(const ts_layout* layout, const Plan& pl) {
   constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
-  if (kInt8) return 0;
   int cap = 0;
 #define TS_CAPACITY(DD, SS) \
-  cap = resident_capacity(query_aware_decode_kernel<DD, SS, false, !kInt8, kInt8, kHalf>, pl.lds_fused)
+  cap = resident_capacity(query_aware_decode_kernel<DD, SS, false, true, kInt8, kHalf>, pl.lds_fused)
   TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_CAPACITY);
 #undef TS_CAPACITY
   return cap;

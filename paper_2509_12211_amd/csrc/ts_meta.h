@@ -160,6 +160,33 @@ __device__ __forceinline__ uint16_t bf16_directed(double x, bool up) {
   return hi;
 }
 
+// The eight codes of a chunk as bytes in channel order.
+__device__ __forceinline__ uint2 i8_chunk_codes(const uint4& c, float scale) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  uint32_t o[2] = {0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = static_cast<uint32_t>(i8_code(bf16_lo(w[i]), scale)) & 0xffu;
+    const uint32_t hi = static_cast<uint32_t>(i8_code(bf16_hi(w[i]), scale)) & 0xffu;
+    o[i >> 1] |= (lo | (hi << 8)) << (16 * (i & 1));
+  }
+  return make_uint2(o[0], o[1]);
+}
+// The dequantised values of a chunk rounded outwards to bf16: lo <= code * scale <= hi.
+__device__ __forceinline__ void i8_chunk_box(const uint4& c, float scale, uint4& lo, uint4& hi) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  uint32_t l[4], h[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const double a = static_cast<double>(i8_code(bf16_lo(w[i]), scale)) * static_cast<double>(scale);
+    const double b = static_cast<double>(i8_code(bf16_hi(w[i]), scale)) * static_cast<double>(scale);
+    l[i] = bf16_directed(a, false) | (static_cast<uint32_t>(bf16_directed(b, false)) << 16);
+    h[i] = bf16_directed(a, true) | (static_cast<uint32_t>(bf16_directed(b, true)) << 16);
+  }
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+}
+
 // One thread per (page, channel): kThreads / D pages per workgroup.  Set-up
 // work (a page is summarised once; appends keep it current), kept plain.
 template <int D>
@@ -222,8 +249,7 @@ static __global__ __launch_bounds__(kThreads) void append_token_i8_kernel(MetaPa
         ka = fmaxf(ka, shfl_xor_f(ka, m));
         va = fmaxf(va, shfl_xor_f(va, m));
       }
-      const float ksc = ka > 0.f ? __fdiv_rn(ka, 127.0f) : 1.0f;
-      const float vsc = va > 0.f ? __fdiv_rn(va, 127.0f) : 1.0f;
+      const float ksc = i8_row_scale(ka), vsc = i8_row_scale(va);
       const size_t tile = ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
       int8_t* k8 = reinterpret_cast<int8_t*>(p.k_pool_w);
       int8_t* v8 = reinterpret_cast<int8_t*>(p.v_pool_w);
@@ -231,14 +257,12 @@ static __global__ __launch_bounds__(kThreads) void append_token_i8_kernel(MetaPa
       for (int i = 0; i < 2; ++i) {
         const int c = lane + 64 * i;
         if (c < D) {
-          const float kq = fminf(fmaxf(rintf(__fdiv_rn(kv[i], ksc)), -127.f), 127.f);
-          const float vq = fminf(fmaxf(rintf(__fdiv_rn(vv[i], vsc)), -127.f), 127.f);
+          const int kq = i8_code(kv[i], ksc), vq = i8_code(vv[i], vsc);
           if (v_new != nullptr) {
             k8[tile + (size_t)slot * D + c] = static_cast<int8_t>(kq);
             v8[tile + (size_t)c * p.S + slot] = static_cast<int8_t>(vq);
           }
-          // (through the integer: a code that rounded to -0.0f must give +0, as the stored byte does)
-          const double kd = static_cast<double>(static_cast<int>(kq)) * static_cast<double>(ksc);
+          const double kd = static_cast<double>(kq) * static_cast<double>(ksc);
           const uint16_t lo = bf16_directed(kd, false), hi = bf16_directed(kd, true);
           const size_t m = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + c;
           if (slot == 0) {

@@ -155,8 +155,9 @@ APPEND8 = {
 @pytest.mark.parametrize("name", list(APPEND8))
 def test_int8_append_quantises_like_the_oracle(oracle, name):
     """ts_append_token_meta on the INT8 cache: codes, scales and the widened boxes are
-    the oracle's, bit for bit; the boxes equal a rebuild; ts_append_and_decode (append
-    kernel + fused kernel) equals the two calls; decode results match the oracle."""
+    the oracle's, bit for bit; the boxes equal a rebuild; ts_append_and_decode (one
+    launch that quantises the token itself) equals the two calls; decode results match
+    the oracle."""
     spec = APPEND8[name]
     print(f"[case] int8 append {name}", flush=True)
     n_new = 36
@@ -170,9 +171,10 @@ def test_int8_append_quantises_like_the_oracle(oracle, name):
         ts.build_page_meta(sess.layout)
         twins.append(sess)
     a, f = twins
-    assert ts.append_and_decode_launches(f.layout, f.w.K_max) == 2
+    assert ts.append_and_decode_launches(f.layout, f.w.K_max) == 1
     units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
     B, Hkv, S, d = spec.B, spec.Hkv, spec.S, spec.d
+    spliced = 0     # (unit, step) pairs whose selection holds the page of the token just appended
     for i in range(n_new):
         lens = a.seq_lens.cpu().numpy().copy()
         omin, omax = wl.bits(a.page_min).copy(), wl.bits(a.page_max).copy()
@@ -202,15 +204,22 @@ def test_int8_append_quantises_like_the_oracle(oracle, name):
             assert np.array_equal(a.w.v_scale[phys, :, slot].cpu().numpy(), vsc[b]), what
             assert np.array_equal(wl.bits(a.page_min[b, :, j]), omin[b, :, j]), what
             assert np.array_equal(wl.bits(a.page_max[b, :, j]), omax[b, :, j]), what
-        # one launch pair == two calls
+        # one launch == two calls
         assert torch.equal(a.seq_lens, f.seq_lens), what
         assert torch.equal(a.w.k_pool, f.w.k_pool) and torch.equal(a.w.v_pool, f.w.v_pool), what
+        assert torch.equal(a.w.k_scale, f.w.k_scale) and torch.equal(a.w.v_scale, f.w.v_scale), what
+        assert np.array_equal(wl.bits(a.page_min), wl.bits(f.page_min)), what
+        assert np.array_equal(wl.bits(a.page_max), wl.bits(f.page_max)), what
         assert torch.equal(a.sel, f.sel) and torch.equal(a.scores, f.scores), what
         assert (a.out - f.out).abs().max().item() <= 1e-6, what
+        sel = f.sel.cpu().numpy().reshape(B, Hkv, -1)
+        spliced += sum(int((sel[b] == int(lens[b]) // S).any(axis=-1).sum())
+                       for b in range(B) if int(lens[b]) // S < f.w.P_max)
         if i in (0, 17, n_new - 1):
             compare_units(oracle, f, units, scale, q_idx=i, what=what)     # includes box == rebuild
     if not spec.L_min:
         assert int(f.seq_lens[0]) == f.w.P_max * S
+    assert spliced > 0      # the attention did take the token from the caller's arrays
 
 
 MANY8 = {
