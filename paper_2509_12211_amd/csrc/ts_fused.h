@@ -260,7 +260,9 @@ query_aware_decode_kernel(FusedParams p) {
           // the tag is fixed by the first unit: the epoch word may already have
           // been advanced (by the workgroup that counted itself in last) when a
           // later unit's loads go out
-          if (tag == 0u) tag = (uint32_t)uniform(epoch_raw) + 1u;
+          // (0 is never a tag: it marks words nobody has written since
+          // ts_workspace_init, so the count skips it when it wraps)
+          if (tag == 0u) tag = max((uint32_t)uniform(epoch_raw) + 1u, 1u);
           L_unit = uniform(L_raw);
           if (app && L_unit / S < Pmax) {  // a sequence with no room left is not extended
             j_new = L_unit / S;

@@ -598,6 +598,37 @@ def test_graph_replays_match_eager(built, splits):
         torch.empty(1 << 20, device=DEV).normal_().sum().item()
 
 
+@pytest.mark.parametrize("splits", [4], indirect=True)
+def test_launch_tag_wraps_past_zero(built, splits):
+    """The words a cluster exchanges carry a 32-bit launch count as their tag, and 0
+    marks a word nobody has written since the workspace was initialised.  A workspace
+    whose count is about to wrap (set by hand here: word 16 of the control block at the
+    head of the workspace) must carry on across the wrap like a fresh one."""
+    print("[case] launch tag wrap", flush=True)
+    spec = wl.WorkloadSpec("wrap", 2, 8, 2, 64, 16, 1500, 12, keys="offset", headroom=64)
+    scale = 1.0 / math.sqrt(spec.d)
+    twins = []
+    for _ in range(2):
+        w = wl.make_workload(spec, DEV, seed=77, n_q=6, n_new=1, poison=0.0)
+        sess = Session(w, poison_meta=False)
+        ts.build_page_meta(sess.layout)
+        twins.append(sess)
+    fresh, old = twins
+    old.ws.view(torch.int32)[16] = -3          # three launches before 2^32
+    torch.cuda.synchronize()
+    for i in range(6):
+        for sess in twins:
+            w = sess.w
+            ts.query_aware_decode(sess.layout, w.q[i], w.topk, w.K_max, scale, sess.out, sess.ws,
+                                  scores_out=sess.scores, sel_out=sess.sel,
+                                  sel_count_out=sess.sel_count)
+        torch.cuda.synchronize()
+        assert ts.workspace_status(fresh.ws) == 0 and ts.workspace_status(old.ws) == 0, f"launch {i}"
+        assert torch.equal(fresh.sel, old.sel) and torch.equal(fresh.scores, old.scores), f"launch {i}"
+        assert torch.equal(fresh.out, old.out), f"launch {i}"
+    assert int(old.ws.view(torch.int32)[16]) == 4 and int(fresh.ws.view(torch.int32)[16]) == 6
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
