@@ -195,6 +195,13 @@ query_aware_decode_kernel(FusedParams p) {
   // first metadata tile) are sent out ahead of everything else: for the first
   // unit right here, before the set-up work that follows, for later units at the
   // end of the unit before.  What they fetch is only looked at inside the loop.
+  // Which pages a member scores: the sequence's groups of PPW consecutive pages
+  // (one wave-wide load each) are dealt out to the cluster's members in turn.
+  // The selection bins the scores over a range it estimates from the member's
+  // own share (see the exchange below), so that share has to be a fair sample
+  // of the sequence; dealing out whole tiles of PPI pages reads 0.3 us faster on
+  // the 16-sequence configuration, but where the scores vary smoothly along the
+  // sequence the few pages that matter then lie in tiles most members never see.
   constexpr int kBtRegs = 8;  // block-table entries per thread fetched through registers
   int L_raw, K_raw, epoch_raw, bt_regs[kBtRegs];
   ScanRegs<D, kHalf> scan;
@@ -220,7 +227,7 @@ query_aware_decode_kernel(FusedParams p) {
     for (int k = 0; k < kBtRegs; ++k)   // no branch around the loads
       bt_regs[k] = bt_row[min((int)threadIdx.x + k * kThreads, Pmax - 1)];
     scan_issue_tile<D, kHalf>(scan, p.page_min + (size_t)uu * Pmax * D, p.page_max + (size_t)uu * Pmax * D,
-                       Pmax, member * kWaves + wave_id());
+                       Pmax, wave_id(), g, member);
   };
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
   TS_MARK(23);
@@ -245,7 +252,7 @@ query_aware_decode_kernel(FusedParams p) {
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
     scan_finish<D, !kLoop, kHalf>(
         scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
-        member * kWaves + wave_id(), g * kWaves, q_stage,
+        wave_id(), kWaves, q_stage,
         [&] {
 #pragma unroll
           for (int k = 0; k < kBtRegs; ++k) {
@@ -305,16 +312,16 @@ query_aware_decode_kernel(FusedParams p) {
           }
         },
         [&](int pg, float s) {
-          if (exchange) {
-            store_agent_tagged(srow + pg, s, tag);
-          } else if (pg < pb_scan) {
+          if (exchange) store_agent_tagged(srow + pg, s, tag);
+          if (pg < pb_scan) {   // (with an exchange: the range of my own share of the scores)
             const uint32_t k = score_key(s);
-            sl.keys[kl.at(pg)] = k;
+            if (!exchange) sl.keys[kl.at(pg)] = k;
             tmin = min(tmin, k);
             tmax = max(tmax, k);
           }
           if (srow_out) srow_out[pg] = s;
-        });
+        },
+        g, member);
     const int L = uniform(L_unit);
     const int Pb = uniform(min(pages_of(L, S), Pmax));
     const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
@@ -328,7 +335,23 @@ query_aware_decode_kernel(FusedParams p) {
 
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
+    const ForcedPages forced = ForcedPages::make(p.keep_first, p.keep_last, Pb);
+    BinMap bins{0.f, 0.f};
     if (exchange) {
+      // The selection's first stage (counting the pages into score bins) is done
+      // here, key by key as the scores come in, instead of in a pass of its own
+      // after them.  The bins need a score range before the first score of the
+      // other members is looked at: the range of this workgroup's own share
+      // (every g-th group of pages: a fair sample), widened; any monotone map
+      // keeps the selection exact.  Each member bins in its own way and all
+      // arrive at the same pages.
+      select_begin(sl, tmin, tmax);
+      __syncthreads();
+      {
+        uint32_t lo_key, hi_key;
+        select_deposited_range(sl, lo_key, hi_key);
+        bins = BinMap::widened(lo_key, hi_key);
+      }
       // every thread polls its own entries of the row until all carry this
       // launch's tag (all loads of a round in flight together; bounded)
       bool expired = false;
@@ -350,17 +373,18 @@ query_aware_decode_kernel(FusedParams p) {
         for (int i = 0; i < 8; ++i) {
           const int j = j0 + i * kThreads;
           if (j < Pb) {
-            const uint32_t k = score_key(__uint_as_float((uint32_t)v[i]));
+            const bool always = j < forced.first || j >= forced.last_begin;
+            const uint32_t k = always ? kForcedKey : score_key(__uint_as_float((uint32_t)v[i]));
             sl.keys[kl.at(j)] = k;
-            tmin = min(tmin, k);
-            tmax = max(tmax, k);
+            atomicAdd(&sl.hist[bin_slot_index(bins.slot<true>(k))], 1u);
           }
         }
       }
       if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
       TS_MARK(3);
+    } else {
+      select_begin(sl, tmin, tmax);
     }
-    select_begin(sl, tmin, tmax);
     __syncthreads();
     TS_MARK(4);
     // The new token lands in its pool slot (one member's first lanes; the
@@ -424,11 +448,12 @@ query_aware_decode_kernel(FusedParams p) {
     if (sel_row)
       for (int i = Kb + threadIdx.x; i < at.Kmax; i += kThreads) sel_row[i] = -1;
     if (p.sel_count && member == 0 && h == 0 && threadIdx.x == 0) p.sel_count[b] = Kb;
-    select_topk_lds(sl, kl, Pb, Kb, ForcedPages::make(p.keep_first, p.keep_last, Pb),
-                    [&](int rank, int page) {
+    auto keep_page = [&](int rank, int page) {
       if (rank >= c0 && rank < c0 + count) my_sel[rank - c0] = page;
       if (sel_row) sel_row[rank] = page;
-    });
+    };
+    if (exchange) select_topk_lds<true>(sl, kl, Pb, Kb, forced, keep_page, bins);
+    else select_topk_lds<false>(sl, kl, Pb, Kb, forced, keep_page);
     __syncthreads();
     TS_MARK(5);
     // The workgroup that counted itself in last knows that every other one has

@@ -92,9 +92,11 @@ struct ScoreLanes {
   }
 };
 
-// The metadata rows one wave has in flight: U wave-wide loads of min and of max
-// covering pages [base, base + PPI).  Rows up to Pmax are always readable
-// (whatever they hold), so the loads do not wait for the sequence length.
+// The metadata rows one wave has in flight: U wave-wide loads of min and of max,
+// each covering PPW consecutive pages, the u-th starting at page base + u * rstep
+// (rstep = PPW: the pages [base, base + PPI); larger when the groups of PPW pages
+// are dealt out in turn to several workgroups).  Rows up to Pmax are always
+// readable (whatever they hold), so the loads do not wait for the sequence length.
 template <int D, bool kHalf = false>
 struct MetaTile {
   static constexpr int U = ScoreLanes<D, kHalf>::U;
@@ -103,12 +105,12 @@ struct MetaTile {
   // Plimit >= 1.  Pages at or past Plimit read row Plimit - 1 instead (no branch
   // around the loads); reduce() never reports them.
   __device__ __forceinline__ void load(const uint16_t* pmin_u, const uint16_t* pmax_u, int base,
-                                       int Plimit) {
-    constexpr int LPR = ScoreLanes<D, kHalf>::LPR, PPW = ScoreLanes<D, kHalf>::PPW;
+                                       int Plimit, int rstep) {
+    constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int pg = min(base + u * PPW + prow, Plimit - 1);
+      const int pg = min(base + u * rstep + prow, Plimit - 1);
       mn[u] = *reinterpret_cast<const uint4*>(pmin_u + (size_t)pg * D + cg * 8);
       mx[u] = *reinterpret_cast<const uint4*>(pmax_u + (size_t)pg * D + cg * 8);
     }
@@ -119,12 +121,12 @@ struct MetaTile {
   // lane holds (a token appended in the same launch).
   template <typename Patch, typename Sink>
   __device__ __forceinline__ void reduce(const ScoreLanes<D, kHalf>& ql, int base, int Pb, int Pmax,
-                                         Patch patch, Sink sink) {
-    constexpr int LPR = ScoreLanes<D, kHalf>::LPR, PPW = ScoreLanes<D, kHalf>::PPW;
+                                         int rstep, Patch patch, Sink sink) {
+    constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int pg = base + u * PPW + prow;
+      const int pg = base + u * rstep + prow;
       patch(mn[u], mx[u], pg);
       const double s = group_sum_f64<LPR>(ql.row_partial(mn[u], mx[u]));
       if (cg == 0 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
@@ -136,8 +138,11 @@ struct MetaTile {
 // first loads of a unit as early as it likes (before unrelated set-up work):
 // scan_issue sends out the query rows and the wave's first metadata tile,
 // scan_finish does everything else.  A wave's iterations are it = first_iter,
-// first_iter + iter_stride, ..., each covering ScoreLanes<D, kHalf>::PPI consecutive
-// pages.
+// first_iter + iter_stride, ..., each covering U groups of PPW consecutive pages
+// (PPI pages in all).  With gs == 1 these are the pages [it * PPI, (it + 1) * PPI);
+// in general the sequence's groups of PPW pages are dealt out in turn to gs
+// parties, and the caller, party goff, gets the groups (it * U + u) * gs + goff:
+// its share is then spread as evenly as can be over the whole sequence.
 template <int D, bool kHalf = false>
 struct ScanRegs {
   typename ScoreLanes<D, kHalf>::QueryRegs q;
@@ -150,8 +155,10 @@ __device__ __forceinline__ void scan_issue_query(ScanRegs<D, kHalf>& r, const ui
 }
 template <int D, bool kHalf>
 __device__ __forceinline__ void scan_issue_tile(ScanRegs<D, kHalf>& r, const uint16_t* pmin_u,
-                                                const uint16_t* pmax_u, int Pmax, int first_iter) {
-  r.tile.load(pmin_u, pmax_u, first_iter * ScoreLanes<D, kHalf>::PPI, Pmax);
+                                                const uint16_t* pmax_u, int Pmax, int first_iter,
+                                                int gs = 1, int goff = 0) {
+  constexpr int PPW = ScoreLanes<D, kHalf>::PPW, PPI = ScoreLanes<D, kHalf>::PPI;
+  r.tile.load(pmin_u, pmax_u, first_iter * PPI * gs + goff * PPW, Pmax, PPW * gs);
 }
 
 // `after_query` runs once the query is in registers and returns Pb.  Must be
@@ -168,8 +175,10 @@ template <int D, bool kBranchless, bool kHalf, typename AfterQuery, typename Pat
 __device__ __forceinline__ void scan_finish(ScanRegs<D, kHalf>& r, const uint16_t* pmin_u,
                                             const uint16_t* pmax_u, int G, int Pmax, int first_iter,
                                             int iter_stride, unsigned char* q_stage,
-                                            AfterQuery after_query, Patch patch, Sink sink) {
-  constexpr int PPI = ScoreLanes<D, kHalf>::PPI;
+                                            AfterQuery after_query, Patch patch, Sink sink,
+                                            int gs = 1, int goff = 0) {
+  constexpr int PPW = ScoreLanes<D, kHalf>::PPW, PPI = ScoreLanes<D, kHalf>::PPI;
+  const int rstep = PPW * gs;
   TS_MARK(19);
   ScoreLanes<D, kHalf> ql;
   ql.finish_query(r.q, G, q_stage);
@@ -177,13 +186,13 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D, kHalf>& r, const uint16_
   const int Pb = after_query();
   // only the first tile is fetched blind; later ones stop at the sequence's
   // last page (pages >= Pb still get their -inf through the sink)
-  int base = first_iter * PPI;
+  int base = first_iter * PPI * gs + goff * PPW;   // first page of the tile's first group
   while (base < Pmax) {
-    const int next = base + iter_stride * PPI;
+    const int next = base + iter_stride * PPI * gs;
     MetaTile<D, kHalf> cur = r.tile;
-    if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1));
-    else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb);
-    cur.reduce(ql, base, Pb, Pmax, patch, sink);
+    if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1), rstep);
+    else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb, rstep);
+    cur.reduce(ql, base, Pb, Pmax, rstep, patch, sink);
     base = next;
   }
 }

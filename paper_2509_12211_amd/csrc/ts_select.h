@@ -103,19 +103,79 @@ __device__ __forceinline__ int bin_slot_index(int k) {
 }
 static_assert(kRadixBins == 64 * 32, "slot layout written for 64 lanes x 32 slots");
 
+// Clears the bins and the candidate count; all threads, a barrier before the
+// first count.
+__device__ __forceinline__ void select_clear(const SelectLds& L) {
+  reinterpret_cast<uint4*>(L.hist)[threadIdx.x] = make_uint4(0, 0, 0, 0);
+  static_assert(kRadixBins == 4 * kThreads, "one 16-byte store per thread clears the bins");
+  if (threadIdx.x == 0) L.red[40] = 0;
+}
 // First half of the selection, to be called by all threads BEFORE the barrier
 // that makes the keys visible: clears the bins and deposits each wave's share
 // of the key range.  tmin / tmax: this thread's share of the min / max over ALL
 // keys (any partition over the threads; 0xffffffff / 0 if it saw none).
 __device__ __forceinline__ void select_begin(const SelectLds& L, uint32_t tmin, uint32_t tmax) {
-  reinterpret_cast<uint4*>(L.hist)[threadIdx.x] = make_uint4(0, 0, 0, 0);
-  static_assert(kRadixBins == 4 * kThreads, "one 16-byte store per thread clears the bins");
+  select_clear(L);
   const uint32_t a = wave_min_u32(tmin), b = wave_max_u32(tmax);
   if (lane_id() == 0) {
     L.red[16 + wave_id()] = (int)a;
     L.red[24 + wave_id()] = (int)b;
-    if (wave_id() == 0) L.red[40] = 0;
   }
+}
+
+// Stage 1 of the selection spreads the pages over the kRadixBins bins linearly in
+// score: bin = floor((s - lo) * scale), clamped to the bins.  ANY lo and scale >= 0
+// give a monotone map (bins respect the order of the keys), which is all the
+// selection needs to be exact; they only decide how evenly the pages spread.
+// With lo = s_min and scale = 2047 / (s_max - s_min) the scores of a unit spread
+// evenly whatever their sign or exponent range.  kForcedKey decodes to a quiet
+// NaN, which fminf drops in favour of 2047 (IEEE minNum, v_min_f32 in the
+// kernels' IEEE mode): the always-kept pages land in slot 0, the slot of the
+// highest scores, with no test of their own (the parity tests with such pages
+// cover it).
+struct BinMap {
+  float lo, scale;
+  // slot of a key; 0 = highest scores (see bin_slot_index).  kClampBelow: scores
+  // below lo occur (only with an estimated range).
+  template <bool kClampBelow>
+  __device__ __forceinline__ int slot(uint32_t k) const {
+    float x = fminf((key_score(k) - lo) * scale, 2047.0f);
+    if (kClampBelow) x = fmaxf(x, 0.f);
+    return kRadixBins - 1 - (int)x;
+  }
+  // the exact range [kmin, kmax] of the keys (all equal: everything in one bin)
+  __device__ __forceinline__ static BinMap exact(uint32_t kmin, uint32_t kmax) {
+    BinMap m;
+    m.lo = key_score(kmin);
+    m.scale = kmax > kmin ? 2047.0f / (key_score(kmax) - m.lo) : 0.f;
+    return m;
+  }
+  // A range estimated from a SAMPLE of the keys: [kmin, kmax] of the sample
+  // widened by a quarter of its width on either side; keys outside fall into the
+  // end bins.  No sample, or a single value: everything goes to one bin, and the
+  // selection's exact passes sort it out.
+  __device__ __forceinline__ static BinMap widened(uint32_t kmin, uint32_t kmax) {
+    BinMap m;
+    const float a = key_score(kmin), b = key_score(kmax), w = b - a;
+    const bool usable = kmax > kmin && w > 0.f && w < 1e37f;
+    m.lo = usable ? a - 0.25f * w : 0.f;
+    m.scale = usable ? 2047.0f / (1.5f * w) : 0.f;
+    return m;
+  }
+};
+
+// The key range the waves deposited with select_begin (a barrier in between).
+__device__ __forceinline__ void select_deposited_range(const SelectLds& L, uint32_t& kmin,
+                                                       uint32_t& kmax) {
+  kmin = 0xffffffffu;
+  kmax = 0u;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    kmin = min(kmin, (uint32_t)L.red[16 + w]);
+    kmax = max(kmax, (uint32_t)L.red[24 + w]);
+  }
+  kmin = (uint32_t)uniform((int)kmin);
+  kmax = (uint32_t)uniform((int)kmax);
 }
 
 // Second half: keeps the Kb largest of the Pb keys in L.keys (ties: lower page
@@ -136,9 +196,17 @@ __device__ __forceinline__ void select_begin(const SelectLds& L, uint32_t tmin, 
 //
 // fp: the always-kept pages (their keys become kForcedKey: linear_slot puts them
 // into the top bin, everything after that works on the integer keys).
-template <typename Emit>
+//
+// kCounted = true: the caller has already done stage 1's counting while it filled
+// in the keys (into bins cleared by select_begin a barrier earlier), with the bin
+// map `counted` and BinMap::slot<true>, and has given the always-kept pages the
+// key kForcedKey itself.  The map may come from an estimate of the range: if the
+// cut then falls into an end bin crowded with the keys outside the estimate,
+// stage 2b's exact passes resolve it like any other crowded bin.
+template <bool kCounted = false, typename Emit>
 __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLayout& kl, int Pb,
-                                                int Kb, const ForcedPages& fp, Emit emit) {
+                                                int Kb, const ForcedPages& fp, Emit emit,
+                                                const BinMap counted = BinMap{0.f, 0.f}) {
   const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
   static_assert(kWaves <= 8, "red[] layout holds 8 wave slots");
   constexpr int kBatch = 8;  // LDS reads issued together
@@ -153,7 +221,7 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     for (int r = tid; r < Kb; r += kThreads) emit(r, r < fp.first ? r : fp.last_begin + (r - fp.first));
     return;
   }
-  const bool any_forced = uniform(fp.count) != 0;
+  const bool any_forced = !kCounted && uniform(fp.count) != 0;
   if (any_forced) {   // (uniform) the keys of the always-kept pages, over what the caller wrote
     for (int j = tid; j < fp.first; j += kThreads) L.keys[kl.at(j)] = kForcedKey;
     for (int j = fp.last_begin + tid; j < Pb; j += kThreads) L.keys[kl.at(j)] = kForcedKey;
@@ -227,24 +295,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   };
 
   // ---- stage 1: linear bins over [s_min, s_max] ------------------------------
-  uint32_t kmin = 0xffffffffu, kmax = 0u;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
-    kmin = min(kmin, (uint32_t)L.red[16 + w]);
-    kmax = max(kmax, (uint32_t)L.red[24 + w]);
-  }
-  kmin = (uint32_t)uniform((int)kmin);
-  kmax = (uint32_t)uniform((int)kmax);
+  // (counted by the caller: the keys' range is not known here, and need not be)
+  uint32_t kmin = 0u, kmax = 0xffffffffu;
+  if (!kCounted) select_deposited_range(L, kmin, kmax);
   TS_MARK(10);
-  const float smin = key_score(kmin);
-  const float scale = kmax > kmin ? 2047.0f / (key_score(kmax) - smin) : 0.f;
-  // 0 = highest scores.  kForcedKey decodes to a quiet NaN, which fminf drops in
-  // favour of 2047 (IEEE minNum, v_min_f32 in the kernels' IEEE mode): the
-  // always-kept pages land in slot 0 with no test of their own (the parity tests
-  // with such pages cover it).
-  auto linear_slot = [&](uint32_t k) {
-    return kRadixBins - 1 - (int)fminf((key_score(k) - smin) * scale, 2047.0f);
-  };
+  const BinMap bins = kCounted ? counted : BinMap::exact(kmin, kmax);
+  auto linear_slot = [&](uint32_t k) { return bins.template slot<kCounted>(k); };
   int need = Kb, cut_slot = 0;
   // how the pages at the cut are told apart from those above it
   enum { kWholeSlot, kThreshold, kRadix } mode = kWholeSlot;
@@ -253,8 +309,10 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   uint32_t clo = kmin, chi = kmax, base = 0u;  // kRadix
   int bits = 0;
   if (kmax > kmin) {
-    for_my_keys([&](uint32_t k, int) { atomicAdd(&L.hist[bin_slot_index(linear_slot(k))], 1u); });
-    __syncthreads();
+    if (!kCounted) {
+      for_my_keys([&](uint32_t k, int) { atomicAdd(&L.hist[bin_slot_index(linear_slot(k))], 1u); });
+      __syncthreads();
+    }
     TS_MARK(11);
     int above, cnt;
     find_cut(need, cut_slot, above, cnt);

@@ -598,6 +598,63 @@ def test_graph_replays_match_eager(built, splits):
         torch.empty(1 << 20, device=DEV).normal_().sum().item()
 
 
+@pytest.mark.parametrize("profile", ["outlier_group", "hidden_peak", "ramp", "all_equal"])
+@pytest.mark.parametrize("splits", [4, 16], indirect=True)
+def test_selection_where_a_member_misjudges_the_score_range(oracle, built, splits, profile):
+    """With a cluster, every member bins the scores over a range estimated from its own
+    share of the pages (every g-th group of eight).  Boxes are overwritten so that page
+    j scores exactly G * s_j, with profiles chosen so that some members misjudge the
+    range badly: one group of very large scores that a single member sees (its bins
+    then lump all other pages together, with heavy ties at the cut); forty large scores
+    in groups only two members see (for the others they crowd into the top bin, and the
+    cut falls inside it); a ramp; all scores equal.  Every member must still arrive at
+    the exact top-K (ties to the lower page), or pages would be attended twice or not
+    at all: scores, selection and output are compared with the oracle's."""
+    print(f"[case] misjudged range {profile} splits={splits}", flush=True)
+    spec = wl.WorkloadSpec("range", 2, 4, 2, 64, 16, 16 * 600, 32, headroom=0)
+    w = wl.make_workload(spec, DEV, seed=31, n_q=1, n_new=1, poison=0.0)
+    sess = Session(w, poison_meta=False)
+    ts.build_page_meta(sess.layout)
+    P, G, g = w.P_max, spec.Hq // spec.Hkv, splits
+    rng = np.random.default_rng(3)
+    s = rng.integers(-8, 9, size=P).astype(np.float32)           # heavy ties
+    topk = 32
+    if profile == "outlier_group":
+        first = 8 * (g - 1)                                       # one group of the last member's
+        s[first:first + 8] = 200 + np.arange(8)
+    elif profile == "hidden_peak":
+        groups = [gi for gi in range(P // 8) if gi % g in (0, 1)][3:8]   # five groups, two members
+        for gi in groups:
+            s[8 * gi:8 * gi + 8] = 100 + (np.arange(8) % 7)
+        topk = 20
+    elif profile == "ramp":
+        s = (np.arange(P) // 3).astype(np.float32)               # top pages all at the end
+    else:
+        s[:] = 3.0
+    box = torch.zeros((P, spec.d), dtype=torch.float32)
+    box[:, 0] = torch.from_numpy(s)
+    box = box.to(sess.page_min.dtype).to(DEV)
+    sess.page_min[:] = box[None, None]
+    sess.page_max[:] = box[None, None]
+    q = w.q[0].clone()
+    q[:, :, 0] = 1.0                                             # score = sum over the group of s_j
+    scale = 1.0 / math.sqrt(spec.d)
+    ts.query_aware_decode(sess.layout, q, topk, w.K_max, scale, sess.out, sess.ws,
+                          scores_out=sess.scores, sel_out=sess.sel, sel_count_out=sess.sel_count)
+    torch.cuda.synchronize()
+    assert ts.workspace_status(sess.ws) == 0
+    lens = sess.seq_lens.cpu().numpy()
+    scores = sess.scores.cpu().numpy()
+    assert np.array_equal(scores, np.broadcast_to(G * s, scores.shape)), "scores"
+    sel, cnt, _ = oracle.select_topk_pages(scores.astype(np.float64), lens, spec.S, topk, w.K_max)
+    assert np.array_equal(sess.sel_count.cpu().numpy(), cnt)
+    assert np.array_equal(sess.sel.cpu().numpy(), sel), "selection"
+    K, V = wl.logical_kv(w)
+    ref = oracle.sparse_decode_attention(wl.bits(q), wl.bits(K), wl.bits(V), sel, cnt, lens, spec.S,
+                                         scale)
+    assert_out_close(sess.out.cpu().numpy(), ref, what=profile)
+
+
 @pytest.mark.parametrize("splits", [4], indirect=True)
 def test_launch_tag_wraps_past_zero(built, splits):
     """The words a cluster exchanges carry a 32-bit launch count as their tag, and 0
