@@ -157,7 +157,11 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 // two waves per SIMD: saying so lets the compiler schedule for latency with the
 // registers of that occupancy instead of saving registers for waves that never
 // come (measured: 0.5 us of 26 on the 16-sequence configuration).
-template <int D, int S, bool kLoop, bool kApp, bool kInt8 = false, bool kHalf = false>
+//
+// kCluster says whether a unit is shared by several workgroups (p.g > 1): the
+// build for one workgroup per unit carries nothing of the exchange, the build
+// for clusters nothing of the selection's stand-alone first stages.
+template <int D, int S, bool kLoop, bool kApp, bool kInt8, bool kHalf, bool kCluster>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 query_aware_decode_kernel(FusedParams p) {
   static_assert(!(kLoop && kApp), "the append is folded only into the loop-free build");
@@ -166,8 +170,8 @@ query_aware_decode_kernel(FusedParams p) {
   TS_MARK_INIT();
   TS_MARK(22);
   const AttendParams& at = p.at;
-  const int g = p.g, G = at.G, Pmax = at.Pmax;
-  const int member = blockIdx.x % g;
+  const int g = kCluster ? p.g : 1, G = at.G, Pmax = at.Pmax;
+  const int member = kCluster ? blockIdx.x % g : 0;
   const int n_clusters = gridDim.x / g;
   const SelectLds sl = carve_select(smem, Pmax);
   const size_t sel_bytes = select_lds_bytes(Pmax);
@@ -176,7 +180,7 @@ query_aware_decode_kernel(FusedParams p) {
   int32_t* my_sel = bt_lds + Pmax;  // [chunk]
   unsigned char* q_stage = reinterpret_cast<unsigned char*>(bt_lds) +
                            ((size_t)Pmax * 4 + (size_t)at.chunk * 4 + 15) / 16 * 16;
-  const bool exchange = g > 1;
+  constexpr bool exchange = kCluster;
   // With one workgroup per unit and more units than workgroups (long ragged
   // batches) the units are handed out from a counter as workgroups become
   // free: a unit then takes tens of microseconds, so the counter is not
@@ -584,15 +588,16 @@ static int resident_capacity(KernelT kernel, size_t lds) {
 // of its own in front of it: the looping build has no registers to spare for
 // it, and against hundreds of microseconds the extra launch does not count.
 // max_resident: workgroups the launch may count on being resident together.
-template <int D, int S, int kFmt>
+// kCluster: pl.g > 1.
+template <int D, int S, int kFmt, bool kCluster>
 static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Plan& pl,
                               const void* k_new, const void* v_new, int max_resident,
                               void* stream) {
   hipStream_t s = (hipStream_t)stream;
   constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
-  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8, kHalf>;
-  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8, kHalf>;
-  auto app_kernel = query_aware_decode_kernel<D, S, false, true, kInt8, kHalf>;
+  auto loop_kernel = query_aware_decode_kernel<D, S, true, false, kInt8, kHalf, kCluster>;
+  auto one_kernel = query_aware_decode_kernel<D, S, false, false, kInt8, kHalf, kCluster>;
+  auto app_kernel = query_aware_decode_kernel<D, S, false, true, kInt8, kHalf, kCluster>;
   int st;
   if ((st = allow_lds(loop_kernel, pl.lds_fused)) != TS_OK ||
       (st = allow_lds(one_kernel, pl.lds_fused)) != TS_OK ||
@@ -628,8 +633,11 @@ template <int kFmt>
 int launch_fused_format(const ts_layout* layout, FusedParams& p, const Plan& pl, const void* k_new,
                         const void* v_new, int max_resident, void* stream) {
   int st = TS_ERR_UNSUPPORTED;
-#define TS_LAUNCH_FUSED(DD, SS) \
-  st = launch_fused_shape<DD, SS, kFmt>(layout, p, pl, k_new, v_new, max_resident, stream)
+#define TS_LAUNCH_FUSED(DD, SS)                                                                     \
+  st = pl.g > 1 ? launch_fused_shape<DD, SS, kFmt, true>(layout, p, pl, k_new, v_new, max_resident, \
+                                                         stream)                                    \
+                : launch_fused_shape<DD, SS, kFmt, false>(layout, p, pl, k_new, v_new,              \
+                                                          max_resident, stream)
   TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_LAUNCH_FUSED);
 #undef TS_LAUNCH_FUSED
   return st;
@@ -658,8 +666,11 @@ template <int kFmt>
 int append_capacity_format(const ts_layout* layout, const Plan& pl) {
   constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
   int cap = 0;
-#define TS_CAPACITY(DD, SS) \
-  cap = resident_capacity(query_aware_decode_kernel<DD, SS, false, true, kInt8, kHalf>, pl.lds_fused)
+#define TS_CAPACITY(DD, SS)                                                                        \
+  cap = pl.g > 1 ? resident_capacity(query_aware_decode_kernel<DD, SS, false, true, kInt8, kHalf, true>, \
+                                     pl.lds_fused)                                                 \
+                 : resident_capacity(query_aware_decode_kernel<DD, SS, false, true, kInt8, kHalf, false>, \
+                                     pl.lds_fused)
   TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_CAPACITY);
 #undef TS_CAPACITY
   return cap;
