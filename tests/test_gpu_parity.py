@@ -409,6 +409,11 @@ def test_many_units_loop_build(oracle, built, name, fmt):
         else:
             sess.fused(scale, q_idx=i)
         compare_units(oracle, sess, units, scale, q_idx=i, what=f"{name} launch {i}")
+        # units are handed out longest sequence first: every one of them must have been
+        # (the buffers start out as NaN / -7)
+        assert torch.isfinite(sess.out).all() and int(sess.sel[:, :, 0].min()) >= 0
+        sess.out.fill_(float("nan"))
+        sess.sel.fill_(-7)
 
 
 def test_query_sums_read_back_through_one_hot_boxes(built):
