@@ -121,7 +121,10 @@ typedef struct ts_layout {
    * quantises the bf16 token: scale = max_c |x_c| / 127 (1 for a zero vector),
    * code = x_c / scale rounded half to even, all in fp32; with v_new == NULL only
    * the box is widened, by the key so quantised.  ts_append_and_decode does the
-   * same quantisation inside its launch. */
+   * same quantisation inside its launch.  The attention over an INT8 cache
+   * multiplies in IEEE half: the bf16 queries are converted (exactly, for
+   * magnitudes from 2^-14 to 65504; smaller ones lose low bits, larger ones are
+   * taken as 65504), the int8 codes are exact. */
   int32_t kv_format;
   float* k_scale;
   float* v_scale;

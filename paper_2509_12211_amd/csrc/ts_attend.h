@@ -190,11 +190,24 @@ __device__ __forceinline__ void load_small_pages(PageFrag<D, 16>& f, const uint1
 
 // ---------------------------------------------------------------------------
 // INT8 cache: the same fragments fetched as int8 (half the bytes) together with
-// the per-token scales, and expanded to the bf16 MFMA operands in registers.
-// An int8 value is a bf16 number, so the products are those of the exact
-// integers; the token's scale multiplies the logit (K) and the softmax weight
-// (V) afterwards.
+// the per-token scales, and expanded to 16-bit MFMA operands in registers; the
+// token's scale multiplies the logit (K) and the softmax weight (V) afterwards.
+//
+// The operands are IEEE halves holding code + kI8Bias: in [1024, 2048) a half
+// has a step of 1, so the half of 1024 + u (u = code + 128, the byte with its top
+// bit flipped) is the bit pattern 0x6400 | u, and four codes become four operands
+// with three byte-shuffling instructions and no conversion (against eight for
+// converting each code to a float and packing pairs: the expansion is what bounds
+// this path on large batches).  The products stay exact (11-bit x 11-bit
+// significands in an fp32 accumulator); the bias is taken out again afterwards:
+//   sum_c (code_c + B) q_c  =  sum_c code_c q_c + B sum_c q_c     (logits)
+//   sum_t (code_t + B) p_t  =  sum_t code_t p_t + B sum_t p_t     (output)
+// with sum_c q_c once per unit and sum_t p_t carried along with the softmax sum.
+// The queries are converted from bf16 to half for this (exact for magnitudes
+// from 2^-14 to 65504; smaller ones lose low bits to the subnormals, larger ones
+// stop at 65504).
 // ---------------------------------------------------------------------------
+constexpr float kI8Bias = 1152.0f;   // 1024 + 128
 template <int D, int F>
 struct PageFrag8 {
   static constexpr int NT = F / 16;
@@ -205,11 +218,11 @@ struct PageFrag8 {
   float4 ks[NT], vs[NT]; // scales of this lane's four tokens of tile t
 };
 
-// bytes b, b + 1 of w as two bf16 numbers
-__device__ __forceinline__ uint32_t i8_pair_to_bf16(uint32_t w, int b) {
-  const float lo = (float)(int)(int8_t)(w >> (8 * b));
-  const float hi = (float)(int)(int8_t)(w >> (8 * b + 8));
-  return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
+// bytes b, b + 1 (b = 0 or 2) of x as two biased halves; x: four codes with their
+// top bits flipped
+__device__ __forceinline__ uint32_t i8_pair_to_half(uint32_t x, int b) {
+  // v_perm_b32: result byte i = byte sel[i] of {0x64646464 (4..7), x (0..3)}
+  return __builtin_amdgcn_perm(0x64646464u, x, b == 0 ? 0x04010400u : 0x04030402u);
 }
 
 template <int D, int F>
@@ -217,13 +230,16 @@ __device__ __forceinline__ void expand_frag(const PageFrag8<D, F>& r, PageFrag<D
 #pragma unroll
   for (int t = 0; t < PageFrag<D, F>::NT; ++t) {
 #pragma unroll
-    for (int i = 0; i < PageFrag<D, F>::KQ; ++i)
-      f.k[t][i] = make_uint4(i8_pair_to_bf16(r.k[t][2 * i], 0), i8_pair_to_bf16(r.k[t][2 * i], 2),
-                             i8_pair_to_bf16(r.k[t][2 * i + 1], 0),
-                             i8_pair_to_bf16(r.k[t][2 * i + 1], 2));
+    for (int i = 0; i < PageFrag<D, F>::KQ; ++i) {
+      const uint32_t a = r.k[t][2 * i] ^ 0x80808080u, b = r.k[t][2 * i + 1] ^ 0x80808080u;
+      f.k[t][i] = make_uint4(i8_pair_to_half(a, 0), i8_pair_to_half(a, 2), i8_pair_to_half(b, 0),
+                             i8_pair_to_half(b, 2));
+    }
 #pragma unroll
-    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb)
-      f.v[t][cb] = make_uint2(i8_pair_to_bf16(r.v[t][cb], 0), i8_pair_to_bf16(r.v[t][cb], 2));
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) {
+      const uint32_t a = r.v[t][cb] ^ 0x80808080u;
+      f.v[t][cb] = make_uint2(i8_pair_to_half(a, 0), i8_pair_to_half(a, 2));
+    }
   }
 }
 
@@ -351,13 +367,13 @@ struct TokenPatch {
 
 // The same for the INT8 cache: the rows are quantised here (scale = max |x| / 127
 // over the row, code = x / scale rounded half to even), the codes spliced in as
-// the bf16 integers the expanded fragments hold and the two scales put where the
+// the biased halves the expanded fragments hold and the two scales put where the
 // fragment keeps the token's.  To be called by a whole wave.
 template <int D, int F>
 struct TokenPatch8 : TokenPatch<D, F> {
   float ksc, vsc;
-  __device__ __forceinline__ static uint32_t code_bf16(float x, float scale) {
-    return __float_as_uint(static_cast<float>(i8_code(x, scale))) >> 16;   // exact: |code| <= 127
+  __device__ __forceinline__ static uint32_t code_half(float x, float scale) {
+    return 0x6400u | (static_cast<uint32_t>(i8_code(x, scale) + 128) & 0xffu);   // half of code + kI8Bias
   }
   __device__ __forceinline__ void load(const NewToken& nt) {
     TokenPatch<D, F>::load(nt);
@@ -380,11 +396,11 @@ struct TokenPatch8 : TokenPatch<D, F> {
       uint32_t o[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        o[e] = code_bf16(bf16_lo(w[e]), ksc) | (code_bf16(bf16_hi(w[e]), ksc) << 16);
+        o[e] = code_half(bf16_lo(w[e]), ksc) | (code_half(bf16_hi(w[e]), ksc) << 16);
       this->k[i] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 #pragma unroll
-    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) this->v[cb] = code_bf16(bf16_lo(this->v[cb]), vsc);
+    for (int cb = 0; cb < PageFrag<D, F>::NCB; ++cb) this->v[cb] = code_half(bf16_lo(this->v[cb]), vsc);
   }
   // the token's scales, where the fragment holds them (x as in apply)
   __device__ __forceinline__ void apply_scales(float4 (&ks)[PageFrag<D, F>::NT],
@@ -410,10 +426,12 @@ __device__ __forceinline__ float log_sum_exp(float m, float l) {
 template <int D>
 struct WaveAcc {
   float m, l;  // running max (log2 domain) and this lane's share of the running sum
+  float lp;    // INT8 cache: this lane's share of the sum of the weights that went into P.V
   float4_t o[D / 16];
   __device__ __forceinline__ void init() {
     m = -1e30f;
     l = 0.f;
+    lp = 0.f;
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) o[i] = float4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -440,14 +458,19 @@ __device__ __forceinline__ void load_q_frag(short4_t (&qf)[D / 16], const uint16
 // Bit x of `vmask` says whether fragment token x exists (tokens past the end of
 // the sequence, and the tokens of a missing page, are masked).
 //
-// kScaled (INT8 cache): ks[t] / vs[t] hold the scales of this lane's four tokens of
-// tile t; a logit is multiplied by its token's key scale, and a softmax weight by
-// its token's value scale on its way into the P.V product (not in the running sum).
+// kScaled (INT8 cache): the operands are biased halves (see kI8Bias; qf then holds
+// halves too, qbias = kI8Bias * the sum of this lane's query row).  ks[t] / vs[t]
+// hold the scales of this lane's four tokens of tile t; a logit is multiplied by
+// its token's key scale, and a softmax weight by its token's value scale on its
+// way into the P.V product (not in the running sum); the sum of those weights is
+// kept in a.lp for the caller to take the bias out of the output.
 template <int D, int F, bool kScaled = false, bool kHalf = false>
 __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short4_t (&qf)[D / 16],
                                             uint32_t vmask, float scale_log2, WaveAcc<D>& a,
-                                            const float4* ks = nullptr, const float4* vs = nullptr) {
+                                            const float4* ks = nullptr, const float4* vs = nullptr,
+                                            float qbias = 0.f) {
   constexpr int NT = PageFrag<D, F>::NT, NCB = PageFrag<D, F>::NCB;
+  constexpr bool kH = kHalf || kScaled;   // the MFMA's 16-bit operand type
   const int kb = lane_id() >> 4;
   float4_t sc[NT];
   float mx = -INFINITY;
@@ -457,14 +480,14 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
     sc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < D / 32; ++i) {
-      sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
-      sc[t] = mfma16<kHalf>(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
+      sc[t] = mfma16<kH>(as_short4(f.k[t][i].x, f.k[t][i].y), qf[2 * i], sc[t]);
+      sc[t] = mfma16<kH>(as_short4(f.k[t][i].z, f.k[t][i].w), qf[2 * i + 1], sc[t]);
     }
     float kst[4] = {1.f, 1.f, 1.f, 1.f};
     if (kScaled) { kst[0] = ks[t].x; kst[1] = ks[t].y; kst[2] = ks[t].z; kst[3] = ks[t].w; }
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-      sc[t][v] = (kScaled ? sc[t][v] * kst[v] : sc[t][v]) * scale_log2;
+      sc[t][v] = (kScaled ? (sc[t][v] - qbias) * kst[v] : sc[t][v]) * scale_log2;
     if (partial) {   // (uniform) a fragment with all its tokens, the common case, masks nothing
       const uint32_t mine = vmask >> tile_token<F>(t, 4 * kb);   // this lane's four tokens
 #pragma unroll
@@ -479,6 +502,7 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
   a.m = m_new;
   a.l *= alpha;
+  if (kScaled) a.lp *= alpha;
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) a.o[cb] *= alpha;
 #pragma unroll
@@ -494,11 +518,14 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
       float pv = __builtin_amdgcn_exp2f(sc[t][v] - m_new);
       a.l += pv;
       // (a slot without a token may hold any scale: its weight is zero, keep it zero)
-      if (kScaled) pv = (mine >> v) & 1u ? pv * vst[v] : 0.f;
+      if (kScaled) {
+        pv = (mine >> v) & 1u ? pv * vst[v] : 0.f;
+        a.lp += pv;
+      }
       pw[v] = pv;
     }
     short4_t ph, pl;
-    split_weights<kHalf>(pw, ph, pl);
+    split_weights<kH>(pw, ph, pl);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       uint32_t v0 = f.v[t][cb].x, v1 = f.v[t][cb].y;
@@ -509,8 +536,8 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
         if (!(mine & 8u)) v1 &= 0x0000ffffu;
       }
       const short4_t vf = as_short4(v0, v1);
-      a.o[cb] = mfma16<kHalf>(vf, ph, a.o[cb]);
-      a.o[cb] = mfma16<kHalf>(vf, pl, a.o[cb]);
+      a.o[cb] = mfma16<kH>(vf, ph, a.o[cb]);
+      a.o[cb] = mfma16<kH>(vf, pl, a.o[cb]);
     }
   }
 }
@@ -557,6 +584,22 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   // q_rows: the unit's G query rows where the caller already holds them (the fused
   // kernel: in LDS, staged by the scoring phase); nullptr: fetched from memory
   load_q_frag<D>(qf, q_rows ? q_rows : p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  float qbias = 0.f;   // INT8 cache: kI8Bias * sum over the channels of this lane's query row
+  if constexpr (kInt8) {
+    typedef __fp16 h2_t __attribute__((ext_vector_type(2)));
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) {
+      const uint32_t w0 = (uint32_t)(uint16_t)qf[i][0] | ((uint32_t)(uint16_t)qf[i][1] << 16);
+      const uint32_t w1 = (uint32_t)(uint16_t)qf[i][2] | ((uint32_t)(uint16_t)qf[i][3] << 16);
+      const h2_t a = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w0), bf16_hi(w0));
+      const h2_t c = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w1), bf16_hi(w1));
+      part += ((float)a[0] + (float)a[1]) + ((float)c[0] + (float)c[1]);
+      qf[i] = as_short4(__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c));
+    }
+    // the row is spread over the four lanes head, head + 16, head + 32, head + 48
+    qbias = kI8Bias * rows_sum_f32(part);
+  }
   // The new token's page is the sequence's last, so in the ascending list it can
   // only be the very last entry: one wave of one workgroup ever needs the token.
   // splice_item: the fragment it falls into, splice_x: its position there.
@@ -659,7 +702,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
                 patch.apply_scales(f[i].ks, f[i].vs, splice_x);
               }
             }
-            attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs);
+            attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs, qbias);
           } else {
             if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
             attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
@@ -671,6 +714,13 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   }
 
   TS_MARK(18);
+  if constexpr (kInt8) {   // the bias of the value operands, out of the accumulator
+    const float wsum = kI8Bias * rows_sum_f32(acc.lp);
+#pragma unroll
+    for (int cb = 0; cb < D / 16; ++cb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc.o[cb][v] -= wsum;
+  }
   // merge the wave states
   const float l = rows_sum_f32(acc.l);
   constexpr int RS = D + 2;
