@@ -52,7 +52,7 @@ struct Plan {
   int units;          // B * Hkv
   int g;              // workgroups per unit (= attention splits = score slices)
   int chunk;          // selected pages per workgroup
-  size_t off_unit;    // int32 [2][units * cstride]: arrival counters of the fused / the staged attention
+  size_t off_unit;    // int32 [2][units * cstride]: [1] = arrival counters of the staged attention ([0] unused)
   int cstride;        // words between the counters of consecutive units
   size_t off_scores;  // {fp32 score, uint32 launch tag} [units][Pmax]
   size_t off_part;    // [units][g][G][d+2]: {fp32, launch tag} words (fused) or fp32 (staged attention)
@@ -124,9 +124,10 @@ __global__ __launch_bounds__(kThreads) void sparse_attention_kernel(AttendParams
 //   1. scores every g-th group of the unit's pages (metadata loads are issued
 //      before anything else; the unit's block-table row is copied to LDS
 //      meanwhile),
-//   2. g > 1: publishes its scores with agent-scope stores, bumps the unit's
-//      scan counter, waits (bounded) until all g members have, and reads the
-//      whole score row back;  g == 1: the scores never leave LDS,
+//   2. g > 1: publishes each score as a word tagged with the launch tag and
+//      polls (bounded) the unit's score row until every word carries the tag,
+//      counting the scores into the selection's bins as they come in;
+//      g == 1: the scores never leave LDS,
 //   3. runs the top-K selection itself (every member computes the same list),
 //   4. attends its own 1/g of the selected pages,
 //   5. g > 1: hands its partial softmax state on as words tagged with the launch
