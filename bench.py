@@ -35,8 +35,8 @@ HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
 MEASURED_TRAFFIC_BYTES = {
     "tinyllama": int((27048.7 * 1.9997 + 2114.1) * 1024),
     "longctx": int((19635.1 * 1.9997 + 1966.6) * 1024),
-    "gpt2_345m": int((24943.3 * 1.9997 + 340.1) * 1024),
-    "tiny": int((128.0 * 1.9997 + 2.7) * 1024),
+    "gpt2_345m": int((25656.6 * 1.9997 + 1136.1) * 1024),
+    "tiny": int((371.0 * 1.9997 + 9.6) * 1024),
     "ragged": int((2383591.8 * 1.9997 + 1104.1) * 1024),
 }
 
