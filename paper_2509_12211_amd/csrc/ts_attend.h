@@ -542,6 +542,58 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   }
 }
 
+// Partials handed on as tagged words (attend_split with a tag): merges the first
+// `n` partials of a unit into the running state (M, Lsum, O) of head g, channel c.
+// The thread polls the words it needs until all carry this launch's tag, so the
+// data arrive with the flag, in one trip through the memory system, with no
+// counter and no wait for store acknowledgements on the producers' side.
+// `spins` counts the polls of this thread against spin_limit; returns false if
+// the bounded wait expired (the state is then invalid).
+// NB: partials polled together (all their loads in flight at once).
+template <int D, int NB>
+__device__ __forceinline__ bool merge_tagged(const uint64_t* part, int G, int g, int c, int n,
+                                             uint32_t tag, int spin_limit, int& spins, float& M,
+                                             float& Lsum, float& O) {
+  constexpr int RS = D + 2;
+  bool ok = true;
+  for (int s0 = 0; s0 < n; s0 += NB) {
+    uint64_t o[NB], m[NB], l[NB];
+    for (;;) {
+      bool all = true;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const bool on = s0 + i < n;  // rows past the end re-read row 0
+        const uint64_t* row = part + ((size_t)(on ? s0 + i : 0) * G + g) * RS;
+        o[i] = load_agent_u64(row + c);
+        m[i] = load_agent_u64(row + D);
+        l[i] = load_agent_u64(row + D + 1);
+        all = all && (uint32_t)(o[i] >> 32) == tag && (uint32_t)(m[i] >> 32) == tag &&
+              (uint32_t)(l[i] >> 32) == tag;
+      }
+      if (all) break;
+      if (++spins > spin_limit) { ok = false; break; }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    float Mn = M;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (s0 + i < n) Mn = fmaxf(Mn, __uint_as_float((uint32_t)m[i]));
+    const float sc = __builtin_amdgcn_exp2f(M - Mn);
+    Lsum *= sc;
+    O *= sc;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      if (s0 + i < n) {
+        const float wgt = __builtin_amdgcn_exp2f(__uint_as_float((uint32_t)m[i]) - Mn);
+        Lsum += __uint_as_float((uint32_t)l[i]) * wgt;
+        O += __uint_as_float((uint32_t)o[i]) * wgt;
+      }
+    }
+    M = Mn;
+  }
+  return ok;
+}
+
 // The workgroup attends `count` selected pages of unit (b, h): entry i of its
 // list is page sel_at(i), stored in physical page phys_at(page).  The list is
 // cut into fragments (PageGeom<S>); wave w takes fragments w, w + kWaves, ...
@@ -559,14 +611,17 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 // kHalf: queries, keys and values are IEEE half instead of bf16.
 // q_rows: see below.
 // tag != 0 (n_split > 1): the partial is handed on as 8-byte words {value, tag}
-// (see combine_tagged), so the caller neither waits for the stores nor counts
-// an arrival; the partial area then holds uint64 [.][n_split][G][D + 2].
+// (see merge_tagged), so the caller neither waits for the stores nor counts an
+// arrival; the partial area then holds uint64 [.][n_split][G][D + 2].  The LAST
+// split keeps its own partial in registers, polls for the others (bounded by
+// spin_limit polls per thread) and writes the unit's output; the function
+// returns false if that wait expired.
 template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, bool kHalf, typename SelAt,
           typename PhysAt>
-__device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h, int split,
+__device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
                                              PhysAt phys_at, float* lds, uint32_t tag = 0u,
-                                             const uint16_t* q_rows = nullptr) {
+                                             const uint16_t* q_rows = nullptr, int spin_limit = 0) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
   static_assert(!(kHalf && kInt8), "the INT8 cache goes with bf16 queries");
@@ -734,6 +789,8 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
   }
   __syncthreads();
   float* part = p.partials + (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
+  bool ok = true;
+  int spins = 0;
   // one thread per (head, channel); the thread of channel 0 also hands on the
   // head's running max and sum
   for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
@@ -756,12 +813,23 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
       store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
       if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
     } else if (tag != 0u) {
-      uint64_t* part64 = reinterpret_cast<uint64_t*>(p.partials) +
-                         (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
-      store_agent_tagged(part64 + g * RS + c, O, tag);
-      if (c == 0) {
-        store_agent_tagged(part64 + g * RS + D, M, tag);
-        store_agent_tagged(part64 + g * RS + D + 1, Lsum, tag);
+      uint64_t* unit64 = reinterpret_cast<uint64_t*>(p.partials) +
+                         ((size_t)b * p.Hkv + h) * p.n_split * (size_t)G * RS;
+      if (split == p.n_split - 1) {   // (uniform) the merging split: its own partial never leaves
+        // (small clusters poll four partials at a time, large ones eight)
+        ok = (p.n_split - 1 <= 4 ? merge_tagged<D, 4>(unit64, G, g, c, p.n_split - 1, tag, spin_limit,
+                                                      spins, M, Lsum, O)
+                                 : merge_tagged<D, 8>(unit64, G, g, c, p.n_split - 1, tag, spin_limit,
+                                                      spins, M, Lsum, O)) && ok;
+        store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
+        if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
+      } else {
+        uint64_t* part64 = unit64 + (size_t)split * G * RS;
+        store_agent_tagged(part64 + g * RS + c, O, tag);
+        if (c == 0) {
+          store_agent_tagged(part64 + g * RS + D, M, tag);
+          store_agent_tagged(part64 + g * RS + D + 1, Lsum, tag);
+        }
       }
     } else {
       store_agent(part + g * RS + c, O);
@@ -772,6 +840,7 @@ __device__ __forceinline__ void attend_split(const AttendParams& p, int b, int h
     }
   }
   __syncthreads();
+  return ok;
 }
 
 // Merge the n_split partials of unit (b, h) and write the normalised output.
@@ -814,73 +883,6 @@ __device__ __forceinline__ void combine_splits(const AttendParams& p, int b, int
     store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
     if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
   }
-}
-
-// The same merge over partials handed on as tagged words (attend_split with a
-// tag): every thread polls the words it needs until all carry this launch's tag,
-// so the data arrive with the flag, in one trip through the memory system, with
-// no counter and no wait for store acknowledgements on the producers' side.
-// Returns false if the bounded wait expired (results are then invalid).
-// NB: partials polled together (all their loads in flight at once).
-template <int D, int NB>
-__device__ __forceinline__ bool combine_tagged_by(const AttendParams& p, int b, int h, uint32_t tag,
-                                                  int spin_limit) {
-  constexpr int RS = D + 2;
-  const int G = p.G;
-  const uint64_t* part = reinterpret_cast<const uint64_t*>(p.partials) +
-                         ((size_t)b * p.Hkv + h) * p.n_split * (size_t)G * RS;
-  bool ok = true;
-  int spins = 0;
-  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-    const int g = idx / D, c = idx % D;
-    float M = -1e30f, Lsum = 0.f, O = 0.f;
-    for (int s0 = 0; s0 < p.n_split; s0 += NB) {
-      uint64_t o[NB], m[NB], l[NB];
-      for (;;) {
-        bool all = true;
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-          const bool on = s0 + i < p.n_split;  // rows past the end re-read row 0
-          const uint64_t* row = part + ((size_t)(on ? s0 + i : 0) * G + g) * RS;
-          o[i] = load_agent_u64(row + c);
-          m[i] = load_agent_u64(row + D);
-          l[i] = load_agent_u64(row + D + 1);
-          all = all && (uint32_t)(o[i] >> 32) == tag && (uint32_t)(m[i] >> 32) == tag &&
-                (uint32_t)(l[i] >> 32) == tag;
-        }
-        if (all) break;
-        if (++spins > spin_limit) { ok = false; break; }
-        __builtin_amdgcn_s_sleep(1);
-      }
-      float Mn = M;
-#pragma unroll
-      for (int i = 0; i < NB; ++i)
-        if (s0 + i < p.n_split) Mn = fmaxf(Mn, __uint_as_float((uint32_t)m[i]));
-      const float sc = __builtin_amdgcn_exp2f(M - Mn);
-      Lsum *= sc;
-      O *= sc;
-#pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        if (s0 + i < p.n_split) {
-          const float wgt = __builtin_amdgcn_exp2f(__uint_as_float((uint32_t)m[i]) - Mn);
-          Lsum += __uint_as_float((uint32_t)l[i]) * wgt;
-          O += __uint_as_float((uint32_t)o[i]) * wgt;
-        }
-      }
-      M = Mn;
-    }
-    store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
-    if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
-  }
-  return ok;
-}
-
-template <int D>
-__device__ __forceinline__ bool combine_tagged(const AttendParams& p, int b, int h, uint32_t tag,
-                                               int spin_limit) {
-  // (uniform) small clusters poll four partials at a time, large ones eight
-  return p.n_split <= 4 ? combine_tagged_by<D, 4>(p, b, h, tag, spin_limit)
-                        : combine_tagged_by<D, 8>(p, b, h, tag, spin_limit);
 }
 
 }  // namespace ts

@@ -484,20 +484,17 @@ query_aware_decode_kernel(FusedParams p) {
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     const size_t new_row = ((size_t)b * at.Hkv + h) * D;
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
-    attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
+    // 5. (inside the same call) the cluster's partials are handed on as tagged
+    // words; the cluster's last member (its chunk of the list is the one that
+    // can be short) keeps its own in registers, polls for the others and writes
+    // the output.  Nobody else waits for anything.
+    const bool merged = attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u,
-        reinterpret_cast<const uint16_t*>(q_stage));   // the raw rows head the staging area
+        reinterpret_cast<const uint16_t*>(q_stage),   // the raw rows head the staging area
+        kSpinLimit);
     TS_MARK(6);
-
-    // 5. merge the cluster's partials: they were handed on as tagged words; the
-    // cluster's last member (its chunk of the list is the one that can be short)
-    // polls for all of them and writes the output.  Nobody else waits for anything.
-    if (exchange && member == g - 1) {
-      TS_MARK(8);
-      if (!combine_tagged<D>(at, b, h, tag, kSpinLimit)) atomic_store_agent(&p.ctrl[kCtrlError], 1);
-      TS_MARK(9);
-    }
+    if (!merged) atomic_store_agent(&p.ctrl[kCtrlError], 1);
     if (!kLoop) break;
     if (dynamic) {
       __syncthreads();

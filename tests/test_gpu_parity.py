@@ -542,6 +542,7 @@ def test_bf16_output_is_the_rounded_fp32_output(built, name, splits):
     torch.cuda.synchronize()
     assert _bits_equal(out16, a.out.to(torch.bfloat16)), "fused"
     out16.fill_(float("nan"))
+    ts.sparse_decode_attention(a.layout, w.q[0], a.sel, a.sel_count, w.K_max, scale, a.out, a.ws)
     ts.sparse_decode_attention(lay16, w.q[0], a.sel, a.sel_count, w.K_max, scale, out16, a.ws)
     torch.cuda.synchronize()
     assert _bits_equal(out16, a.out.to(torch.bfloat16)), "staged"
