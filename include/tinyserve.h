@@ -252,7 +252,9 @@ int ts_workspace_status(const void* workspace, int32_t* status_host);
  *   reserved             must be 0
  *   num_splits           workgroups sharing one (b, h): each scores 1/n of its pages and
  *                        attends 1/n of its selected pages
- *   workgroups_per_cu    resident workgroups per compute unit of the fused kernel
+ *   workgroups_per_cu    resident workgroups per compute unit the fused kernel may count on
+ *                        (capped by the occupancy the runtime reports; the kernels are
+ *                        built for one per compute unit)
  * Process-wide; affects ts_workspace_bytes too, so set it before sizing. */
 int ts_set_tuning(int32_t reserved, int32_t num_splits, int32_t workgroups_per_cu);
 
