@@ -386,23 +386,30 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     mode = kRadix;
     need = Kb - fp.count;
   }
-  auto classify = [&](uint32_t k, int page) -> int {   // bit 0: g, bit 1: e
-    if (mode == kWholeSlot) return linear_slot(k) <= cut_slot ? 1 : 0;
-    if (mode == kThreshold) return (k > key_t || (k == key_t && page <= page_t)) ? 1 : 0;
-    const uint32_t nk = k - clo, d = nk - base;
-    const bool inside = bits >= 32 || (d >> bits) == 0u;
-    const bool in = k >= clo && k <= chi && nk >= base;
-    return ((k > chi || (in && !inside)) ? 1 : 0) | ((in && inside) ? 2 : 0);
-  };
   // Ordered compaction in one pass: every thread classifies its own chunk of
   // consecutive pages (bit masks in registers), a workgroup scan of the packed
   // counts gives its starting offsets, and it emits its kept pages in order.
+  // (One loop per mode: the test of the mode stays outside the pass over the keys,
+  // and the two common modes carry no e class.)
   uint64_t gbits = 0, ebits = 0;  // chunk masks (C <= 64)
-  for_my_keys([&](uint32_t k, int i) {
-    const int c = classify(k, my_first + i);
-    gbits |= (uint64_t)(c & 1) << i;
-    ebits |= (uint64_t)(c >> 1) << i;
-  });
+  if (mode == kWholeSlot) {
+    for_my_keys([&](uint32_t k, int i) {
+      gbits |= (uint64_t)(linear_slot(k) <= cut_slot ? 1 : 0) << i;
+    });
+  } else if (mode == kThreshold) {
+    for_my_keys([&](uint32_t k, int i) {
+      const int page = my_first + i;
+      gbits |= (uint64_t)((k > key_t || (k == key_t && page <= page_t)) ? 1 : 0) << i;
+    });
+  } else {
+    for_my_keys([&](uint32_t k, int i) {
+      const uint32_t nk = k - clo, d = nk - base;
+      const bool inside = bits >= 32 || (d >> bits) == 0u;
+      const bool in = k >= clo && k <= chi && nk >= base;
+      gbits |= (uint64_t)((k > chi || (in && !inside)) ? 1 : 0) << i;
+      ebits |= (uint64_t)((in && inside) ? 1 : 0) << i;
+    });
+  }
   const int cg = __popcll(gbits), ce = __popcll(ebits);
   const int packed = cg | (ce << 16);  // both sums stay below 2^15
   int incl = wave_inclusive_sum(packed);
