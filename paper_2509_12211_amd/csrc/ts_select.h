@@ -424,12 +424,17 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const int excl = incl - packed;
   const int goff = excl & 0xffff, eoff = excl >> 16;
   // only the marked pages are visited (few threads hold any when K << P)
-  for (uint64_t todo = gbits | ebits; todo != 0; todo &= todo - 1) {
-    const int i = __builtin_ctzll(todo);
-    const uint64_t below = (1ull << i) - 1;
-    const int gb = goff + __popcll(gbits & below), eb = eoff + __popcll(ebits & below);
-    if ((gbits >> i) & 1) emit(gb + min(eb, need), my_first + i);
-    else if (eb < need) emit(gb + eb, my_first + i);
+  if (mode != kRadix) {   // no e class: the kept pages are the g pages, in order
+    int rank = goff;
+    for (uint64_t todo = gbits; todo != 0; todo &= todo - 1) emit(rank++, my_first + __builtin_ctzll(todo));
+  } else {
+    for (uint64_t todo = gbits | ebits; todo != 0; todo &= todo - 1) {
+      const int i = __builtin_ctzll(todo);
+      const uint64_t below = (1ull << i) - 1;
+      const int gb = goff + __popcll(gbits & below), eb = eoff + __popcll(ebits & below);
+      if ((gbits >> i) & 1) emit(gb + min(eb, need), my_first + i);
+      else if (eb < need) emit(gb + eb, my_first + i);
+    }
   }
 }
 
