@@ -33,8 +33,8 @@ HBM_PEAK = 8.0e12   # MI355X published HBM3E bandwidth, B/s
 # 256 MiB copy: x1.9997 and x1.0000).  Counters cannot be read from inside this process, so the
 # figures are carried here from the committed summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "tinyllama": int((27048.7 * 1.9997 + 2114.1) * 1024),
-    "longctx": int((19635.1 * 1.9997 + 1966.6) * 1024),
+    "tinyllama": int((26954.1 * 1.9997 + 1818.1) * 1024),
+    "longctx": int((19619.5 * 1.9997 + 1892.6) * 1024),
     "gpt2_345m": int((25656.6 * 1.9997 + 1136.1) * 1024),
     "tiny": int((371.0 * 1.9997 + 9.6) * 1024),
     "ragged": int((2383591.8 * 1.9997 + 1104.1) * 1024),
