@@ -416,6 +416,52 @@ def test_many_units_loop_build(oracle, built, name, fmt):
         sess.sel.fill_(-7)
 
 
+CLUSTER_LOOP = {
+    # 129 to 255 units: clusters of two (or more, forced) workgroups per unit, more of
+    # them than fit on the device at once, so every cluster works through several units
+    "d64_s16": wl.WorkloadSpec("cl1", 40, 16, 4, 64, 16, 1800, 20, L_min=1, headroom=32),
+    "d128_s32": wl.WorkloadSpec("cl2", 22, 16, 8, 128, 32, 2600, 0, L_min=1, budget_frac=0.2,
+                                headroom=64),
+    "d64_s4_walk": wl.WorkloadSpec("cl3", 36, 8, 4, 64, 4, 700, 30, keys="walk", L_min=1,
+                                   headroom=32),
+}
+
+
+@pytest.mark.parametrize("name,splits", [("d64_s16", 0), ("d128_s32", 0), ("d64_s4_walk", 0),
+                                         ("d64_s16", 5)], indirect=["splits"])
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_clusters_that_work_through_several_units(oracle, built, name, splits, fmt):
+    """The looping build of the fused kernel WITH clusters: more clusters than the device
+    holds at once, so each takes several units in turn (score exchange, bin counting and
+    the tagged partials once per unit, the launch tag fixed at the first).  Three launches
+    in a row, the middle one with the append in front; sampled units against the oracle,
+    and every unit must have been written."""
+    spec = wl.scaled(CLUSTER_LOOP[name], kv=fmt)
+    print(f"[case] cluster loop {name} splits={splits} {fmt}", flush=True)
+    w = wl.make_workload(spec, DEV, seed=505, n_q=3, n_new=3)
+    sess = Session(w)
+    ts.build_page_meta(sess.layout)
+    scale = 1.0 / math.sqrt(spec.d)
+    n_units = spec.B * spec.Hkv
+    assert 128 < n_units < 256
+    assert ts.append_and_decode_launches(sess.layout, w.K_max) == 2   # not all resident at once
+    rng = np.random.default_rng(10)
+    picks = sorted(set(rng.integers(0, n_units, 10).tolist()) | {0, 127, 128, n_units - 1})
+    units = [(u // spec.Hkv, u % spec.Hkv) for u in picks]
+    for i in range(3):
+        if i == 1:
+            ts.append_and_decode(sess.layout, w.k_new[i], w.v_new[i], w.q[i], w.topk, w.K_max, scale,
+                                 sess.out, sess.ws, topk_per_seq=w.topk_per_seq,
+                                 scores_out=sess.scores, sel_out=sess.sel,
+                                 sel_count_out=sess.sel_count)
+        else:
+            sess.fused(scale, q_idx=i)
+        compare_units(oracle, sess, units, scale, q_idx=i, what=f"{name} launch {i}")
+        assert torch.isfinite(sess.out).all() and int(sess.sel[:, :, 0].min()) >= 0
+        sess.out.fill_(float("nan"))
+        sess.sel.fill_(-7)
+
+
 def test_query_sums_read_back_through_one_hot_boxes(built):
     """Boxes are overwritten so that page c has max = unit vector c and min = 0: the
     score of page c then equals Qp_c = sum over the group's heads of max(q_c, 0), read
