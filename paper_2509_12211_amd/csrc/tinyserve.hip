@@ -22,7 +22,15 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   const int G = L->num_q_heads / L->num_kv_heads;
   const int Pmax = L->max_pages_per_seq;
   pl.units = L->num_seqs * L->num_kv_heads;
-  int g = (target_workgroups + pl.units - 1) / pl.units;
+  // The query-aware path: as many workgroups per unit as keep the WHOLE launch
+  // resident (the members of a cluster wait for each other, and clusters that do
+  // not fit take the units in turns: 160 units in clusters of two take 53 us, one
+  // workgroup each 33 us).  The dense baseline's workgroups wait for nobody, so
+  // it rounds up.
+  int g = target_workgroups == kTargetWorkgroups
+              ? target_workgroups / pl.units
+              : (target_workgroups + pl.units - 1) / pl.units;
+  if (g < 1) g = 1;
   const int cap = (max_topk + 3) / 4;  // at least one page per wave
   if (g > cap) g = cap;
   if (g > kMaxCluster) g = kMaxCluster;

@@ -417,8 +417,9 @@ def test_many_units_loop_build(oracle, built, name, fmt):
 
 
 CLUSTER_LOOP = {
-    # 129 to 255 units: clusters of two (or more, forced) workgroups per unit, more of
-    # them than fit on the device at once, so every cluster works through several units
+    # 129 to 255 units in clusters of two or more workgroups (forced: the library's own
+    # plan keeps a launch resident and would give these batches one workgroup per unit):
+    # more clusters than fit on the device at once, so each works through several units
     "d64_s16": wl.WorkloadSpec("cl1", 40, 16, 4, 64, 16, 1800, 20, L_min=1, headroom=32),
     "d128_s32": wl.WorkloadSpec("cl2", 22, 16, 8, 128, 32, 2600, 0, L_min=1, budget_frac=0.2,
                                 headroom=64),
@@ -427,7 +428,7 @@ CLUSTER_LOOP = {
 }
 
 
-@pytest.mark.parametrize("name,splits", [("d64_s16", 0), ("d128_s32", 0), ("d64_s4_walk", 0),
+@pytest.mark.parametrize("name,splits", [("d64_s16", 2), ("d128_s32", 2), ("d64_s4_walk", 3),
                                          ("d64_s16", 5)], indirect=["splits"])
 @pytest.mark.parametrize("fmt", FORMATS)
 def test_clusters_that_work_through_several_units(oracle, built, name, splits, fmt):
