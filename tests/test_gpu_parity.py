@@ -739,6 +739,53 @@ def test_launch_tag_wraps_past_zero(built, splits):
     assert int(old.ws.view(torch.int32)[16]) == 4 and int(fresh.ws.view(torch.int32)[16]) == 6
 
 
+def test_fused_agrees_with_staged_on_random_shapes(built):
+    """150 random shapes (head_dim, page size, group size, lengths, K, key structure,
+    always-kept pages, coarsely quantised boxes for heavy ties) with random cluster
+    sizes: the fused kernel's selection must equal, entry for entry, what the staged
+    selection (itself bit-exact against the oracle in the tests above) makes of the
+    fused kernel's scores, and its output must agree with the staged attention over that
+    selection.  Every member of a cluster bins the scores in its own way; this is the
+    test that they still agree whatever the shape."""
+    rng = np.random.default_rng(2024)
+    for case in range(150):
+        d = int(rng.choice([64, 128]))
+        S = int(rng.choice([4, 8, 16, 32, 64]))
+        Hkv, G, B = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4, 8])), int(rng.integers(1, 4))
+        L = int(rng.integers(S * 3, S * 400))
+        K = min(int(rng.integers(1, max(2, (L + S - 1) // S))), 200)
+        keys = str(rng.choice(["normal", "offset", "walk"]))
+        splits = int(rng.choice([0, 0, 2, 3, 4, 8, 16]))
+        keep = (int(rng.integers(0, 3)), int(rng.integers(0, 3))) if rng.random() < 0.3 else (0, 0)
+        spec = wl.WorkloadSpec("rand", B, Hkv * G, Hkv, d, S, L, K, keys=keys,
+                               L_min=(1 if rng.random() < 0.5 else 0), headroom=S)
+        what = f"case {case}: {spec} splits={splits} keep={keep}"
+        print(f"[case] random shape {case}", flush=True)
+        w = wl.make_workload(spec, DEV, seed=int(rng.integers(1 << 30)), n_q=1, n_new=1, poison=0.0)
+        a = Session(w, poison_meta=False, keep=keep)
+        ts.build_page_meta(a.layout)
+        if rng.random() < 0.3:
+            a.page_min.copy_((a.page_min.float() * 2).round() / 2)
+            a.page_max.copy_((a.page_max.float() * 2).round() / 2)
+        scale = 1.0 / math.sqrt(d)
+        ts.set_tuning(0, splits, 0)
+        try:
+            ws = ts.new_workspace(a.layout, w.K_max, DEV)
+            ts.query_aware_decode(a.layout, w.q[0], w.topk, w.K_max, scale, a.out, ws,
+                                  topk_per_seq=w.topk_per_seq, scores_out=a.scores, sel_out=a.sel,
+                                  sel_count_out=a.sel_count)
+            sel2, cnt2, out2 = torch.full_like(a.sel, -7), torch.full_like(a.sel_count, -7), torch.full_like(a.out, float("nan"))
+            ts.select_topk_pages(a.layout, a.scores, w.topk, w.K_max, sel2, cnt2,
+                                 topk_per_seq=w.topk_per_seq)
+            ts.sparse_decode_attention(a.layout, w.q[0], sel2, cnt2, w.K_max, scale, out2, ws)
+            torch.cuda.synchronize()
+            assert ts.workspace_status(ws) == 0, what
+        finally:
+            ts.set_tuning(0, 0, 0)
+        assert torch.equal(a.sel_count, cnt2) and torch.equal(a.sel, sel2), what
+        assert torch.isfinite(a.out).all() and (a.out - out2).abs().max().item() <= 2e-5, what
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
