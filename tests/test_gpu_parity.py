@@ -786,6 +786,63 @@ def test_fused_agrees_with_staged_on_random_shapes(built):
         assert torch.isfinite(a.out).all() and (a.out - out2).abs().max().item() <= 2e-5, what
 
 
+def test_append_and_decode_agrees_with_two_calls_on_random_shapes(built):
+    """90 random shapes in all three cache formats, three decode steps each:
+    ts_append_and_decode on one twin, ts_append_token_meta + ts_query_aware_decode on the
+    other.  Pool, scales, metadata, lengths and selection must come out bit-equal and the
+    outputs agree (the in-launch append splices the token into registers, and for the
+    INT8 cache quantises it in three different waves)."""
+    rng = np.random.default_rng(77)
+
+    def twin(spec, seed):
+        w = wl.make_workload(spec, DEV, seed=seed, n_q=3, n_new=3, poison=0.0)
+        meta_dtype = torch.bfloat16 if spec.kv == "int8" else w.k_pool.dtype
+        pmin = torch.zeros((spec.B, spec.Hkv, w.P_max, spec.d), dtype=meta_dtype, device=DEV)
+        pmax = torch.zeros_like(pmin)
+        lens = w.seq_lens.clone()
+        lay = ts.make_layout(spec.B, spec.Hq, spec.Hkv, spec.d, spec.S, w.P_max, w.k_pool, w.v_pool,
+                             w.block_table, lens, pmin, pmax, k_scale=w.k_scale, v_scale=w.v_scale)
+        ts.build_page_meta(lay)
+        out = torch.full((spec.B, spec.Hq, spec.d), float("nan"), dtype=torch.float32, device=DEV)
+        sel = torch.full((spec.B, spec.Hkv, w.K_max), -7, dtype=torch.int32, device=DEV)
+        return w, lay, pmin, pmax, lens, out, sel, ts.new_workspace(lay, w.K_max, DEV)
+
+    for case in range(90):
+        d, S = int(rng.choice([64, 128])), int(rng.choice([4, 8, 16, 32, 64]))
+        Hkv, G, B = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4, 8])), int(rng.integers(1, 4))
+        L = int(rng.integers(S * 3, S * 300))
+        K = min(int(rng.integers(1, max(2, (L + S - 1) // S))), 150)
+        fmt, splits = str(rng.choice(["bf16", "fp16", "int8"])), int(rng.choice([0, 0, 2, 4, 8]))
+        spec = wl.WorkloadSpec("rand", B, Hkv * G, Hkv, d, S, L, K,
+                               keys=str(rng.choice(["normal", "offset", "walk"])),
+                               L_min=(1 if rng.random() < 0.5 else 0), headroom=3 * S, kv=fmt)
+        seed = int(rng.integers(1 << 30))
+        print(f"[case] random append {case} {fmt}", flush=True)
+        scale = 1.0 / math.sqrt(d)
+        ts.set_tuning(0, splits, 0)
+        try:
+            wa, la, amin, amax, alens, aout, asel, aws = twin(spec, seed)
+            wf, lf, fmin, fmax, flens, fout, fsel, fws = twin(spec, seed)
+            for i in range(3):
+                what = f"case {case} step {i}: {spec} splits={splits}"
+                ts.append_token_meta(la, wa.k_new[i], wa.v_new[i], advance_seq_lens=True)
+                ts.query_aware_decode(la, wa.q[i], wa.topk, wa.K_max, scale, aout, aws,
+                                      topk_per_seq=wa.topk_per_seq, sel_out=asel)
+                ts.append_and_decode(lf, wf.k_new[i], wf.v_new[i], wf.q[i], wf.topk, wf.K_max, scale,
+                                     fout, fws, topk_per_seq=wf.topk_per_seq, sel_out=fsel)
+                torch.cuda.synchronize()
+                assert ts.workspace_status(aws) == 0 and ts.workspace_status(fws) == 0, what
+                assert torch.equal(alens, flens), what
+                assert torch.equal(wa.k_pool, wf.k_pool) and torch.equal(wa.v_pool, wf.v_pool), what
+                assert _bits_equal(amin, fmin) and _bits_equal(amax, fmax), what
+                if fmt == "int8":
+                    assert torch.equal(wa.k_scale, wf.k_scale) and torch.equal(wa.v_scale, wf.v_scale), what
+                assert torch.equal(asel, fsel), what
+                assert torch.isfinite(fout).all() and (aout - fout).abs().max().item() <= 2e-5, what
+        finally:
+            ts.set_tuning(0, 0, 0)
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
