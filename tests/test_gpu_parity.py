@@ -843,6 +843,18 @@ def test_append_and_decode_agrees_with_two_calls_on_random_shapes(built):
             ts.set_tuning(0, 0, 0)
 
 
+@pytest.mark.parametrize("B,Hkv", [(40, 4), (25, 4), (24, 8), (50, 4), (16, 4), (4, 4)])
+def test_plan_keeps_the_launch_resident(built, B, Hkv):
+    """Up to 256 units the library sizes its clusters so that every workgroup of the
+    launch is resident at once (the members of a cluster wait for each other; clusters
+    that do not fit would take the units in turns, which measured up to 40 % slower):
+    ts_append_and_decode is then a single launch."""
+    spec = wl.WorkloadSpec("plan", B, Hkv * 4, Hkv, 64, 16, 2048, 32, headroom=32)
+    w = wl.make_workload(spec, DEV, seed=1, n_q=1, n_new=1, poison=0.0)
+    sess = Session(w, poison_meta=False)
+    assert ts.append_and_decode_launches(sess.layout, w.K_max) == 1
+
+
 def test_degenerate_lengths(oracle, built):
     """Empty sequence, single token, exactly one page, one token past a page."""
     print("[case] degenerate", flush=True)
