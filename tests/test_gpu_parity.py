@@ -757,6 +757,10 @@ def test_fused_agrees_with_staged_on_random_shapes(built):
         keys = str(rng.choice(["normal", "offset", "walk"]))
         splits = int(rng.choice([0, 0, 2, 3, 4, 8, 16]))
         keep = (int(rng.integers(0, 3)), int(rng.integers(0, 3))) if rng.random() < 0.3 else (0, 0)
+        if case % 10 == 9:    # one or two long units, many kept pages: the library's largest clusters
+            B, Hkv, splits = 1, int(rng.choice([1, 2])), 0
+            L = int(rng.integers(S * 300, S * 3000))
+            K = int(rng.integers(64, 600))
         spec = wl.WorkloadSpec("rand", B, Hkv * G, Hkv, d, S, L, K, keys=keys,
                                L_min=(1 if rng.random() < 0.5 else 0), headroom=S)
         what = f"case {case}: {spec} splits={splits} keep={keep}"
