@@ -43,8 +43,8 @@ def _run(cmd, verbose):
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every .hip file of csrc/ to an object (in parallel: the cache formats are
-    separate files) and link them into the shared library."""
+    """Compile every .hip file of csrc/ to an object (in parallel: every cache format and
+    head_dim is a file of its own) and link them into the shared library."""
     if not force and not stale():
         return LIB
     from concurrent.futures import ThreadPoolExecutor
@@ -53,6 +53,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     srcs = sources()
     objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    for stale_obj in set(glob.glob(os.path.join(objdir, "*.o"))) - set(objs):
+        os.remove(stale_obj)          # objects of sources that no longer exist
     jobs = min(len(srcs), max(1, min(os.cpu_count() or 1, 8)))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda so: _run([hipcc] + HIPCC_FLAGS + ["-c", so[0], "-o", so[1]], verbose),

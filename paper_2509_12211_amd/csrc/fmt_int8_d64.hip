@@ -1,0 +1,6 @@
+// The format-dependent kernels and their launch logic for the INT8 cache format, head_dim 64.
+#include "ts_fused.h"
+
+namespace ts {
+TS_FORMAT_FUNCTIONS(, TS_KV_INT8, 64)
+}  // namespace ts

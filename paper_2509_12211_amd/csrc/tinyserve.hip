@@ -6,9 +6,12 @@
 namespace ts {
 
 // the three formats are compiled in fmt_bf16.hip, fmt_fp16.hip, fmt_int8.hip
-TS_FORMAT_FUNCTIONS(extern, TS_KV_BF16)
-TS_FORMAT_FUNCTIONS(extern, TS_KV_FP16)
-TS_FORMAT_FUNCTIONS(extern, TS_KV_INT8)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_BF16, 64)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_BF16, 128)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_FP16, 64)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_FP16, 128)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_INT8, 64)
+TS_FORMAT_FUNCTIONS(extern, TS_KV_INT8, 128)
 
 static int g_tune_splits = 0, g_tune_wg_per_cu = 0, g_tune_reserved = 0;
 
@@ -257,16 +260,10 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.units = pl.units;
   p.g = pl.g;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-  switch (layout->kv_format) {
-    case TS_KV_INT8:
-      st = launch_fused_format<TS_KV_INT8>(layout, p, pl, k_new, v_new, cus * per_cu, stream);
-      break;
-    case TS_KV_FP16:
-      st = launch_fused_format<TS_KV_FP16>(layout, p, pl, k_new, v_new, cus * per_cu, stream);
-      break;
-    default:
-      st = launch_fused_format<TS_KV_BF16>(layout, p, pl, k_new, v_new, cus * per_cu, stream);
-  }
+#define TS_CALL(FMT, DD) \
+  st = launch_fused_format<FMT, DD>(layout, p, pl, k_new, v_new, cus * per_cu, stream)
+  TS_DISPATCH_FORMAT(layout, TS_CALL);
+#undef TS_CALL
   if (st != TS_OK) return st;
   return launch_status();
 }
@@ -439,14 +436,12 @@ static int launch_attention(const ts_layout* layout, const Plan& pl, const void*
   AttendParams a = attend_params(layout, pl, q, out, ws, max_topk, softmax_scale);
   a.lse = lse_out;
   int32_t* unit_done = reinterpret_cast<int32_t*>(ws + pl.off_unit) + (size_t)pl.units * pl.cstride;
-  switch (layout->kv_format) {
-    case TS_KV_INT8:
-      return launch_attention_format<TS_KV_INT8>(layout, a, pl, sel, sel_count, unit_done, stream);
-    case TS_KV_FP16:
-      return launch_attention_format<TS_KV_FP16>(layout, a, pl, sel, sel_count, unit_done, stream);
-    default:
-      return launch_attention_format<TS_KV_BF16>(layout, a, pl, sel, sel_count, unit_done, stream);
-  }
+  int st = TS_ERR_UNSUPPORTED;
+#define TS_CALL(FMT, DD) \
+  st = launch_attention_format<FMT, DD>(layout, a, pl, sel, sel_count, unit_done, stream)
+  TS_DISPATCH_FORMAT(layout, TS_CALL);
+#undef TS_CALL
+  return st;
 }
 
 int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int32_t* sel,
@@ -492,9 +487,10 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
   const int cus = num_compute_units();
   if (cus <= 0) return TS_ERR_DEVICE;
   const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
-  int cap1 = layout->kv_format == TS_KV_FP16   ? append_capacity_format<TS_KV_FP16>(layout, pl)
-             : layout->kv_format == TS_KV_INT8 ? append_capacity_format<TS_KV_INT8>(layout, pl)
-                                               : append_capacity_format<TS_KV_BF16>(layout, pl);
+  int cap1 = 0;
+#define TS_CALL(FMT, DD) cap1 = append_capacity_format<FMT, DD>(layout, pl)
+  TS_DISPATCH_FORMAT(layout, TS_CALL);
+#undef TS_CALL
   if (cap1 <= 0) return TS_ERR_DEVICE;
   if (cap1 > cus * per_cu) cap1 = cus * per_cu;
   return pl.units * pl.g <= cap1 ? 1 : 2;

@@ -1,9 +1,9 @@
 // The kernels that depend on the cache format (attention over the selected
 // pages, and Algorithm 1 in one launch) and their host-side launch logic.  Each
-// format is compiled in a file of its own (fmt_*.hip instantiate
+// format and head_dim is compiled in a file of its own (fmt_*.hip instantiate
 // launch_fused_format / launch_attention_format / append_capacity_format for
-// one format each); tinyserve.hip holds the entry points and everything that
-// does not depend on the format.
+// one pair each, so that they build in parallel); tinyserve.hip holds the entry
+// points and everything that does not depend on the format.
 #pragma once
 #include "../../include/tinyserve.h"
 
@@ -562,7 +562,7 @@ static int resident_capacity(KernelT kernel, size_t lds) {
   return cap;
 }
 
-// CALL(D, S) for the layout's head_dim / page_size (check_layout has admitted them).
+// CALL(DD, S) for the layout's page_size (check_layout has admitted it).
 #define TS_DISPATCH_PAGE(DD, S, CALL) \
   switch (S) {                        \
     case 4: CALL(DD, 4); break;       \
@@ -571,14 +571,6 @@ static int resident_capacity(KernelT kernel, size_t lds) {
     case 32: CALL(DD, 32); break;     \
     default: CALL(DD, 64); break;     \
   }
-#define TS_DISPATCH_SHAPE(D, S, CALL)   \
-  do {                                  \
-    if ((D) == 64) {                    \
-      TS_DISPATCH_PAGE(64, S, CALL)     \
-    } else {                            \
-      TS_DISPATCH_PAGE(128, S, CALL)    \
-    }                                   \
-  } while (0)
 
 // One unit per cluster and everything resident: the loop-free build, which
 // also exists with the append folded in.  Otherwise (thousands of
@@ -626,8 +618,8 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
   return TS_OK;
 }
 
-// The fused launch for the layout's head_dim / page_size in one cache format.
-template <int kFmt>
+// The fused launch for the layout's page_size in one cache format and head_dim.
+template <int kFmt, int kD>
 int launch_fused_format(const ts_layout* layout, FusedParams& p, const Plan& pl, const void* k_new,
                         const void* v_new, int max_resident, void* stream) {
   int st = TS_ERR_UNSUPPORTED;
@@ -636,13 +628,13 @@ int launch_fused_format(const ts_layout* layout, FusedParams& p, const Plan& pl,
                                                          stream)                                    \
                 : launch_fused_shape<DD, SS, kFmt, false>(layout, p, pl, k_new, v_new,              \
                                                           max_resident, stream)
-  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_LAUNCH_FUSED);
+  TS_DISPATCH_PAGE(kD, layout->page_size, TS_LAUNCH_FUSED)
 #undef TS_LAUNCH_FUSED
   return st;
 }
 
 // The staged attention kernel (grid (g, units)); sel == nullptr: every page.
-template <int kFmt>
+template <int kFmt, int kD>
 int launch_attention_format(const ts_layout* layout, const AttendParams& a, const Plan& pl,
                             const int32_t* sel, const int32_t* sel_count, int32_t* unit_done,
                             void* stream) {
@@ -653,14 +645,14 @@ int launch_attention_format(const ts_layout* layout, const AttendParams& a, cons
 #define TS_LAUNCH_ATTENTION(DD, SS)              \
   sparse_attention_kernel<DD, SS, kInt8, kHalf> \
       <<<grid, kThreads, lds, s>>>(a, sel, sel_count, unit_done, pl.cstride)
-  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_LAUNCH_ATTENTION);
+  TS_DISPATCH_PAGE(kD, layout->page_size, TS_LAUNCH_ATTENTION)
 #undef TS_LAUNCH_ATTENTION
   return launch_status();
 }
 
 // Workgroups of the loop-free build with the append folded in that can be
 // resident at once.
-template <int kFmt>
+template <int kFmt, int kD>
 int append_capacity_format(const ts_layout* layout, const Plan& pl) {
   constexpr bool kInt8 = kFmt == TS_KV_INT8, kHalf = kFmt == TS_KV_FP16;
   int cap = 0;
@@ -669,18 +661,34 @@ int append_capacity_format(const ts_layout* layout, const Plan& pl) {
                                      pl.lds_fused)                                                 \
                  : resident_capacity(query_aware_decode_kernel<DD, SS, false, true, kInt8, kHalf, false>, \
                                      pl.lds_fused)
-  TS_DISPATCH_SHAPE(layout->head_dim, layout->page_size, TS_CAPACITY);
+  TS_DISPATCH_PAGE(kD, layout->page_size, TS_CAPACITY)
 #undef TS_CAPACITY
   return cap;
 }
 
-// Instantiated once per format, each in its own file.
-#define TS_FORMAT_FUNCTIONS(LINKAGE, FMT)                                                          \
-  LINKAGE template int launch_fused_format<FMT>(const ts_layout*, FusedParams&, const Plan&,       \
-                                                const void*, const void*, int, void*);             \
-  LINKAGE template int launch_attention_format<FMT>(const ts_layout*, const AttendParams&,         \
-                                                    const Plan&, const int32_t*, const int32_t*,   \
-                                                    int32_t*, void*);                              \
-  LINKAGE template int append_capacity_format<FMT>(const ts_layout*, const Plan&);
+// Instantiated once per format and head_dim, each in its own file.
+#define TS_FORMAT_FUNCTIONS(LINKAGE, FMT, DD)                                                      \
+  LINKAGE template int launch_fused_format<FMT, DD>(const ts_layout*, FusedParams&, const Plan&,   \
+                                                    const void*, const void*, int, void*);         \
+  LINKAGE template int launch_attention_format<FMT, DD>(const ts_layout*, const AttendParams&,     \
+                                                        const Plan&, const int32_t*,               \
+                                                        const int32_t*, int32_t*, void*);          \
+  LINKAGE template int append_capacity_format<FMT, DD>(const ts_layout*, const Plan&);
+
+// CALL(FMT, DD) for the layout's cache format and head_dim (check_layout has admitted them).
+#define TS_DISPATCH_FORMAT(layout, CALL)                            \
+  do {                                                              \
+    const bool d64 = (layout)->head_dim == 64;                      \
+    switch ((layout)->kv_format) {                                  \
+      case TS_KV_INT8:                                              \
+        if (d64) { CALL(TS_KV_INT8, 64); } else { CALL(TS_KV_INT8, 128); } \
+        break;                                                      \
+      case TS_KV_FP16:                                              \
+        if (d64) { CALL(TS_KV_FP16, 64); } else { CALL(TS_KV_FP16, 128); } \
+        break;                                                      \
+      default:                                                      \
+        if (d64) { CALL(TS_KV_BF16, 64); } else { CALL(TS_KV_BF16, 128); } \
+    }                                                               \
+  } while (0)
 
 }  // namespace ts
