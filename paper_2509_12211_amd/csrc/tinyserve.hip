@@ -3,9 +3,11 @@
 // wrappers, the work decomposition, and the host-side validation / launches.
 #include "ts_fused.h"
 
+#include <atomic>
+
 namespace ts {
 
-// the three formats are compiled in fmt_bf16.hip, fmt_fp16.hip, fmt_int8.hip
+// every cache format and head_dim is compiled in a file of its own (fmt_<format>_d<head_dim>.hip)
 TS_FORMAT_FUNCTIONS(extern, TS_KV_BF16, 64)
 TS_FORMAT_FUNCTIONS(extern, TS_KV_BF16, 128)
 TS_FORMAT_FUNCTIONS(extern, TS_KV_FP16, 64)
@@ -13,7 +15,9 @@ TS_FORMAT_FUNCTIONS(extern, TS_KV_FP16, 128)
 TS_FORMAT_FUNCTIONS(extern, TS_KV_INT8, 64)
 TS_FORMAT_FUNCTIONS(extern, TS_KV_INT8, 128)
 
-static int g_tune_splits = 0, g_tune_wg_per_cu = 0, g_tune_reserved = 0;
+// Launch-shape overrides for tuning sweeps (ts_set_tuning): process-wide, read once
+// per call; a layout's own cluster_size takes precedence.
+static std::atomic<int> g_tune_splits{0}, g_tune_wg_per_cu{0};
 
 // target_workgroups: about how many workgroups a launch should have.  The
 // query-aware path is latency-bound and wants one per compute unit; the dense
@@ -39,8 +43,11 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   if (g > kMaxCluster) g = kMaxCluster;
   // (Even the shortest configurations measured, 256 pages with 32 kept, are
   // faster spread over a cluster than on one workgroup: 12.5 against 14.0 us.)
-  if (g_tune_splits > 0 && target_workgroups == kTargetWorkgroups)
-    g = g_tune_splits < kMaxCluster ? g_tune_splits : kMaxCluster;
+  if (target_workgroups == kTargetWorkgroups) {
+    const int tuned = g_tune_splits.load(std::memory_order_relaxed);
+    const int forced = L->cluster_size > 0 ? L->cluster_size : tuned;
+    if (forced > 0) g = forced < kMaxCluster ? forced : kMaxCluster;
+  }
   if (g > max_topk) g = max_topk;
   if (g < 1) g = 1;
   pl.chunk = (max_topk + g - 1) / g;
@@ -161,10 +168,20 @@ static int check_layout(const ts_layout* L) {
   if (L->max_pages_per_seq > TS_MAX_PAGES_PER_SEQ) return TS_ERR_UNSUPPORTED;
   if ((long long)L->num_seqs * L->num_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
   if (L->keep_first_pages < 0 || L->keep_last_pages < 0) return TS_ERR_SHAPE;
+  if (L->cluster_size < 0 || L->wait_limit < 0) return TS_ERR_SHAPE;
   if (L->out_format != TS_OUT_F32 && L->out_format != TS_OUT_BF16) return TS_ERR_UNSUPPORTED;
   if (L->kv_format != TS_KV_BF16 && L->kv_format != TS_KV_INT8 && L->kv_format != TS_KV_FP16)
     return TS_ERR_UNSUPPORTED;
   if (L->kv_format == TS_KV_INT8 && L->kv_tile_stride % 16 != 0) return TS_ERR_SHAPE;
+  return TS_OK;
+}
+
+// The pool pointers every call that attends (or appends into the pool) needs:
+// K and V tiles, the block table, the lengths and, for the INT8 cache, the two
+// per-token scale arrays the kernels dereference.
+static int check_pool(const ts_layout* L) {
+  if (!L->k_pool || !L->v_pool || !L->block_table || !L->seq_lens) return TS_ERR_NULL;
+  if (L->kv_format == TS_KV_INT8 && (!L->k_scale || !L->v_scale)) return TS_ERR_NULL;
   return TS_OK;
 }
 
@@ -230,9 +247,8 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
                         size_t workspace_bytes, void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
-  if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
-      !layout->seq_lens || !layout->page_min || !layout->page_max)
-    return TS_ERR_NULL;
+  if (!q || !out || !workspace || !layout->page_min || !layout->page_max) return TS_ERR_NULL;
+  if ((st = check_pool(layout)) != TS_OK) return st;
   if (max_topk < 1 || (!topk_per_seq && (topk < 1 || max_topk < topk))) return TS_ERR_SHAPE;
   Plan pl = make_plan(layout, max_topk);
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
@@ -259,7 +275,9 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.S = layout->page_size;
   p.units = pl.units;
   p.g = pl.g;
-  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
+  p.spin_limit = layout->wait_limit > 0 ? layout->wait_limit : kSpinLimit;
+  const int tuned_per_cu = g_tune_wg_per_cu.load(std::memory_order_relaxed);
+  const int per_cu = tuned_per_cu > 0 ? tuned_per_cu : 1;
 #define TS_CALL(FMT, DD) \
   st = launch_fused_format<FMT, DD>(layout, p, pl, k_new, v_new, cus * per_cu, stream)
   TS_DISPATCH_FORMAT(layout, TS_CALL);
@@ -294,10 +312,9 @@ const char* ts_strerror(int status) {
 }
 
 int ts_set_tuning(int32_t reserved, int32_t num_splits, int32_t workgroups_per_cu) {
-  if (reserved < 0 || num_splits < 0 || workgroups_per_cu < 0) return TS_ERR_SHAPE;
-  g_tune_reserved = reserved;
-  g_tune_splits = num_splits;
-  g_tune_wg_per_cu = workgroups_per_cu;
+  if (reserved != 0 || num_splits < 0 || workgroups_per_cu < 0) return TS_ERR_SHAPE;
+  g_tune_splits.store(num_splits, std::memory_order_relaxed);
+  g_tune_wg_per_cu.store(workgroups_per_cu, std::memory_order_relaxed);
   return TS_OK;
 }
 
@@ -450,9 +467,8 @@ int ts_sparse_decode_attention(const ts_layout* layout, const void* q, const int
                                size_t workspace_bytes, void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
-  if (!q || !sel || !sel_count || !out || !workspace || !layout->k_pool || !layout->v_pool ||
-      !layout->block_table || !layout->seq_lens)
-    return TS_ERR_NULL;
+  if (!q || !sel || !sel_count || !out || !workspace) return TS_ERR_NULL;
+  if ((st = check_pool(layout)) != TS_OK) return st;
   if (max_topk < 1) return TS_ERR_SHAPE;
   const Plan pl = make_plan(layout, max_topk);
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
@@ -470,9 +486,8 @@ int ts_dense_decode_attention(const ts_layout* layout, const void* q, float soft
                               void* stream) {
   int st = check_layout(layout);
   if (st != TS_OK) return st;
-  if (!q || !out || !workspace || !layout->k_pool || !layout->v_pool || !layout->block_table ||
-      !layout->seq_lens)
-    return TS_ERR_NULL;
+  if (!q || !out || !workspace) return TS_ERR_NULL;
+  if ((st = check_pool(layout)) != TS_OK) return st;
   const Plan pl = make_plan(layout, layout->max_pages_per_seq, kDenseTargetWorkgroups);
   if (workspace_bytes < pl.total) return TS_ERR_WORKSPACE;
   return launch_attention(layout, pl, q, nullptr, nullptr, layout->max_pages_per_seq, softmax_scale,
@@ -486,7 +501,8 @@ int ts_append_and_decode_launches(const ts_layout* layout, int32_t max_topk) {
   const Plan pl = make_plan(layout, max_topk);
   const int cus = num_compute_units();
   if (cus <= 0) return TS_ERR_DEVICE;
-  const int per_cu = g_tune_wg_per_cu > 0 ? g_tune_wg_per_cu : 1;
+  const int tuned_per_cu = g_tune_wg_per_cu.load(std::memory_order_relaxed);
+  const int per_cu = tuned_per_cu > 0 ? tuned_per_cu : 1;
   int cap1 = 0;
 #define TS_CALL(FMT, DD) cap1 = append_capacity_format<FMT, DD>(layout, pl)
   TS_DISPATCH_FORMAT(layout, TS_CALL);

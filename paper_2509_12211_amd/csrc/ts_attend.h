@@ -788,6 +788,7 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
     if (kb == 0) { row[D] = acc.m; row[D + 1] = l; }
   }
   __syncthreads();
+  TS_MARK(24);
   float* part = p.partials + (((size_t)b * p.Hkv + h) * p.n_split + split) * (size_t)G * RS;
   bool ok = true;
   int spins = 0;
@@ -839,6 +840,7 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
       }
     }
   }
+  TS_MARK(25);
   __syncthreads();
   return ok;
 }

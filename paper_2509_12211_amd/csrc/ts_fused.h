@@ -11,6 +11,7 @@
 
 #include <map>
 #include <mutex>
+#include <tuple>
 #include <utility>
 
 #include "ts_attend.h"
@@ -80,6 +81,7 @@ struct FusedParams {
   const uint16_t* v_new;
   int topk, S, units, g, cstride, B;
   int keep_first, keep_last;   // pages kept whatever their score (0, 0: the paper's selection)
+  int spin_limit;              // polls before a cross-workgroup wait gives up
 };
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
@@ -371,7 +373,7 @@ query_aware_decode_kernel(FusedParams p) {
             all = all && (uint32_t)(v[i] >> 32) == tag;
           }
           if (all) break;
-          if (++spins > kSpinLimit) { expired = true; break; }
+          if (++spins > p.spin_limit) { expired = true; break; }
           __builtin_amdgcn_s_sleep(1);
         }
 #pragma unroll
@@ -492,7 +494,7 @@ query_aware_decode_kernel(FusedParams p) {
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u,
         reinterpret_cast<const uint16_t*>(q_stage),   // the raw rows head the staging area
-        kSpinLimit);
+        p.spin_limit);
     TS_MARK(6);
     if (!merged) atomic_store_agent(&p.ctrl[kCtrlError], 1);
     if (!kLoop) break;
@@ -544,13 +546,15 @@ static int allow_lds(KernelT kernel, size_t bytes) {
 }
 
 // Workgroups of `kernel` that can be resident on the whole device at once.  The
-// runtime's answer is remembered per (kernel, LDS size): the query costs more
+// runtime's answer is remembered per (device, kernel, LDS size): the query costs more
 // host time than the launch itself.
 template <typename KernelT>
 static int resident_capacity(KernelT kernel, size_t lds) {
   static std::mutex mu;
-  static std::map<std::pair<const void*, size_t>, int> known;
-  const std::pair<const void*, size_t> key(reinterpret_cast<const void*>(kernel), lds);
+  static std::map<std::tuple<int, const void*, size_t>, int> known;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  const std::tuple<int, const void*, size_t> key(dev, reinterpret_cast<const void*>(kernel), lds);
   std::lock_guard<std::mutex> lock(mu);
   auto it = known.find(key);
   if (it != known.end()) return it->second;
