@@ -52,10 +52,12 @@ enum { TS_KV_BF16 = 0, TS_KV_INT8 = 1, TS_KV_FP16 = 2 };
 
 typedef enum ts_status {
   TS_OK = 0,
-  TS_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  TS_ERR_NULL = -1,        /* a required pointer is NULL (with the INT8 cache: k_scale / v_scale
+                              in every call that reads or writes the pool)                  */
   TS_ERR_SHAPE = -2,       /* non-positive dimension, Hq % Hkv != 0, topk < 1, max_topk < topk,
                               0 < kv_tile_stride < S*d or not a multiple of 8, a negative
-                              keep_*_pages count */
+                              keep_*_pages count, cluster_size or wait_limit, a non-zero
+                              reserved argument */
   TS_ERR_UNSUPPORTED = -3, /* head_dim / page_size / group size / page count outside the built set */
   TS_ERR_WORKSPACE = -4,   /* workspace_bytes smaller than ts_workspace_bytes()             */
   TS_ERR_LAUNCH = -5,      /* the HIP runtime reported an error when enqueueing             */
@@ -126,6 +128,21 @@ typedef struct ts_layout {
    * magnitudes from 2^-14 to 65504; smaller ones lose low bits, larger ones are
    * taken as 65504), the int8 codes are exact. */
   int32_t kv_format;
+  /* How the fused calls (ts_query_aware_decode, ts_append_and_decode) spread one
+   * (sequence, KV head) over workgroups.  0 (the default): automatic, about one
+   * workgroup per compute unit in all; with few units a unit is then shared by a
+   * cluster of workgroups that wait for each other inside the launch, which needs
+   * the whole launch resident at once, i.e. a device that runs nothing else at the
+   * same time.  1: one workgroup per unit; no workgroup ever waits for another, so
+   * the launch is safe beside kernels of other streams (slower for small batches).
+   * A serving engine that overlaps other work with the decode step on the same
+   * device should set 1; one that runs the step alone should leave 0.  n > 1: that
+   * many workgroups per unit (for sweeps).  Changes ts_workspace_bytes. */
+  int32_t cluster_size;
+  /* Polls after which a workgroup of a cluster stops waiting for its partners
+   * (0 = the default, about a second; see ts_query_aware_decode).  Tests of the
+   * expiry path set a tiny value. */
+  int32_t wait_limit;
   float* k_scale;
   float* v_scale;
 } ts_layout;
@@ -198,15 +215,19 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream);
 
-/* Section 3.4 + Algorithm 1: one decode step of a layer in ONE launch.  Exactly
- * equivalent to ts_append_token_meta(layout, k_new, v_new, 1, stream) followed
- * by ts_query_aware_decode(...) with the same remaining arguments: the new
+/* Section 3.4 + Algorithm 1: one decode step of a layer in ONE launch.  With
+ * valid block-table entries it leaves exactly the state and results of
+ * ts_append_token_meta(layout, k_new, v_new, 1, stream) followed by
+ * ts_query_aware_decode(...) with the same remaining arguments: the new
  * token of every sequence (k_new, v_new: bf16 [B][Hkv][d], both required) is
  * stored in its pool slot, widens (or opens) the box of its page, takes part in
  * the scoring, selection and attention of this same call, and seq_lens[b] is
  * advanced by one before the call completes.  A sequence whose new page would
  * be >= P_max is left unchanged.  The block-table entry of the page that
- * receives the token must be valid.  It is a single launch whenever all
+ * receives the token must be valid: the two-call form leaves a sequence with an
+ * out-of-range entry untouched, whereas the single launch decides from the
+ * length alone, so it still widens the box and advances seq_lens[b] and only
+ * skips the pool write.  It is a single launch whenever all
  * (sequence, KV head) units are worked on at once (up to one per compute unit);
  * for larger batches, which are bound by bandwidth, the append is enqueued as a
  * kernel of its own in front of the decode on the same stream. */
@@ -249,7 +270,10 @@ int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 int ts_workspace_status(const void* workspace, int32_t* status_host);
 
 /* Launch-shape overrides for tuning sweeps; 0 restores the built-in choice.
- *   reserved             must be 0
+ * A debugging aid, not part of the serving interface (use ts_layout.cluster_size,
+ * which takes precedence over num_splits): the values are process-wide atomics
+ * read once per call.
+ *   reserved             must be 0 (TS_ERR_SHAPE otherwise)
  *   num_splits           workgroups sharing one (b, h): each scores 1/n of its pages and
  *                        attends 1/n of its selected pages
  *   workgroups_per_cu    resident workgroups per compute unit the fused kernel may count on

@@ -47,6 +47,7 @@ class TsLayout(ctypes.Structure):
         ("page_min", ctypes.c_void_p), ("page_max", ctypes.c_void_p),
         ("keep_first_pages", ctypes.c_int32), ("keep_last_pages", ctypes.c_int32),
         ("out_format", ctypes.c_int32), ("kv_format", ctypes.c_int32),
+        ("cluster_size", ctypes.c_int32), ("wait_limit", ctypes.c_int32),
         ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
@@ -113,7 +114,7 @@ def _check(status, where):
 
 def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, page_min,
                 page_max, keep_first_pages=0, keep_last_pages=0, out_format=TS_OUT_F32,
-                k_scale=None, v_scale=None) -> TsLayout:
+                k_scale=None, v_scale=None, cluster_size=0, wait_limit=0) -> TsLayout:
     """Fill the C struct; tensors must stay alive while calls using it are in flight.
     int8 pools (with k_scale / v_scale) select the INT8 cache format, float16 pools the
     FP16 one (q, new tokens and metadata must then be float16 too)."""
@@ -136,6 +137,7 @@ def make_layout(B, Hq, Hkv, d, S, P_max, k_pool, v_pool, block_table, seq_lens, 
                    int(keep_first_pages), int(keep_last_pages), int(out_format),
                    (TS_KV_BF16 if k_pool is None else
                     {torch.int8: TS_KV_INT8, torch.float16: TS_KV_FP16}.get(k_pool.dtype, TS_KV_BF16)),
+                   int(cluster_size), int(wait_limit),
                    None if k_scale is None else k_scale.data_ptr(),
                    None if v_scale is None else v_scale.data_ptr())
     return lay

@@ -83,6 +83,8 @@ def test_workspace_bytes_is_host_only_and_monotone():
     (dict(keep_first_pages=-1), ts.TS_ERR_SHAPE),
     (dict(out_format=7), ts.TS_ERR_UNSUPPORTED),
     (dict(keep_last_pages=-2), ts.TS_ERR_SHAPE),
+    (dict(cluster_size=-1), ts.TS_ERR_SHAPE),
+    (dict(wait_limit=-1), ts.TS_ERR_SHAPE),
     (dict(max_pages_per_seq=-1), ts.TS_ERR_SHAPE),
     (dict(kv_tile_stride=512), ts.TS_ERR_SHAPE),      # smaller than one S*d tile
     (dict(kv_tile_stride=2052), ts.TS_ERR_SHAPE),     # tiles must stay 16-byte aligned
@@ -138,6 +140,45 @@ def test_argument_validation():
     assert lib.ts_workspace_init(p, 8, None) == ts.TS_ERR_WORKSPACE
     assert lib.ts_workspace_status(None, None) == ts.TS_ERR_NULL
     assert lib.ts_set_tuning(-1, 0, 0) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_tuning(1, 0, 0) == ts.TS_ERR_SHAPE      # reserved must be 0
+    assert lib.ts_set_tuning(0, -1, 0) == ts.TS_ERR_SHAPE
+
+
+@pytest.mark.parametrize("missing", ["k_scale", "v_scale"])
+def test_int8_cache_needs_both_scale_arrays(missing):
+    """Every call that reads or writes an INT8 pool dereferences the per-token scales on
+    the device: a forgotten array is a host-side error, not a GPU fault."""
+    lib = ts.lib()
+    scales = dict(k_scale=0x1000, v_scale=0x1000)
+    scales[missing] = None
+    lay = _layout(kv_format=ts.TS_KV_INT8, kv_tile_stride=1024, **scales)
+    good = _layout(kv_format=ts.TS_KV_INT8, kv_tile_stride=1024, k_scale=0x1000, v_scale=0x1000)
+    p = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+    L = ctypes.byref(lay)
+    assert lib.ts_query_aware_decode(L, p, 4, None, 8, 1.0, p, None, None, None, p, big,
+                                     None) == ts.TS_ERR_NULL
+    assert lib.ts_append_and_decode(L, p, p, p, 4, None, 8, 1.0, p, None, None, None, p, big,
+                                    None) == ts.TS_ERR_NULL
+    assert lib.ts_sparse_decode_attention(L, p, p, p, 8, 1.0, p, None, p, big, None) == ts.TS_ERR_NULL
+    assert lib.ts_dense_decode_attention(L, p, 1.0, p, None, p, big, None) == ts.TS_ERR_NULL
+    assert lib.ts_append_token_meta(L, p, p, 1, None) == ts.TS_ERR_NULL
+    if missing == "k_scale":
+        assert lib.ts_build_page_meta(L, None) == ts.TS_ERR_NULL
+    # with both arrays the same calls get past the pointer checks (and stop at the workspace size)
+    assert lib.ts_query_aware_decode(ctypes.byref(good), p, 4, None, 8, 1.0, p, None, None, None, p,
+                                     16, None) == ts.TS_ERR_WORKSPACE
+
+
+def test_cluster_size_changes_workspace_plan():
+    lay1 = _layout(num_seqs=16, max_pages_per_seq=1024, cluster_size=1)
+    lay8 = _layout(num_seqs=16, max_pages_per_seq=1024, cluster_size=8)
+    assert 0 < ts.workspace_bytes(lay1, 128) < ts.workspace_bytes(lay8, 128)
+    try:   # the layout's own value wins over the process-wide override
+        ts.set_tuning(0, 32, 0)
+        assert ts.workspace_bytes(lay1, 128) < ts.workspace_bytes(lay8, 128)
+    finally:
+        ts.set_tuning(0, 0, 0)
 
 
 def test_tuning_changes_workspace_plan():
