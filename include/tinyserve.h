@@ -282,6 +282,15 @@ int ts_workspace_status(const void* workspace, int32_t* status_host);
  * Process-wide; affects ts_workspace_bytes too, so set it before sizing. */
 int ts_set_tuning(int32_t reserved, int32_t num_splits, int32_t workgroups_per_cu);
 
+/* For tests and tuning: launches num_workgroups workgroups of the size the fused
+ * kernel uses and stores into ids[w] (device, int32 [num_workgroups]) the number
+ * of the XCD (die with an L2 of its own) workgroup w ran on.  The fused kernel
+ * lays the workgroups of one cluster out so that they share a die under the
+ * dispatch order this reports on MI355X (consecutive workgroups go to the eight
+ * dies in turn, starting where the previous launch left off, so workgroups whose
+ * numbers are congruent modulo 8 share a die); results never depend on it. */
+int ts_debug_xcc_ids(int32_t* ids, int32_t num_workgroups, void* stream);
+
 const char* ts_strerror(int status);
 int ts_version(void);
 

@@ -142,6 +142,13 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float* scor
   TS_MARK(5);
 }
 
+// Which XCD each workgroup of a launch runs on (the XCC_ID hardware register).
+__global__ __launch_bounds__(kThreads) void xcc_ids_kernel(int32_t* out) {
+  uint32_t id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(id));
+  if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)id;
+}
+
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x)
@@ -333,6 +340,13 @@ int ts_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   const unsigned blocks = (unsigned)((n + 256 * 64 - 1) / (256 * 64));
   fill_zero_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
       static_cast<int32_t*>(workspace), n);
+  return launch_status();
+}
+
+int ts_debug_xcc_ids(int32_t* ids, int32_t num_workgroups, void* stream) {
+  if (!ids) return TS_ERR_NULL;
+  if (num_workgroups < 1 || num_workgroups > 65535) return TS_ERR_SHAPE;
+  xcc_ids_kernel<<<(unsigned)num_workgroups, kThreads, 0, (hipStream_t)stream>>>(ids);
   return launch_status();
 }
 

@@ -634,6 +634,7 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
   L = uniform(L);
   count = uniform(count);
   const int n_items = Geo::items(count);
+  TS_MARK(26);
 
   short4_t qf[D / 16];
   // q_rows: the unit's G query rows where the caller already holds them (the fused
@@ -673,6 +674,7 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
   if (splice) patch.load(nt);
   WaveAcc<D> acc;
   acc.init();
+  TS_MARK(27);
 
   for (int batch = wave; batch < n_items; batch += kWave * kWaves) {
     // lane x holds the page ids of this wave's x-th fragment of the batch
@@ -689,17 +691,18 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
       }
     }
     const int n = min(kWave, (n_items - batch + kWaves - 1) / kWaves);
+    TS_MARK(28);
     // A ring of NBUF fragment buffers: up to NBUF fragments of this wave are in
     // flight (2 KiB - 8 KiB each) before the first is consumed.
     constexpr int NBUF = (D * F <= 1024) ? 4 : ((D == 64 && D * F <= 2048) ? 3 : 2);
     Frag f[NBUF];
     uint32_t vmask[NBUF];
     int item[NBUF];
-    // No branch around the loads (a load under a branch makes the compiler
-    // wait for ALL outstanding loads wherever it needs one of them, so the ring
-    // would drain before the first fragment is used): a slot past the end of
-    // the list, or one whose page id is out of range, re-reads a page that is
-    // certainly mapped (a single cache line of it) and has no valid token.
+    // No branch around a single load (a load under a branch of its own makes the
+    // compiler wait for ALL outstanding loads wherever it needs one of them, so
+    // the ring would drain before the first fragment is used): a slot past the
+    // end of the list, or one whose page id is out of range, re-reads a page that
+    // is certainly mapped (a single cache line of it) and has no valid token.
     auto issue = [&](Frag& fr, int& it, int x) -> uint32_t {
       const int xc = min(x, n - 1);
       it = batch + xc * kWaves;
@@ -741,34 +744,44 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
         return m;
       }
     };
+    auto consume = [&](int i) {
+      if constexpr (kInt8) {
+        PageFrag<D, F> fx;
+        expand_frag<D, F>(f[i], fx);
+        if constexpr (kPatch) {
+          if (splice && item[i] == splice_item) {
+            patch.apply(fx, splice_x);
+            patch.apply_scales(f[i].ks, f[i].vs, splice_x);
+          }
+        }
+        attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs, qbias);
+      } else {
+        if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
+        attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
+      }
+    };
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) vmask[i] = issue(f[i], item[i], i);
     TS_MARK(17);
+    TS_MARK_WAVE(48);
     for (int x0 = 0; x0 < n; x0 += NBUF) {
+      // kBranchless: a round refills all its buffers or none, on ONE uniform test
+      // per round (does a further round follow?), so that inside a round the
+      // number of loads in flight is the same for every buffer and the last round
+      // issues no loads at all: a refill with nothing to fetch would still have to
+      // queue behind the compute unit's outstanding misses (measured: 0.4 us on
+      // the 16-sequence configuration, 1.3 us on the 8-sequence MHA one).
+      const bool more = x0 + NBUF < n;
 #pragma unroll
       for (int i = 0; i < NBUF; ++i) {
-        if (x0 + i < n) {
-          if constexpr (kInt8) {
-            PageFrag<D, F> fx;
-            expand_frag<D, F>(f[i], fx);
-            if constexpr (kPatch) {
-              if (splice && item[i] == splice_item) {
-                patch.apply(fx, splice_x);
-                patch.apply_scales(f[i].ks, f[i].vs, splice_x);
-              }
-            }
-            attend_page<D, F, true>(fx, qf, vmask[i], p.scale_log2, acc, f[i].ks, f[i].vs, qbias);
-          } else {
-            if (splice && item[i] == splice_item) patch.apply(f[i], splice_x);
-            attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
-          }
-        }
-        if (kBranchless || x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
+        if (x0 + i < n) consume(i);
+        if (kBranchless ? more : x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
       }
     }
   }
 
   TS_MARK(18);
+  TS_MARK_WAVE(56);
   if constexpr (kInt8) {   // the bias of the value operands, out of the accumulator
     const float wsum = kI8Bias * rows_sum_f32(acc.lp);
 #pragma unroll

@@ -232,7 +232,7 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
 // (a file that includes every .hip file of this directory), since the buffer
 // pointer below is one device variable.
 #ifdef TS_PROFILE
-__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][32]
+__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][64]
 __device__ __forceinline__ unsigned long long** profile_slot() {
   __shared__ unsigned long long* slot;
   return &slot;
@@ -248,12 +248,21 @@ __device__ __forceinline__ unsigned long long** profile_slot() {
   do {                                                                                  \
     if (((TS_PROFILE_MASK >> (i)) & 1u) && threadIdx.x == 0) {                          \
       unsigned long long* ts_pb = *ts::profile_slot();                                  \
-      if (ts_pb) ts_pb[(size_t)blockIdx.x * 32 + (i)] = wall_clock64();                 \
+      if (ts_pb) ts_pb[(size_t)blockIdx.x * 64 + (i)] = wall_clock64();                 \
+    }                                                                                   \
+  } while (0)
+// the same by the first lane of EVERY wave: slot base + wave (base = 32, 40, 48, 56)
+#define TS_MARK_WAVE(base)                                                              \
+  do {                                                                                  \
+    if ((threadIdx.x & 63) == 0) {                                                      \
+      unsigned long long* ts_pb = *ts::profile_slot();                                  \
+      if (ts_pb) ts_pb[(size_t)blockIdx.x * 64 + (base) + (threadIdx.x >> 6)] = wall_clock64(); \
     }                                                                                   \
   } while (0)
 #else
 #define TS_MARK_INIT() do { } while (0)
 #define TS_MARK(i) do { } while (0)
+#define TS_MARK_WAVE(base) do { } while (0)
 #endif
 
 }  // namespace ts

@@ -82,7 +82,37 @@ struct FusedParams {
   int topk, S, units, g, cstride, B;
   int keep_first, keep_last;   // pages kept whatever their score (0, 0: the paper's selection)
   int spin_limit;              // polls before a cross-workgroup wait gives up
+  int xcds;                    // > 1: clusters laid out one per XCD over that many XCDs (see cluster_of)
+  int n_arrive;                // workgroups of the launch that work on a unit
 };
+
+// Which cluster a workgroup belongs to, and as which member.  The hardware deals
+// consecutive workgroup ids out to the XCDs in turn (on a part with eight of them,
+// ids congruent modulo 8 share a die; the first id of a launch goes wherever the
+// previous launch left off; ts_debug_xcc_ids lets a test look), and each XCD has an
+// L2 of its own.
+// With xcds > 1 the g members of a cluster are the workgroups
+// id = xcd + xcds * (k * g + member): all on one XCD.  Nothing depends on it for
+// correctness (everything the members hand each other goes through agent-scope
+// accesses whichever die they run on); measured, it is worth 0.5 us on a single
+// short sequence and nothing either way on the 16- and 4-sequence batches, whose
+// exchanges wait for the slowest member rather than for the hand-off itself.  The
+// host asks for it only when the grid is a multiple of xcds * g workgroups;
+// clusters beyond the last unit then have nothing to do.  Otherwise the members
+// are consecutive ids.
+struct ClusterSlot { int cluster, member; };
+__device__ __forceinline__ ClusterSlot cluster_of(int wg, int g, int xcds) {
+  ClusterSlot c;
+  if (xcds > 1) {
+    const int xcd = wg % xcds, slot = wg / xcds;
+    c.member = slot % g;
+    c.cluster = (slot / g) * xcds + xcd;
+  } else {
+    c.member = wg % g;
+    c.cluster = wg / g;
+  }
+  return c;
+}
 
 __device__ __forceinline__ int pages_of(int len, int S) { return (len + S - 1) / S; }
 
@@ -174,8 +204,12 @@ query_aware_decode_kernel(FusedParams p) {
   TS_MARK(22);
   const AttendParams& at = p.at;
   const int g = kCluster ? p.g : 1, G = at.G, Pmax = at.Pmax;
-  const int member = kCluster ? blockIdx.x % g : 0;
+  const ClusterSlot where = cluster_of(blockIdx.x, g, kCluster ? p.xcds : 0);
+  const int member = kCluster ? where.member : 0;
   const int n_clusters = gridDim.x / g;
+  // (a launch laid out by XCD is padded to whole rounds of the XCDs: clusters past
+  // the last unit leave at once, before any barrier, and are not counted in)
+  if (kCluster && !kLoop && where.cluster >= p.units) return;
   const SelectLds sl = carve_select(smem, Pmax);
   const size_t sel_bytes = select_lds_bytes(Pmax);
   const size_t att_bytes = (size_t)kWaves * G * (D + 2) * 4;
@@ -190,7 +224,7 @@ query_aware_decode_kernel(FusedParams p) {
   // contended, and the spread of sequence lengths no longer decides the finish
   // time.  Nothing ever waits on a ticket holder.
   const bool dynamic = kLoop && !exchange && p.units > (int)gridDim.x;
-  int u = blockIdx.x / g;
+  int u = where.cluster;
   if (dynamic) {
     if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
     __syncthreads();
@@ -328,7 +362,8 @@ query_aware_decode_kernel(FusedParams p) {
           }
           if (srow_out) srow_out[pg] = s;
         },
-        g, member);
+        g, member, srow_out != nullptr);
+    TS_MARK_WAVE(32);
     const int L = uniform(L_unit);
     const int Pb = uniform(min(pages_of(L, S), Pmax));
     const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
@@ -389,6 +424,7 @@ query_aware_decode_kernel(FusedParams p) {
       }
       if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
       TS_MARK(3);
+      TS_MARK_WAVE(40);
     } else {
       select_begin(sl, tmin, tmax);
     }
@@ -468,7 +504,7 @@ query_aware_decode_kernel(FusedParams p) {
     // its first wave re-arms the count, advances the epoch and (append mode)
     // the lengths, here where the count's return has long arrived and nothing
     // waits for the few stores.
-    if (wave_id() == 0 && uniform(arrived) == (int)gridDim.x - 1) {
+    if (wave_id() == 0 && uniform(arrived) == p.n_arrive - 1) {
       arrived = -2;
       if (lane_id() == 0) {
         atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
@@ -533,6 +569,14 @@ static int num_compute_units() {
     cus = n;
   }
   return cus;
+}
+
+// XCDs (dies with an L2 of their own) the device deals workgroups out to: eight
+// on the full part (32 compute units each), one in the single-die partition modes.
+constexpr int kCusPerXcd = 32;
+static int num_xcds() {
+  const int cus = num_compute_units();
+  return cus >= 2 * kCusPerXcd && cus % kCusPerXcd == 0 ? cus / kCusPerXcd : 1;
 }
 
 template <typename KernelT>
@@ -605,8 +649,19 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
     if ((st = ts_append_token_meta(layout, k_new, v_new, 1, stream)) != TS_OK) return st;
     p.k_new = p.v_new = nullptr;
   }
+  const int xcds = num_xcds();
+  p.xcds = 0;
+  p.n_arrive = 0;
   if (one_unit_each) {
-    const unsigned grid = (unsigned)(pl.units * pl.g);
+    unsigned grid = (unsigned)(pl.units * pl.g);
+    p.n_arrive = (int)grid;
+    // clusters one per XCD: the grid is padded to whole rounds of the XCDs if the
+    // padded launch is still resident at once
+    const unsigned padded = (unsigned)((pl.units + xcds - 1) / xcds * xcds * pl.g);
+    if (kCluster && xcds > 1 && (int)padded <= cap1) {
+      grid = padded;
+      p.xcds = xcds;
+    }
     if (p.k_new)
       app_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
     else
@@ -618,6 +673,11 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
   int clusters = cap / pl.g;
   if (clusters < 1) return TS_ERR_DEVICE;   // a cluster must be co-resident
   if (clusters > pl.units) clusters = pl.units;
+  if (kCluster && xcds > 1 && clusters >= xcds) {
+    clusters = clusters / xcds * xcds;
+    p.xcds = xcds;
+  }
+  p.n_arrive = clusters * pl.g;
   loop_kernel<<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);
   return TS_OK;
 }

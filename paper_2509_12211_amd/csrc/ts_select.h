@@ -60,7 +60,8 @@ struct KeyLayout {
     KeyLayout k;
     k.C = max(1, (Pb + kThreads - 1) / kThreads);
     k.stride = k.C | 1;
-    k.magic = k.C == 1 ? 0u : (uint32_t)((0x100000000ull + k.C - 1) / k.C);
+    // (= ceil(2^32 / C) for every C >= 2, with a 32-bit division)
+    k.magic = k.C == 1 ? 0u : 0xffffffffu / (uint32_t)k.C + 1u;
     return k;
   }
   __device__ __forceinline__ int at(int j) const {

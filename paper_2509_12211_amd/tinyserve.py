@@ -33,6 +33,7 @@ EXPORTS = [
     "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_append_and_decode",
     "ts_append_and_decode_launches", "ts_dense_workspace_bytes", "ts_dense_decode_attention", "ts_workspace_bytes",
     "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
+    "ts_debug_xcc_ids",
 ]
 
 
@@ -88,6 +89,7 @@ def lib():
         L.ts_workspace_init.argtypes = [vp, sz, vp]
         L.ts_workspace_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
         L.ts_set_tuning.argtypes = [i32, i32, i32]
+        L.ts_debug_xcc_ids.argtypes = [vp, i32, vp]
         L.ts_strerror.argtypes = [ctypes.c_int]
         L.ts_strerror.restype = ctypes.c_char_p
         L.ts_version.restype = ctypes.c_int
@@ -236,6 +238,13 @@ def append_and_decode_launches(layout, max_topk) -> int:
     if n < 0:
         raise TinyServeError(n, "ts_append_and_decode_launches")
     return n
+
+
+def debug_xcc_ids(num_workgroups, device) -> torch.Tensor:
+    """int32 [num_workgroups]: the XCD each workgroup of a probe launch ran on."""
+    ids = torch.full((int(num_workgroups),), -1, dtype=torch.int32, device=device)
+    _check(lib().ts_debug_xcc_ids(_ptr(ids), int(num_workgroups), _stream()), "ts_debug_xcc_ids")
+    return ids
 
 
 def set_tuning(reserved=0, num_splits=0, workgroups_per_cu=0):

@@ -10,7 +10,8 @@ import torch
 from paper_2509_12211_amd import tinyserve as ts
 from paper_2509_12211_amd import workloads as wl
 
-from helpers import assert_out_close, assert_scores_close, check_selection, unit_samples
+from helpers import (assert_out_close, assert_scores_close, attention_on_set, by_sequence,
+                     check_selection, full_size_units, head_view, oracle_sequence, unit_samples)
 
 pytestmark = pytest.mark.gpu
 
@@ -61,6 +62,7 @@ def unit_inputs(w, b, h, q_idx, lens):
 
 
 def compare_units(oracle, sess, units, scale, q_idx=0, what=""):
+    """One oracle call per sequence (all the wanted KV heads of it at once)."""
     w = sess.w
     sp = w.spec
     G = sp.Hq // sp.Hkv
@@ -69,22 +71,20 @@ def compare_units(oracle, sess, units, scale, q_idx=0, what=""):
     scores, sel = sess.scores.cpu().numpy(), sess.sel.cpu().numpy()
     cnt, out = sess.sel_count.cpu().numpy(), sess.out.cpu().numpy()
     lens = sess.seq_lens.cpu()
-    for (b, h) in units:
-        tag = f"{what} unit(b={b},h={h})"
-        q, Kq, ks, Vq, vs, L = unit_inputs(w, b, h, q_idx, lens)
-        pmin, pmax = oracle.build_page_meta_i8(Kq, ks, L, sp.S, w.P_max)
+    for b, heads in by_sequence(units).items():
+        r = oracle_sequence(oracle, w, b, heads, scale, q_idx=q_idx, seq_lens=lens)
         Pb = int(oracle.num_pages(int(lens[b]), sp.S))
-        assert np.array_equal(wl.bits(sess.page_min[b, h, :Pb]), pmin[0, 0, :Pb]), f"{tag}: page_min"
-        assert np.array_equal(wl.bits(sess.page_max[b, h, :Pb]), pmax[0, 0, :Pb]), f"{tag}: page_max"
-        topk = int(w.topk_per_seq[b]) if w.topk_per_seq is not None else w.topk
-        r = oracle.query_aware_decode_i8(q, Kq, ks, Vq, vs, pmin, pmax, L, sp.S, topk, w.K_max, scale)
-        assert_scores_close(scores[b, h], r["scores"][0, 0], Pb, tag)
-        same = check_selection(sel[b, h], cnt[b], r, tag)
-        ref = r["out"][0]
-        if not same:
-            ref = oracle.sparse_decode_attention_i8(q, Kq, ks, Vq, vs, sel[b, h][None, None],
-                                                    cnt[b:b + 1], L, sp.S, scale)[0]
-        assert_out_close(out[b, h * G:(h + 1) * G], ref, tag)
+        for i, h in enumerate(heads):
+            tag = f"{what} unit(b={b},h={h})"
+            v = head_view(r, i, G)
+            assert np.array_equal(wl.bits(sess.page_min[b, h, :Pb]), v["pmin"][0, 0, :Pb]), f"{tag}: page_min"
+            assert np.array_equal(wl.bits(sess.page_max[b, h, :Pb]), v["pmax"][0, 0, :Pb]), f"{tag}: page_max"
+            assert_scores_close(scores[b, h], v["scores"][0, 0], Pb, tag)
+            same = check_selection(sel[b, h], cnt[b], v, tag)
+            ref = v["out"][0]
+            if not same:
+                ref = attention_on_set(oracle, w, v, sel[b, h], cnt[b], scale)
+            assert_out_close(out[b, h * G:(h + 1) * G], ref, tag)
 
 
 def spec8(name, *a, **kw):
@@ -253,7 +253,8 @@ def test_int8_many_units_loop_build(oracle, name):
 
 @pytest.mark.parametrize("name", ["tinyllama", "ragged"])
 def test_int8_full_size_sampled(oracle, name):
-    """Benchmark workloads at full size with the INT8 cache, default launch shapes."""
+    """Benchmark workloads at full size with the INT8 cache, default launch shapes; the same
+    units as the bf16 full-size test (all of tinyllama's, 20 sequences of ragged's)."""
     spec = wl.scaled(wl.SPECS[name], kv="int8")
     print(f"[case] int8 full {name}", flush=True)
     w = wl.make_workload(spec, DEV, seed=1500, n_q=2, n_new=1)
@@ -263,4 +264,4 @@ def test_int8_full_size_sampled(oracle, name):
     ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[1], w.topk, w.K_max, scale, sess.out,
                          sess.ws, topk_per_seq=w.topk_per_seq, scores_out=sess.scores,
                          sel_out=sess.sel, sel_count_out=sess.sel_count)
-    compare_units(oracle, sess, unit_samples(w, 6, seed=3), scale, q_idx=1, what=f"int8 full/{name}")
+    compare_units(oracle, sess, full_size_units(w, name), scale, q_idx=1, what=f"int8 full/{name}")

@@ -1,7 +1,7 @@
 """GPU parity: every C-ABI entry point against the CPU oracle on the same seeded
 inputs.  Reduced shapes are compared for every (sequence, KV head); the five
-full-size workloads are compared on sampled units, in the launch configuration
-bench.py times."""
+full-size workloads are compared on every unit (the ragged batch: on every unit of
+20 of its 64 sequences), in the launch configuration bench.py times."""
 import math
 
 import numpy as np
@@ -11,8 +11,8 @@ import torch
 from paper_2509_12211_amd import tinyserve as ts
 from paper_2509_12211_amd import workloads as wl
 
-from helpers import (assert_out_close, assert_scores_close, check_selection, oracle_unit,
-                     unit_samples)
+from helpers import (assert_out_close, assert_scores_close, attention_on_set, by_sequence,
+                     check_selection, full_size_units, head_view, oracle_sequence, unit_samples)
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +22,7 @@ DEV = "cuda:0"
 class Session:
     """Device buffers + layout struct for one workload."""
 
-    def __init__(self, w, poison_meta=True, keep=(0, 0)):
+    def __init__(self, w, poison_meta=True, keep=(0, 0), cluster_size=0, wait_limit=0):
         self.w = w
         self.keep = keep      # pages kept whatever their score: (first, last)
         sp = w.spec
@@ -33,7 +33,8 @@ class Session:
         self.seq_lens = w.seq_lens.clone()
         self.layout = ts.make_layout(sp.B, sp.Hq, sp.Hkv, sp.d, sp.S, w.P_max, w.k_pool, w.v_pool,
                                      w.block_table, self.seq_lens, self.page_min, self.page_max,
-                                     keep_first_pages=keep[0], keep_last_pages=keep[1])
+                                     keep_first_pages=keep[0], keep_last_pages=keep[1],
+                                     cluster_size=cluster_size, wait_limit=wait_limit)
         self.scores = torch.full((sp.B, sp.Hkv, w.P_max), float("nan"), dtype=torch.float32,
                                  device=DEV)
         self.sel = torch.full((sp.B, sp.Hkv, w.K_max), -7, dtype=torch.int32, device=DEV)
@@ -80,24 +81,26 @@ def compare_units(oracle, sess, units, scale, q_idx=0, what=""):
 
 def _compare_units(oracle, sess, units, scale, q_idx, what, w, sp, G, scores, sel, cnt, out, lens,
                    mdt):
+    """One oracle call per sequence (all the wanted KV heads of it at once)."""
     worst = 0.0
-    for (b, h) in units:
-        tag = f"{what} unit(b={b},h={h})"
-        r = oracle_unit(oracle, w, b, h, scale, q_idx=q_idx, seq_lens=lens, keep=sess.keep)
+    for b, heads in by_sequence(units).items():
+        r = oracle_sequence(oracle, w, b, heads, scale, q_idx=q_idx, seq_lens=lens, keep=sess.keep)
         Pb = int(oracle.num_pages(int(lens[b]), sp.S))
-        omin = wl.from_bits(r["pmin"], dtype=mdt).to(torch.float64).numpy()[0, 0]
-        omax = wl.from_bits(r["pmax"], dtype=mdt).to(torch.float64).numpy()[0, 0]
-        gmin = sess.page_min[b, h, :Pb].to(torch.float64).cpu().numpy()
-        gmax = sess.page_max[b, h, :Pb].to(torch.float64).cpu().numpy()
-        assert np.array_equal(gmin, omin[:Pb]), f"{tag}: page_min"
-        assert np.array_equal(gmax, omax[:Pb]), f"{tag}: page_max"
-        assert_scores_close(scores[b, h], r["scores"][0, 0], Pb, tag)
-        same = check_selection(sel[b, h], cnt[b], r, tag)
-        ref = r["out"][0]
-        if not same:   # near-tie at the cut: attention is checked on the GPU's own set
-            ref = oracle.sparse_decode_attention(r["q"], r["K"], r["V"], sel[b, h][None, None],
-                                                 cnt[b:b + 1], r["L"], sp.S, scale)[0]
-        worst = max(worst, assert_out_close(out[b, h * G:(h + 1) * G], ref, tag))
+        for i, h in enumerate(heads):
+            tag = f"{what} unit(b={b},h={h})"
+            v = head_view(r, i, G)
+            omin = wl.from_bits(v["pmin"], dtype=mdt).to(torch.float64).numpy()[0, 0]
+            omax = wl.from_bits(v["pmax"], dtype=mdt).to(torch.float64).numpy()[0, 0]
+            gmin = sess.page_min[b, h, :Pb].to(torch.float64).cpu().numpy()
+            gmax = sess.page_max[b, h, :Pb].to(torch.float64).cpu().numpy()
+            assert np.array_equal(gmin, omin[:Pb]), f"{tag}: page_min"
+            assert np.array_equal(gmax, omax[:Pb]), f"{tag}: page_max"
+            assert_scores_close(scores[b, h], v["scores"][0, 0], Pb, tag)
+            same = check_selection(sel[b, h], cnt[b], v, tag)
+            ref = v["out"][0]
+            if not same:   # near-tie at the cut: attention is checked on the GPU's own set
+                ref = attention_on_set(oracle, w, v, sel[b, h], cnt[b], scale)
+            worst = max(worst, assert_out_close(out[b, h * G:(h + 1) * G], ref, tag))
     return worst
 
 
@@ -847,6 +850,75 @@ def test_append_and_decode_agrees_with_two_calls_on_random_shapes(built):
             ts.set_tuning(0, 0, 0)
 
 
+def test_workgroups_are_dealt_out_to_the_xcds_in_turn(built):
+    """The fused kernel puts the workgroups of one cluster on ids that are congruent modulo
+    the number of XCDs, on the understanding that the hardware deals consecutive ids out to
+    the XCDs in turn (starting wherever the previous launch left off).  Nothing but speed
+    depends on it; this is the check that it holds here."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    xcds = cus // 32 if cus >= 64 and cus % 32 == 0 else 1
+    for n in (16, 256, 1024):
+        ids = ts.debug_xcc_ids(n, DEV)
+        torch.cuda.synchronize()
+        want = (torch.arange(n, dtype=torch.int32, device=DEV) + ids[0]) % xcds
+        assert torch.equal(ids, want), f"{n} workgroups: XCDs {ids[:16].tolist()} ..."
+
+
+@pytest.mark.parametrize("name", ["gqa8_d64_s16_offset", "mha_d64_s16"])
+def test_one_workgroup_per_unit_on_request(oracle, built, name):
+    """ts_layout.cluster_size = 1 (a device shared with other kernels): no workgroup waits for
+    another, whatever the batch; results as always.  cluster_size = 3 overrides the plan the
+    other way."""
+    spec = REDUCED[name]
+    w = wl.make_workload(spec, DEV, seed=77, n_q=1, n_new=1)
+    units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
+    scale = 1.0 / math.sqrt(spec.d)
+    try:
+        ts.set_tuning(0, 8, 0)       # the layout's own value must win over the process-wide one
+        for cs in (1, 3):
+            print(f"[case] cluster_size={cs} {name}", flush=True)
+            sess = Session(w, cluster_size=cs)
+            ts.build_page_meta(sess.layout)
+            sess.fused(scale)
+            compare_units(oracle, sess, units, scale, what=f"cluster_size={cs}/{name}")
+    finally:
+        ts.set_tuning(0, 0, 0)
+
+
+def test_an_expired_wait_raises_the_sticky_word_and_the_launch_still_ends(oracle, built):
+    """ts_layout.wait_limit = 1 lets a workgroup give up on its partners after two looks.  Such a
+    launch must still run to its end (nothing hangs, nothing is read out of bounds) and
+    report itself through ts_workspace_status; after ts_workspace_init the same workspace
+    serves a normal launch again.  The limit is made to bite from the host: with 33 pages to
+    keep out of a list laid out for 40 and clusters of eight, the cluster's last member, the
+    one that merges, has no page of its own and looks for its partners' partial results
+    while they are still fetching theirs."""
+    spec = REDUCED["gqa8_d64_s16_offset"]      # topk (= the list's stride) is 40
+    w = wl.make_workload(spec, DEV, seed=91, n_q=1, n_new=1)
+    assert w.K_max == 40
+    units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
+    scale = 1.0 / math.sqrt(spec.d)
+    hasty = Session(w, cluster_size=8, wait_limit=1)
+    ts.build_page_meta(hasty.layout)
+    expired = 0
+    for attempt in range(8):
+        print(f"[case] expiring wait, try {attempt}", flush=True)
+        ts.query_aware_decode(hasty.layout, w.q[0], 33, w.K_max, scale, hasty.out, hasty.ws)
+        torch.cuda.synchronize()
+        if ts.workspace_status(hasty.ws) != 0:
+            expired += 1
+            ts.workspace_init(hasty.ws)
+            torch.cuda.synchronize()
+            assert ts.workspace_status(hasty.ws) == 0
+    assert expired > 0, "no launch ran into a two-look limit"
+    # the same workspace, patient again
+    patient = Session(w, cluster_size=8)
+    ts.build_page_meta(patient.layout)
+    patient.ws = hasty.ws
+    patient.fused(scale)
+    compare_units(oracle, patient, units, scale, what="after an expired launch")
+
+
 @pytest.mark.parametrize("B,Hkv", [(40, 4), (25, 4), (24, 8), (50, 4), (16, 4), (4, 4)])
 def test_plan_keeps_the_launch_resident(built, B, Hkv):
     """Up to 256 units the library sizes its clusters so that every workgroup of the
@@ -886,7 +958,7 @@ def test_full_size_other_page_sizes(oracle, built, S):
     sess = Session(w)
     ts.build_page_meta(sess.layout)
     scale = 1.0 / math.sqrt(spec.d)
-    units = unit_samples(w, 6, seed=4)
+    units = full_size_units(w, "tinyllama")
     sess.fused(scale, q_idx=1)
     compare_units(oracle, sess, units, scale, q_idx=1, what=f"full/S{S}")
     ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[0], w.topk, w.K_max, scale,
@@ -898,7 +970,7 @@ def test_full_size_other_page_sizes(oracle, built, S):
 @pytest.mark.parametrize("name", ["tinyllama", "ragged"])
 def test_full_size_fp16(oracle, built, name):
     """Benchmark workloads at full size with IEEE-half tensors, default launch shapes: one
-    step through ts_append_and_decode, sampled units."""
+    step through ts_append_and_decode, the same units as test_full_size_sampled."""
     spec = wl.scaled(wl.SPECS[name], kv="fp16")
     print(f"[case] full fp16 {name}", flush=True)
     w = wl.make_workload(spec, DEV, seed=1700, n_q=2, n_new=1)
@@ -908,7 +980,7 @@ def test_full_size_fp16(oracle, built, name):
     ts.append_and_decode(sess.layout, w.k_new[0], w.v_new[0], w.q[1], w.topk, w.K_max, scale,
                          sess.out, sess.ws, topk_per_seq=w.topk_per_seq, scores_out=sess.scores,
                          sel_out=sess.sel, sel_count_out=sess.sel_count)
-    compare_units(oracle, sess, unit_samples(w, 6, seed=3), scale, q_idx=1, what=f"full fp16/{name}")
+    compare_units(oracle, sess, full_size_units(w, name), scale, q_idx=1, what=f"full fp16/{name}")
 
 
 FULL = ["tiny", "gpt2_345m", "tinyllama", "longctx", "ragged"]
@@ -916,7 +988,9 @@ FULL = ["tiny", "gpt2_345m", "tinyllama", "longctx", "ragged"]
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_sampled(oracle, built, name):
-    """The five benchmark workloads at full size, default launch shapes, sampled units."""
+    """The five benchmark workloads at full size, default launch shapes: EVERY unit of the four
+    small batches, and of the ragged batch every KV head of 20 sequences (shortest, longest, the
+    ticket boundaries), against the oracle."""
     spec = wl.SPECS[name]
     print(f"[case] full {name}", flush=True)
     w = wl.make_workload(spec, DEV, seed=1000 + FULL.index(name), n_q=2, n_new=1)
@@ -926,8 +1000,9 @@ def test_full_size_sampled(oracle, built, name):
     if name == "ragged":      # the serving step: append one token per sequence, then decode
         ts.append_token_meta(sess.layout, w.k_new[0], w.v_new[0], advance_seq_lens=True)
     sess.fused(scale, q_idx=1)
-    units = unit_samples(w, 8 if name != "ragged" else 6, seed=3)
+    units = full_size_units(w, name)
     worst = compare_units(oracle, sess, units, scale, q_idx=1, what=f"full/{name}")
+    print(f"[full {name}] {len(units)} of {spec.B * spec.Hkv} units compared", flush=True)
     print(f"[full {name}] worst |out - oracle| = {worst:.3e}", flush=True)
     # properties that hold for every unit: counts, ordering, finite outputs
     torch.cuda.synchronize()
