@@ -215,6 +215,29 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           int32_t* sel_count_out, void* workspace, size_t workspace_bytes,
                           void* stream);
 
+/* ts_query_aware_decode for callers that cannot allocate device memory at all, not
+ * even a workspace: code under HIP graph capture that has no buffer of its own to
+ * hand over, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results, minus the workspace: the kernels use a fixed region of
+ * TS_STATIC_WORKSPACE_BYTES of device memory that belongs to the library (every
+ * GPU the library runs on holds its own copy until the process ends) and needs no
+ * ts_workspace_init.  The call allocates nothing and frees nothing.  Layouts whose
+ * ts_workspace_bytes exceeds the region are rejected with TS_ERR_WORKSPACE
+ * (batches of up to 256 (sequence, KV head) units fit with room to spare up to
+ * about 4000 pages a sequence; larger batches run one workgroup per unit and
+ * need a few KiB).  All calls on one GPU share the region: calls that overlap in
+ * time on the same GPU (two streams) race; order them.  A bounded wait that
+ * expired cannot be read back here (there is no workspace to ask):
+ * callers that share the device with other kernels use ts_layout.cluster_size = 1,
+ * with which nothing waits.  The first call on a device looks the region's
+ * address up (no allocation, but not a stream operation: make that first call
+ * outside a graph capture). */
+#define TS_STATIC_WORKSPACE_BYTES (4 << 20)
+int ts_query_aware_decode_static(const ts_layout* layout, const void* q, int32_t topk,
+                                 const int32_t* topk_per_seq, int32_t max_topk,
+                                 float softmax_scale, void* out, float* scores_out,
+                                 int32_t* sel_out, int32_t* sel_count_out, void* stream);
+
 /* Section 3.4 + Algorithm 1: one decode step of a layer in ONE launch.  With
  * valid block-table entries it leaves exactly the state and results of
  * ts_append_token_meta(layout, k_new, v_new, 1, stream) followed by

@@ -4,6 +4,7 @@
 #include "ts_fused.h"
 
 #include <atomic>
+#include <mutex>
 
 namespace ts {
 
@@ -59,10 +60,13 @@ static Plan make_plan(const ts_layout* L, int max_topk, int target_workgroups = 
   pl.off_unit = off;
   pl.cstride = pl.units <= kCounterPadUnits ? kCounterPadStride : 1;
   off = align_up(off + 2 * (size_t)pl.units * pl.cstride * sizeof(int32_t), 256);
+  // (one workgroup per unit exchanges nothing: its scores never leave LDS and its
+  // result goes straight to the output)
   pl.off_scores = off;
-  off = align_up(off + (size_t)pl.units * Pmax * sizeof(uint64_t), 256);
+  if (pl.g > 1) off = align_up(off + (size_t)pl.units * Pmax * sizeof(uint64_t), 256);
   pl.off_part = off;
-  off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(uint64_t), 256);
+  if (pl.g > 1)
+    off = align_up(off + (size_t)pl.units * pl.g * G * (L->head_dim + 2) * sizeof(uint64_t), 256);
   pl.total = off;
   // fused kernel LDS: select scratch (keys, bins), the unit's block-table row,
   // this workgroup's selected pages; the wave-merge area aliases the keys
@@ -533,6 +537,51 @@ int ts_query_aware_decode(const ts_layout* layout, const void* q, int32_t topk,
                           void* stream) {
   return launch_fused(layout, nullptr, nullptr, q, topk, topk_per_seq, max_topk, softmax_scale, out,
                       scores_out, sel_out, sel_count_out, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------
+// The workspace of ts_query_aware_decode_static: device memory of the library
+// itself.  In host code the array's name only stands for the symbol: its address
+// on a given device comes from hipGetSymbolAddress with that device current, is
+// asked for once per device, and is what every launch is given.  A __device__
+// array starts out zeroed, which is the state ts_workspace_init would leave; from
+// then on the launches keep it consistent themselves (launch tags only grow,
+// whatever layout the bytes were last used for: every exchange word is an aligned
+// 8-byte {value, tag} pair and the control words always sit at the front).
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[TS_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_of_device[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TS_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_of_device[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr)
+      return TS_ERR_DEVICE;
+    g_scratch_of_device[dev] = p;
+  }
+  *ptr = g_scratch_of_device[dev];
+  return TS_OK;
+}
+
+int ts_query_aware_decode_static(const ts_layout* layout, const void* q, int32_t topk,
+                                 const int32_t* topk_per_seq, int32_t max_topk,
+                                 float softmax_scale, void* out, float* scores_out,
+                                 int32_t* sel_out, int32_t* sel_count_out, void* stream) {
+  const int st = check_layout(layout);
+  if (st != TS_OK) return st;
+  if (max_topk < 1) return TS_ERR_SHAPE;
+  if (make_plan(layout, max_topk).total > (size_t)TS_STATIC_WORKSPACE_BYTES) return TS_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int sw = static_scratch(&ws);
+  if (sw != TS_OK) return sw;
+  return launch_fused(layout, nullptr, nullptr, q, topk, topk_per_seq, max_topk, softmax_scale, out,
+                      scores_out, sel_out, sel_count_out, ws, (size_t)TS_STATIC_WORKSPACE_BYTES,
+                      stream);
 }
 
 int ts_append_and_decode(const ts_layout* layout, const void* k_new, const void* v_new,

@@ -33,7 +33,7 @@ EXPORTS = [
     "ts_sparse_decode_attention", "ts_query_aware_decode", "ts_append_and_decode",
     "ts_append_and_decode_launches", "ts_dense_workspace_bytes", "ts_dense_decode_attention", "ts_workspace_bytes",
     "ts_workspace_init", "ts_workspace_status", "ts_set_tuning", "ts_strerror", "ts_version",
-    "ts_debug_xcc_ids",
+    "ts_debug_xcc_ids", "ts_query_aware_decode_static",
 ]
 
 
@@ -79,6 +79,7 @@ def lib():
         L.ts_select_topk_pages.argtypes = [lp, vp, i32, vp, i32, vp, vp, vp]
         L.ts_sparse_decode_attention.argtypes = [lp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
         L.ts_query_aware_decode.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ts_query_aware_decode_static.argtypes = [lp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp]
         L.ts_append_and_decode.argtypes = [lp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ts_append_and_decode_launches.argtypes = [lp, i32]
         L.ts_dense_workspace_bytes.argtypes = [lp]
@@ -206,6 +207,18 @@ def query_aware_decode(layout, q, topk, max_topk, softmax_scale, out, workspace,
         float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out), _ptr(sel_count_out),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
         "ts_query_aware_decode")
+
+
+STATIC_WORKSPACE_BYTES = 4 << 20
+
+
+def query_aware_decode_static(layout, q, topk, max_topk, softmax_scale, out, topk_per_seq=None,
+                              scores_out=None, sel_out=None, sel_count_out=None):
+    """ts_query_aware_decode on the library's own fixed workspace (allocates nothing)."""
+    _check(lib().ts_query_aware_decode_static(
+        ctypes.byref(layout), _ptr(q), int(topk), _ptr(topk_per_seq), int(max_topk),
+        float(softmax_scale), _ptr(out), _ptr(scores_out), _ptr(sel_out), _ptr(sel_count_out),
+        _stream()), "ts_query_aware_decode_static")
 
 
 def append_and_decode(layout, k_new, v_new, q, topk, max_topk, softmax_scale, out, workspace,

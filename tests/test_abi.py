@@ -193,6 +193,21 @@ def test_tuning_changes_workspace_plan():
         ts.set_tuning(0, 0, 0)
 
 
+def test_static_workspace_entry_rejects_what_does_not_fit():
+    """ts_query_aware_decode_static has a fixed region to work in: a layout that needs more is
+    turned away on the host (before the region is even looked up)."""
+    lay = _layout(num_seqs=8, num_q_heads=16, num_kv_heads=4, max_pages_per_seq=16384,
+                  num_phys_pages=1 << 20)
+    assert ts.workspace_bytes(lay, 512) > ts.STATIC_WORKSPACE_BYTES
+    p = ctypes.c_void_p(0x1000)
+    call = ts.lib().ts_query_aware_decode_static
+    assert call(ctypes.byref(lay), p, 512, None, 512, 1.0, p, None, None, None,
+                None) == ts.TS_ERR_WORKSPACE
+    assert call(ctypes.byref(_layout(head_dim=96)), p, 4, None, 4, 1.0, p, None, None, None,
+                None) == ts.TS_ERR_UNSUPPORTED
+    assert call(None, p, 4, None, 4, 1.0, p, None, None, None, None) == ts.TS_ERR_NULL
+
+
 def test_binding_raises_without_library(monkeypatch):
     """No silent fallback: a missing library is an error."""
     monkeypatch.setattr(ts, "_lib", None)
