@@ -8,6 +8,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtinyserve_hip.so")
+# the same sources with phase timestamps compiled in (bench.py --phase-marks); built on request
+PROFILE_LIB = os.path.join(HERE, "libtinyserve_prof.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
@@ -21,10 +23,10 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def stale() -> bool:
-    if not os.path.exists(LIB):
+def stale(lib: str = LIB) -> bool:
+    if not os.path.exists(lib):
         return True
-    t = os.path.getmtime(LIB)
+    t = os.path.getmtime(lib)
     deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(
         os.path.join(HERE, "..", "include", "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
@@ -42,14 +44,18 @@ def _run(cmd, verbose):
         print(out, flush=True)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, profile: bool = False) -> str:
     """Compile every .hip file of csrc/ to an object (in parallel: every cache format and
-    head_dim is a file of its own) and link them into the shared library."""
-    if not force and not stale():
-        return LIB
+    head_dim is a file of its own) and link them into the shared library.  profile=True
+    builds the tuning library instead: the same code with -DTS_PROFILE, whose fused kernel
+    records a timestamp at each numbered point of its path (ts_debug_set_profile_buffer)."""
+    lib = PROFILE_LIB if profile else LIB
+    if not force and not stale(lib):
+        return lib
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build_prof" if profile else "_build")
+    flags = HIPCC_FLAGS + (["-DTS_PROFILE"] if profile else [])
     os.makedirs(objdir, exist_ok=True)
     srcs = sources()
     objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
@@ -57,11 +63,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
         os.remove(stale_obj)          # objects of sources that no longer exist
     jobs = min(len(srcs), max(1, min(os.cpu_count() or 1, 8)))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        list(pool.map(lambda so: _run([hipcc] + HIPCC_FLAGS + ["-c", so[0], "-o", so[1]], verbose),
+        list(pool.map(lambda so: _run([hipcc] + flags + ["-c", so[0], "-o", so[1]], verbose),
                       zip(srcs, objs)))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
-    return LIB
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib], verbose)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    import sys
+    print(build(force=True, verbose=True, profile="--profile" in sys.argv))

@@ -303,9 +303,17 @@ extern "C" {
 int ts_version(void) { return 4; }
 
 #ifdef TS_PROFILE
+// buf: device, uint64 [workgroups of the largest launch][64] (NULL: stop recording).
 int ts_debug_set_profile_buffer(void* buf) {
-  return hipMemcpyToSymbol(HIP_SYMBOL(g_profile_buf), &buf, sizeof(buf)) == hipSuccess ? TS_OK
-                                                                                        : TS_ERR_LAUNCH;
+  int st = hipMemcpyToSymbol(HIP_SYMBOL(g_profile_buf), &buf, sizeof(buf)) == hipSuccess
+               ? TS_OK
+               : TS_ERR_LAUNCH;
+#define TS_SET(FMT, DD) \
+  if (st == TS_OK) st = set_profile_buffer_format<FMT, DD>(buf)
+  TS_SET(TS_KV_BF16, 64); TS_SET(TS_KV_BF16, 128); TS_SET(TS_KV_FP16, 64);
+  TS_SET(TS_KV_FP16, 128); TS_SET(TS_KV_INT8, 64); TS_SET(TS_KV_INT8, 128);
+#undef TS_SET
+  return st;
 }
 #endif
 

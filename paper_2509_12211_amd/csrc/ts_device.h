@@ -228,11 +228,11 @@ __device__ __forceinline__ int wait_at_least(const int* p, int target, int limit
 // workgroup records the constant-rate 100 MHz clock at numbered points.  The
 // buffer address is parked in LDS once (TS_MARK_INIT at kernel entry) so that a
 // mark costs an LDS read and a store, and waits for no memory load in flight.
-// Compiled out of the product library.  A tuning build is one translation unit
-// (a file that includes every .hip file of this directory), since the buffer
-// pointer below is one device variable.
+// Compiled out of the product library (build.py builds the tuning library,
+// libtinyserve_prof.so, on request).  The buffer pointer is a device variable of
+// each translation unit: ts_debug_set_profile_buffer sets all of them.
 #ifdef TS_PROFILE
-__device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][64]
+static __device__ unsigned long long* g_profile_buf = nullptr;   // [workgroup][64]
 __device__ __forceinline__ unsigned long long** profile_slot() {
   __shared__ unsigned long long* slot;
   return &slot;

@@ -730,8 +730,21 @@ int append_capacity_format(const ts_layout* layout, const Plan& pl) {
   return cap;
 }
 
+#ifdef TS_PROFILE
+// The timestamp buffer of the translation unit that holds this format's kernels.
+template <int kFmt, int kD>
+int set_profile_buffer_format(void* buf) {
+  return hipMemcpyToSymbol(HIP_SYMBOL(g_profile_buf), &buf, sizeof(buf)) == hipSuccess ? TS_OK
+                                                                                        : TS_ERR_LAUNCH;
+}
+#define TS_FORMAT_PROFILE(LINKAGE, FMT, DD) LINKAGE template int set_profile_buffer_format<FMT, DD>(void*);
+#else
+#define TS_FORMAT_PROFILE(LINKAGE, FMT, DD)
+#endif
+
 // Instantiated once per format and head_dim, each in its own file.
 #define TS_FORMAT_FUNCTIONS(LINKAGE, FMT, DD)                                                      \
+  TS_FORMAT_PROFILE(LINKAGE, FMT, DD)                                                              \
   LINKAGE template int launch_fused_format<FMT, DD>(const ts_layout*, FusedParams&, const Plan&,   \
                                                     const void*, const void*, int, void*);         \
   LINKAGE template int launch_attention_format<FMT, DD>(const ts_layout*, const AttendParams&,     \
