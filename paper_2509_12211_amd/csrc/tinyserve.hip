@@ -388,16 +388,21 @@ int ts_build_page_meta(const ts_layout* layout, void* stream) {
       build_page_meta_i8_kernel<128><<<grid8, kThreads, 0, (hipStream_t)stream>>>(p);
     return launch_status();
   }
-  dim3 grid((p.Pmax + kWaves - 1) / kWaves, p.Hkv, p.B);
+  const int pages_per_wg = kWaves * (kWave / (layout->head_dim / 8));
+  dim3 grid((p.Pmax + pages_per_wg - 1) / pages_per_wg, p.Hkv, p.B);
   const bool half = layout->kv_format == TS_KV_FP16;
-  if (layout->head_dim == 64 && !half)
-    build_page_meta_kernel<64, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
-  else if (layout->head_dim == 64)
-    build_page_meta_kernel<64, true><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
-  else if (!half)
-    build_page_meta_kernel<128, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
-  else
-    build_page_meta_kernel<128, true><<<grid, kThreads, 0, (hipStream_t)stream>>>(p);
+  hipStream_t s = (hipStream_t)stream;
+#define TS_LAUNCH_BUILD(DD, HH)                                                                 \
+  do {                                                                                          \
+    if (p.S == 4) build_page_meta_kernel<DD, HH, 4><<<grid, kThreads, 0, s>>>(p);               \
+    else if (p.S == 8) build_page_meta_kernel<DD, HH, 8><<<grid, kThreads, 0, s>>>(p);          \
+    else build_page_meta_kernel<DD, HH, 16><<<grid, kThreads, 0, s>>>(p);                       \
+  } while (0)
+  if (layout->head_dim == 64 && !half) TS_LAUNCH_BUILD(64, false);
+  else if (layout->head_dim == 64) TS_LAUNCH_BUILD(64, true);
+  else if (!half) TS_LAUNCH_BUILD(128, false);
+  else TS_LAUNCH_BUILD(128, true);
+#undef TS_LAUNCH_BUILD
   return launch_status();
 }
 

@@ -760,8 +760,16 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
         attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
       }
     };
+    // The first fill.  In the latency-bound builds a wave often has fewer fragments
+    // than buffers (one page, or none): only the fragments that exist are fetched,
+    // each under a uniform test, so all of them are waited for before the first is
+    // used (they were all sent out together anyway), instead of queueing placeholder
+    // loads for the empty buffers behind the compute unit's outstanding misses
+    // (-1.1 us on the 4-sequence long-context batch, -0.5 us on a single sequence).
+    constexpr bool kExactFill = kBranchless;
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i) vmask[i] = issue(f[i], item[i], i);
+    for (int i = 0; i < NBUF; ++i)
+      if (!kExactFill || i < n) vmask[i] = issue(f[i], item[i], i);
     TS_MARK(17);
     TS_MARK_WAVE(48);
     for (int x0 = 0; x0 < n; x0 += NBUF) {

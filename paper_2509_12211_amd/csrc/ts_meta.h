@@ -17,44 +17,54 @@ struct MetaParams {
   float* v_scale;
 };
 
-// One wavefront summarises one (sequence, KV head, logical page): the S x D
-// bf16 tile is contiguous, so the wave reads it as 16-byte chunks (lane ->
-// token lane / (D/8), channels 8 * (lane % (D/8)) ..+7), takes the channel-wise
-// min / max over its tokens, then folds the lanes that share a channel group.
-template <int D, bool kHalf>
+// A wavefront summarises kWave / (D/8) logical pages of one (sequence, KV head) at
+// a time: a page's D/8 consecutive lanes each own eight channels (one 16-byte
+// chunk of a token row) and walk down the page's tokens, so a lane takes the
+// channel-wise min / max over the tokens in its own registers and nothing is
+// folded across lanes.  A wave-wide load reads one token row of every page of
+// the group (128 or 256 contiguous bytes each); up to NT = 16 of them are in
+// flight per wave before the first is used (16 KiB), behind ONE dependent
+// look-up of the sequence length and the block-table entries, so the kernel
+// streams the pool at memory speed instead of paying that chain per page.
+// NT: token rows fetched together, min(page_size, 16); longer pages take several
+// rounds.  Slots past the sequence's last token are read (they lie inside the
+// page's tile) and ignored.
+template <int D, bool kHalf, int NT>
 __global__ __launch_bounds__(kThreads) void build_page_meta_kernel(MetaParams p) {
-  constexpr int LPR = D / 8;        // lanes per token row
-  constexpr int TPW = kWave / LPR;  // token rows per wave-wide load
-  const int lane = lane_id();
-  const int j = blockIdx.x * kWaves + wave_id();
+  constexpr int LPR = D / 8;        // lanes per page (one per 16-byte chunk of a token row)
+  constexpr int PPW = kWave / LPR;  // pages per wave
+  const int lane = lane_id(), cg = lane % LPR;
+  const int j = (blockIdx.x * kWaves + wave_id()) * PPW + lane / LPR;
   const int h = blockIdx.y, b = blockIdx.z;
   const int L = p.seq_lens[b];
-  const int Pb = (L + p.S - 1) / p.S;
-  if (j >= Pb || j >= p.Pmax) return;
-  const int phys = p.block_table[(size_t)b * p.Pmax + j];
-  if (phys < 0 || phys >= p.n_phys) return;
-  const int valid = min(p.S, L - j * p.S);
-  const uint16_t* tile = p.k_pool + ((size_t)phys * p.Hkv + h) * (size_t)p.tile_stride;
-  const int cg = lane % LPR;
+  const int Pb = min((L + p.S - 1) / p.S, p.Pmax);
+  if (uniform((blockIdx.x * kWaves + wave_id()) * PPW) >= Pb) return;   // the whole group is past the end
+  const bool page_on = j < Pb;
+  const int phys = p.block_table[(size_t)b * p.Pmax + min(j, Pb - 1)];
+  const bool on = page_on && phys >= 0 && phys < p.n_phys;
+  const int valid = min(p.S, L - j * p.S);   // tokens the page holds (only looked at when `on`)
+  const uint16_t* tile =
+      p.k_pool + ((size_t)(on ? phys : 0) * p.Hkv + h) * (size_t)p.tile_stride + cg * 8;
   float lo[8], hi[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) { lo[i] = INFINITY; hi[i] = -INFINITY; }
-  for (int t = lane / LPR; t < valid; t += TPW) {
-    const uint4 w = *reinterpret_cast<const uint4*>(tile + (size_t)t * D + cg * 8);
-    float f[8];
-    unpack8e<kHalf>(w, f);
+  for (int t0 = 0; t0 < p.S; t0 += NT) {
+    uint4 w[NT];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { lo[i] = fminf(lo[i], f[i]); hi[i] = fmaxf(hi[i], f[i]); }
-  }
+    for (int t = 0; t < NT; ++t) w[t] = *reinterpret_cast<const uint4*>(tile + (size_t)(t0 + t) * D);
 #pragma unroll
-  for (int m = LPR; m < kWave; m <<= 1) {
+    for (int t = 0; t < NT; ++t) {
+      float f[8];
+      unpack8e<kHalf>(w[t], f);
+      const bool tok = t0 + t < valid;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      lo[i] = fminf(lo[i], shfl_xor_f(lo[i], m));
-      hi[i] = fmaxf(hi[i], shfl_xor_f(hi[i], m));
+      for (int i = 0; i < 8; ++i) {
+        lo[i] = fminf(lo[i], tok ? f[i] : INFINITY);
+        hi[i] = fmaxf(hi[i], tok ? f[i] : -INFINITY);
+      }
     }
   }
-  if (lane < LPR) {
+  if (on) {
     const size_t row = (((size_t)b * p.Hkv + h) * p.Pmax + j) * D + cg * 8;
     // back to 16-bit elements: the values are elements of the cache, so this is exact
     // (bf16: the upper half of the fp32 pattern)
