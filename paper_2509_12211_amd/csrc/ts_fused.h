@@ -274,11 +274,11 @@ query_aware_decode_kernel(FusedParams p) {
   TS_MARK(23);
 
   // Launch tag of the score exchange.  The epoch word is read by every
-  // workgroup before it counts itself in; the workgroup that counts in last
-  // (every other one has read the word by then) advances it for the next launch
-  // on its way out.
+  // workgroup before it counts itself in; the launch's first workgroup advances it
+  // for the next launch on its way out, once the count says that every workgroup
+  // has read it.
   uint32_t tag = 0;
-  int arrived = -1;
+  bool counted = false;
   while (kLoop ? u < p.units : true) {
     TS_MARK(0);
     const int b = u / at.Hkv, h = u % at.Hkv;
@@ -290,6 +290,7 @@ query_aware_decode_kernel(FusedParams p) {
     KeyLayout kl;
     int L_unit = 0, j_new = -1, slot_new = 0;  // length after the append; the new token's page / slot
     int pb_scan = 0;                         // the unit's page count, known once the scan runs
+    int K_unit = 0;                          // the sequence's page budget (read with the length)
     uint32_t tmin = 0xffffffffu, tmax = 0u;  // this thread's share of the key range
     scan_finish<D, !kLoop, kHalf>(
         scan, p.page_min + (size_t)u * Pmax * D, p.page_max + (size_t)u * Pmax * D, G, Pmax,
@@ -306,12 +307,13 @@ query_aware_decode_kernel(FusedParams p) {
           // using them earlier would put a memory round trip in front of the scan)
           asm volatile("" : "+v"(L_raw), "+v"(K_raw), "+v"(epoch_raw));
           // the tag is fixed by the first unit: the epoch word may already have
-          // been advanced (by the workgroup that counted itself in last) when a
-          // later unit's loads go out
+          // been advanced (by the launch's first workgroup, once it is through
+          // with its own units) when a later unit's loads go out
           // (0 is never a tag: it marks words nobody has written since
           // ts_workspace_init, so the count skips it when it wraps)
           if (tag == 0u) tag = max((uint32_t)uniform(epoch_raw) + 1u, 1u);
           L_unit = uniform(L_raw);
+          K_unit = uniform(K_raw);
           if (app && L_unit / S < Pmax) {  // a sequence with no room left is not extended
             j_new = L_unit / S;
             slot_new = L_unit % S;
@@ -366,13 +368,16 @@ query_aware_decode_kernel(FusedParams p) {
     TS_MARK_WAVE(32);
     const int L = uniform(L_unit);
     const int Pb = uniform(min(pages_of(L, S), Pmax));
-    const int Kb = uniform(max(0, min(min(K_raw, Pb), at.Kmax)));
+    const int Kb = uniform(max(0, min(min(K_unit, Pb), at.Kmax)));
 
     // count this workgroup in (once): it has read the epoch and, in append mode,
-    // the sequence length
+    // the sequence length.  The count's value is not asked for: an atomic that
+    // returns one would hold this wave, and with it the barrier below, for a trip
+    // to memory and back.
     if (!kLoop || exchange) {
-      if (arrived == -1 && threadIdx.x == 0 && (exchange || app))
-        arrived = atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
+      if (!counted && threadIdx.x == 0 && (exchange || app))
+        (void)atomic_add_agent(&p.ctrl[kCtrlArrive], 1);
+      counted = true;
     }
 
     // 2. exchange the scores inside the cluster
@@ -398,30 +403,38 @@ query_aware_decode_kernel(FusedParams p) {
       // launch's tag (all loads of a round in flight together; bounded)
       bool expired = false;
       int spins = 0;
-      for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * 8) {
-        uint64_t v[8];
-        for (;;) {
-          bool all = true;
+      auto poll = [&](auto np_tag) {
+        constexpr int NP = decltype(np_tag)::value;
+        for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * NP) {
+          uint64_t v[NP];
+          for (;;) {
+            bool all = true;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
-            all = all && (uint32_t)(v[i] >> 32) == tag;
+            for (int i = 0; i < NP; ++i) {
+              v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
+              all = all && (uint32_t)(v[i] >> 32) == tag;
+            }
+            if (all) break;
+            if (++spins > p.spin_limit) { expired = true; break; }
+            __builtin_amdgcn_s_sleep(1);
           }
-          if (all) break;
-          if (++spins > p.spin_limit) { expired = true; break; }
-          __builtin_amdgcn_s_sleep(1);
-        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int j = j0 + i * kThreads;
-          if (j < Pb) {
-            const bool always = j < forced.first || j >= forced.last_begin;
-            const uint32_t k = always ? kForcedKey : score_key(__uint_as_float((uint32_t)v[i]));
-            sl.keys[kl.at(j)] = k;
-            atomicAdd(&sl.hist[bin_slot_index(bins.slot<true>(k))], 1u);
+          for (int i = 0; i < NP; ++i) {
+            const int j = j0 + i * kThreads;
+            if (j < Pb) {
+              const bool always = j < forced.first || j >= forced.last_begin;
+              const uint32_t k = always ? kForcedKey : score_key(__uint_as_float((uint32_t)v[i]));
+              sl.keys[kl.at(j)] = k;
+              atomicAdd(&sl.hist[bin_slot_index(bins.slot<true>(k))], 1u);
+            }
           }
         }
-      }
+      };
+      const int per_thread = uniform((Pb + kThreads - 1) / kThreads);
+      if (per_thread <= 1) poll(std::integral_constant<int, 1>{});
+      else if (per_thread <= 2) poll(std::integral_constant<int, 2>{});
+      else if (per_thread <= 4) poll(std::integral_constant<int, 4>{});
+      else poll(std::integral_constant<int, 8>{});
       if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
       TS_MARK(3);
       TS_MARK_WAVE(40);
@@ -499,26 +512,6 @@ query_aware_decode_kernel(FusedParams p) {
     else select_topk_lds<false>(sl, kl, Pb, Kb, forced, keep_page);
     __syncthreads();
     TS_MARK(5);
-    // The workgroup that counted itself in last knows that every other one has
-    // read the epoch word and, with one unit per workgroup, its sequence length:
-    // its first wave re-arms the count, advances the epoch and (append mode)
-    // the lengths, here where the count's return has long arrived and nothing
-    // waits for the few stores.
-    if (wave_id() == 0 && uniform(arrived) == p.n_arrive - 1) {
-      arrived = -2;
-      if (lane_id() == 0) {
-        atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
-        if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
-      }
-      if (app) {
-        int32_t* seq_lens_w = const_cast<int32_t*>(at.seq_lens);
-        for (int i = lane_id(); i < p.B; i += kWave) {
-          const int len = seq_lens_w[i];
-          if (len / S < Pmax) seq_lens_w[i] = len + 1;
-        }
-      }
-    }
-
     // 4. attend my chunk (the wave-merge area reuses the select scratch)
     const size_t new_row = ((size_t)b * at.Hkv + h) * D;
     const NewToken nt{j_new, slot_new, app ? p.k_new + new_row : at.q, app ? p.v_new + new_row : at.q};
@@ -545,6 +538,25 @@ query_aware_decode_kernel(FusedParams p) {
     }
     if (u >= p.units) break;
     issue_unit(u);
+  }
+  // The launch's first workgroup, at the end of its own work, closes the books: once
+  // the count shows that every workgroup has read the epoch word and, with one unit per
+  // workgroup, its sequence length (all of them did so microseconds ago), its first
+  // wave re-arms the count, advances the epoch and (append mode) the lengths.
+  if ((!kLoop || exchange) && (exchange || app) && blockIdx.x == 0 && wave_id() == 0) {
+    if (!wait_at_least(&p.ctrl[kCtrlArrive], p.n_arrive, p.spin_limit))
+      atomic_store_agent(&p.ctrl[kCtrlError], 1);
+    if (lane_id() == 0) {
+      atomic_store_agent(&p.ctrl[kCtrlArrive], 0);
+      if (exchange) atomic_store_agent(&p.ctrl[kCtrlEpoch], (int)tag);
+    }
+    if (app) {
+      int32_t* seq_lens_w = const_cast<int32_t*>(at.seq_lens);
+      for (int i = lane_id(); i < p.B; i += kWave) {
+        const int len = seq_lens_w[i];
+        if (len / S < Pmax) seq_lens_w[i] = len + 1;
+      }
+    }
   }
   if (dynamic) {  // the last workgroup out re-arms the counters for the next launch
     __syncthreads();

@@ -111,8 +111,8 @@ struct MetaTile {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int pg = min(base + u * rstep + prow, Plimit - 1);
-      mn[u] = *reinterpret_cast<const uint4*>(pmin_u + (size_t)pg * D + cg * 8);
-      mx[u] = *reinterpret_cast<const uint4*>(pmax_u + (size_t)pg * D + cg * 8);
+      mn[u] = load_stream16(pmin_u + (size_t)pg * D + cg * 8);
+      mx[u] = load_stream16(pmax_u + (size_t)pg * D + cg * 8);
     }
   }
 
@@ -195,13 +195,28 @@ __device__ __forceinline__ void scan_finish(ScanRegs<D, kHalf>& r, const uint16_
   // only the first tile is fetched blind; later ones stop at the sequence's
   // last page (pages >= Pb still get their -inf through the sink)
   int base = first_iter * PPI * gs + goff * PPW;   // first page of the tile's first group
-  while (base < limit) {
-    const int next = base + iter_stride * PPI * gs;
-    MetaTile<D, kHalf> cur = r.tile;
-    if (kBranchless) r.tile.load(pmin_u, pmax_u, next, max(Pb, 1), rstep);
-    else if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb, rstep);
-    cur.reduce(ql, base, Pb, Pmax, rstep, patch, sink);
-    base = next;
+  if (kBranchless) {
+    // The first tile is reduced whether or not it holds a page below the limit (the sink
+    // sees no page at or past the limit).  With a path around the loop the tile's loads
+    // would still be in flight where the two paths meet, and the compiler, which cannot
+    // count across such a join, would wait there for EVERY outstanding memory operation:
+    // the write-through stores of the scores included, a trip to memory and back in front
+    // of the barrier that follows (measured, with the arrival count below: 0.3-0.5 us).
+    do {
+      const int next = base + iter_stride * PPI * gs;
+      MetaTile<D, kHalf> cur = r.tile;
+      r.tile.load(pmin_u, pmax_u, next, max(Pb, 1), rstep);
+      cur.reduce(ql, base, Pb, min(Pmax, limit), rstep, patch, sink);
+      base = next;
+    } while (base < limit);
+  } else {
+    while (base < limit) {
+      const int next = base + iter_stride * PPI * gs;
+      MetaTile<D, kHalf> cur = r.tile;
+      if (next < Pb) r.tile.load(pmin_u, pmax_u, next, Pb, rstep);
+      cur.reduce(ql, base, Pb, Pmax, rstep, patch, sink);
+      base = next;
+    }
   }
 }
 
