@@ -603,9 +603,8 @@ __device__ __forceinline__ bool merge_tagged(const uint64_t* part, int G, int g,
 // handed to the combining workgroup through agent-scope stores.
 // Ends with a barrier after which `lds` may be reused; on return (n_split > 1)
 // the caller still has to wait for its stores and count its arrival.
-// kBranchless: the ring is refilled without a branch around the loads (see
-// below); with false the refill past the end of the list is skipped instead,
-// which suits bandwidth-bound launches with thousands of units.
+// kLatency: the launch is bound by the latency of its single pass (every workgroup has
+// one unit): the ring waits for each fragment by count (see below).
 // kPatch: a token appended in the same launch may have to be spliced in (nt).
 // kInt8: the cache holds int8 keys / values with per-token scales.
 // kHalf: queries, keys and values are IEEE half instead of bf16.
@@ -616,7 +615,7 @@ __device__ __forceinline__ bool merge_tagged(const uint64_t* part, int G, int g,
 // split keeps its own partial in registers, polls for the others (bounded by
 // spin_limit polls per thread) and writes the unit's output; the function
 // returns false if that wait expired.
-template <int D, int S, bool kBranchless, bool kPatch, bool kInt8, bool kHalf, typename SelAt,
+template <int D, int S, bool kLatency, bool kPatch, bool kInt8, bool kHalf, typename SelAt,
           typename PhysAt>
 __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
@@ -698,11 +697,9 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
     Frag f[NBUF];
     uint32_t vmask[NBUF];
     int item[NBUF];
-    // No branch around a single load (a load under a branch of its own makes the
-    // compiler wait for ALL outstanding loads wherever it needs one of them, so
-    // the ring would drain before the first fragment is used): a slot past the
-    // end of the list, or one whose page id is out of range, re-reads a page that
-    // is certainly mapped (a single cache line of it) and has no valid token.
+    // issue(buffer, item, x): fetch this wave's x-th fragment of the batch.  x >= n, or an
+    // entry whose page id is out of range, re-reads a page that is certainly mapped (a
+    // single cache line of it) and has no valid token: no branch around the loads.
     auto issue = [&](Frag& fr, int& it, int x) -> uint32_t {
       const int xc = min(x, n - 1);
       it = batch + xc * kWaves;
@@ -760,30 +757,68 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
         attend_page<D, F, false, kHalf>(f[i], qf, vmask[i], p.scale_log2, acc);
       }
     };
-    // The first fill.  In the latency-bound builds a wave often has fewer fragments
-    // than buffers (one page, or none): only the fragments that exist are fetched,
-    // each under a uniform test, so all of them are waited for before the first is
-    // used (they were all sent out together anyway), instead of queueing placeholder
-    // loads for the empty buffers behind the compute unit's outstanding misses
-    // (-1.1 us on the 4-sequence long-context batch, -0.5 us on a single sequence).
-    constexpr bool kExactFill = kBranchless;
+    if constexpr (kLatency) {
+      // The ring.  A wait for a fragment can only count the loads sent out after it
+      // ("all but the newest k have arrived") where that number is the same on every path
+      // that leads to the wait; where paths with different numbers meet, the compiler falls
+      // back to waiting for everything in flight, which exposes a full memory latency per
+      // fragment.  So the code is laid out by how many buffers are in use:
+      //   - n >= NBUF: all buffers filled with no test in between; whole rounds (every
+      //     buffer consumed and refilled, no test) as long as a full ring lies ahead; one
+      //     round that consumes every buffer and refills the first `live` of them; then
+      //   - the last `live` < NBUF fragments (also the whole of a short list, fetched
+      //     under a test each): these are waited for together.
+      // No placeholder loads anywhere: a load with nothing to fetch would still queue
+      // behind the compute unit's outstanding misses.
+      int live;   // fragments in buffers 0 .. live - 1 once the rounds are through
+      if (n >= NBUF) {
+  #pragma unroll
+        for (int i = 0; i < NBUF; ++i) vmask[i] = issue(f[i], item[i], i);
+        TS_MARK(17);
+        TS_MARK_WAVE(48);
+        int x0 = 0;
+        for (; x0 + 2 * NBUF <= n; x0 += NBUF) {
+  #pragma unroll
+          for (int i = 0; i < NBUF; ++i) {
+            consume(i);
+            vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
+          }
+        }
+        live = n - x0 - NBUF;
+  #pragma unroll
+        for (int i = 0; i < NBUF; ++i) {
+          consume(i);
+          if (i < live) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
+        }
+      } else {
+        live = n;
+  #pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i)
+          if (i < live) vmask[i] = issue(f[i], item[i], i);
+        TS_MARK(17);
+        TS_MARK_WAVE(48);
+      }
+  #pragma unroll
+      for (int i = 0; i < NBUF - 1; ++i)
+        if (i < live) consume(i);
+    } else {
+      // Bandwidth-bound launches (thousands of units, other workgroups to hide a wave's
+      // waits): every buffer is filled at once (a slot past the end re-reads one cache
+      // line) and refilled under a test of its own, which makes the compiler wait for
+      // everything in flight before each fragment.  Measured on the 64-sequence batch,
+      // that is 2 % FASTER than the counted waits above: with fewer bytes of a wave in
+      // flight, the lines of a key tile, which four instructions come back to, are still
+      // in the L1 when the last of them arrives.
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i)
-      if (!kExactFill || i < n) vmask[i] = issue(f[i], item[i], i);
-    TS_MARK(17);
-    TS_MARK_WAVE(48);
-    for (int x0 = 0; x0 < n; x0 += NBUF) {
-      // kBranchless: a round refills all its buffers or none, on ONE uniform test
-      // per round (does a further round follow?), so that inside a round the
-      // number of loads in flight is the same for every buffer and the last round
-      // issues no loads at all: a refill with nothing to fetch would still have to
-      // queue behind the compute unit's outstanding misses (measured: 0.4 us on
-      // the 16-sequence configuration, 1.3 us on the 8-sequence MHA one).
-      const bool more = x0 + NBUF < n;
+      for (int i = 0; i < NBUF; ++i) vmask[i] = issue(f[i], item[i], i);
+      TS_MARK(17);
+      TS_MARK_WAVE(48);
+      for (int x0 = 0; x0 < n; x0 += NBUF) {
 #pragma unroll
-      for (int i = 0; i < NBUF; ++i) {
-        if (x0 + i < n) consume(i);
-        if (kBranchless ? more : x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
+        for (int i = 0; i < NBUF; ++i) {
+          if (x0 + i < n) consume(i);
+          if (x0 + i + NBUF < n) vmask[i] = issue(f[i], item[i], x0 + i + NBUF);
+        }
       }
     }
     // Every fragment has been consumed, so nothing is in flight here; saying so (a wait
@@ -791,7 +826,7 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
     // closes, that a buffer may still be waiting for a refill: it then drained the memory
     // pipeline in front of each buffer's first fill, so that the ring's fragments were
     // fetched one after the other (-0.3 us on the 16-sequence configuration).
-    if (kBranchless) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
+    if (kLatency) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
   }
 
   TS_MARK(18);
