@@ -286,6 +286,9 @@ static int launch_fused(const ts_layout* layout, const void* k_new, const void* 
   p.S = layout->page_size;
   p.units = pl.units;
   p.g = pl.g;
+  p.div_g = make_fast_div(pl.g);
+  p.div_hkv = make_fast_div(layout->num_kv_heads);
+  p.div_xcds = make_fast_div(1);
   p.spin_limit = layout->wait_limit > 0 ? layout->wait_limit : kSpinLimit;
   const int tuned_per_cu = g_tune_wg_per_cu.load(std::memory_order_relaxed);
   const int per_cu = tuned_per_cu > 0 ? tuned_per_cu : 1;

@@ -118,20 +118,41 @@ __device__ __forceinline__ int wave_inclusive_sum(int v) {
 }
 // Sum over each aligned group of N (8 or 16) lanes, delivered to every lane of
 // the group: butterfly on quad permutes, then the half-row / row mirrors.
+// (the controls used here name a source for every lane, so the destination needs no
+// initial value: one instruction per half)
 template <int CTRL>
 __device__ __forceinline__ double dpp_move_f64(double v) {
-  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+  const int lo = __builtin_amdgcn_mov_dpp(__double2loint(v), CTRL, 0xf, 0xf, true);
+  const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(v), CTRL, 0xf, 0xf, true);
   return __hiloint2double(hi, lo);
 }
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;          // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141, kDppMirror = 0x140;  // lane i <-> 7 - i of 8, 15 - i of 16
+
+// Four values per lane, each to be summed over the aligned group of N (8 or 16) lanes the
+// lane belongs to: returns, in lanes 2u and 2u + 1 of the group's first eight lanes, the
+// sum of v[u].  A butterfly in which every stage halves what a lane still carries (the
+// partner takes over the other half): 4 additions (N = 8) instead of the 12 of four
+// separate sums.
 template <int N>
-__device__ __forceinline__ double group_sum_f64(double v) {
+__device__ __forceinline__ double group_sum4_f64(const double (&v)[4], int lane_in_group) {
   static_assert(N == 8 || N == 16, "group of 8 or 16 lanes");
-  v += dpp_move_f64<0xB1>(v);    // quad_perm [1,0,3,2]
-  v += dpp_move_f64<0x4E>(v);    // quad_perm [2,3,0,1]
-  v += dpp_move_f64<0x141>(v);   // row_half_mirror
-  if (N == 16) v += dpp_move_f64<0x140>(v);  // row_mirror
-  return v;
+  double s[4] = {v[0], v[1], v[2], v[3]};
+  if (N == 16) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s[u] += dpp_move_f64<kDppMirror>(s[u]);
+  }
+  // lanes 0-3 of each eight go on with v[0], v[1], lanes 4-7 with v[2], v[3]
+  const bool upper = (lane_in_group & 4) != 0;
+  double k0 = upper ? s[2] : s[0], k1 = upper ? s[3] : s[1];
+  k0 += dpp_move_f64<kDppHalfMirror>(upper ? s[0] : s[2]);
+  k1 += dpp_move_f64<kDppHalfMirror>(upper ? s[1] : s[3]);
+  // of those, lanes with bit 1 clear go on with the first, the others with the second
+  const bool second = (lane_in_group & 2) != 0;
+  double k = second ? k1 : k0;
+  k += dpp_move_f64<kDppXor2>(second ? k0 : k1);
+  k += dpp_move_f64<kDppXor1>(k);
+  return k;
 }
 
 // Combine a value over the four lanes {l, l^16, l^32, l^48} (the four rows of a
@@ -171,6 +192,26 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast15, 0xa>(0, x));
   x = (int)max((uint32_t)x, (uint32_t)dpp_move<kDppRowBcast31, 0xc>(0, x));
   return (uint32_t)__builtin_amdgcn_readlane(x, 63);
+}
+
+// x / d for 0 <= x < 2^16 and 1 <= d < 2^16 by one multiply, with a constant the host
+// works out: magic = floor(2^32 / d) + 1 (exact as long as x * d < 2^32); 0 stands for
+// d == 1.  The kernels' first instructions run ahead of their first loads, and a
+// division by a run-time value costs some thirty of them.
+struct FastDiv {
+  uint32_t d, magic;
+};
+inline FastDiv make_fast_div(int d) {
+  FastDiv f;
+  f.d = (uint32_t)(d < 1 ? 1 : d);
+  f.magic = f.d == 1 ? 0u : 0xffffffffu / f.d + 1u;
+  return f;
+}
+__device__ __forceinline__ int fast_div(int x, const FastDiv& f) {
+  return f.magic ? (int)__umulhi((uint32_t)x, f.magic) : x;
+}
+__device__ __forceinline__ int fast_mod(int x, const FastDiv& f) {
+  return x - fast_div(x, f) * (int)f.d;
 }
 
 // Streaming loads (the `nt` bit): for lines that ONE instruction of one wave consumes whole

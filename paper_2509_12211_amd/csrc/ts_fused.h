@@ -84,6 +84,7 @@ struct FusedParams {
   int spin_limit;              // polls before a cross-workgroup wait gives up
   int xcds;                    // > 1: clusters laid out one per XCD over that many XCDs (see cluster_of)
   int n_arrive;                // workgroups of the launch that work on a unit
+  FastDiv div_g, div_xcds, div_hkv;   // divisions by g, xcds and the number of KV heads
 };
 
 // Which cluster a workgroup belongs to, and as which member.  The hardware deals
@@ -101,15 +102,17 @@ struct FusedParams {
 // clusters beyond the last unit then have nothing to do.  Otherwise the members
 // are consecutive ids.
 struct ClusterSlot { int cluster, member; };
-__device__ __forceinline__ ClusterSlot cluster_of(int wg, int g, int xcds) {
+__device__ __forceinline__ ClusterSlot cluster_of(int wg, const FastDiv& g, const FastDiv& xcds,
+                                                  bool by_xcd) {
   ClusterSlot c;
-  if (xcds > 1) {
-    const int xcd = wg % xcds, slot = wg / xcds;
-    c.member = slot % g;
-    c.cluster = (slot / g) * xcds + xcd;
+  if (by_xcd) {
+    const int slot = fast_div(wg, xcds), xcd = wg - slot * (int)xcds.d;
+    c.cluster = fast_div(slot, g);
+    c.member = slot - c.cluster * (int)g.d;
+    c.cluster = c.cluster * (int)xcds.d + xcd;
   } else {
-    c.member = wg % g;
-    c.cluster = wg / g;
+    c.cluster = fast_div(wg, g);
+    c.member = wg - c.cluster * (int)g.d;
   }
   return c;
 }
@@ -204,12 +207,13 @@ query_aware_decode_kernel(FusedParams p) {
   TS_MARK(22);
   const AttendParams& at = p.at;
   const int g = kCluster ? p.g : 1, G = at.G, Pmax = at.Pmax;
-  const ClusterSlot where = cluster_of(blockIdx.x, g, kCluster ? p.xcds : 0);
+  const ClusterSlot where = kCluster ? cluster_of(blockIdx.x, p.div_g, p.div_xcds, p.xcds > 1)
+                                     : ClusterSlot{(int)blockIdx.x, 0};
   const int member = kCluster ? where.member : 0;
-  const int n_clusters = gridDim.x / g;
+  const int n_clusters = kCluster ? fast_div(gridDim.x, p.div_g) : (int)gridDim.x;
   // (a launch laid out by XCD is padded to whole rounds of the XCDs: clusters past
-  // the last unit leave at once, before any barrier, and are not counted in)
-  if (kCluster && !kLoop && where.cluster >= p.units) return;
+  // the last unit leave before any barrier, see below, and are not counted in)
+  const bool padding = kCluster && !kLoop && where.cluster >= p.units;
   const SelectLds sl = carve_select(smem, Pmax);
   const size_t sel_bytes = select_lds_bytes(Pmax);
   const size_t att_bytes = (size_t)kWaves * G * (D + 2) * 4;
@@ -224,7 +228,7 @@ query_aware_decode_kernel(FusedParams p) {
   // contended, and the spread of sequence lengths no longer decides the finish
   // time.  Nothing ever waits on a ticket holder.
   const bool dynamic = kLoop && !exchange && p.units > (int)gridDim.x;
-  int u = where.cluster;
+  int u = padding ? 0 : where.cluster;
   if (dynamic) {
     if (threadIdx.x == 0) s_flag = atomic_add_agent(&p.ctrl[kCtrlTicket], 1);
     __syncthreads();
@@ -253,7 +257,7 @@ query_aware_decode_kernel(FusedParams p) {
   constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
   uint4 kn16 = make_uint4(0, 0, 0, 0), vn16 = make_uint4(0, 0, 0, 0);
   auto issue_unit = [&](int uu) {
-    const int b = uu / at.Hkv, h = uu % at.Hkv;
+    const int b = fast_div(uu, p.div_hkv), h = uu - b * at.Hkv;
     epoch_raw = p.ctrl[kCtrlEpoch];
     L_raw = at.seq_lens[b];
     K_raw = p.topk_per_seq ? p.topk_per_seq[b] : p.topk;
@@ -271,6 +275,10 @@ query_aware_decode_kernel(FusedParams p) {
                        Pmax, wave_id(), g, member);
   };
   if (kLoop ? u < p.units : true) issue_unit(u);   // the host launches no idle cluster
+  // (a padding workgroup leaves only here, behind the loads of unit 0, whose results it
+  // drops: with an exit ahead of them the kernel's arguments would be fetched in two
+  // dependent trips, the second one behind the test)
+  if (padding) return;
   TS_MARK(23);
 
   // Launch tag of the score exchange.  The epoch word is read by every
@@ -281,7 +289,7 @@ query_aware_decode_kernel(FusedParams p) {
   bool counted = false;
   while (kLoop ? u < p.units : true) {
     TS_MARK(0);
-    const int b = u / at.Hkv, h = u % at.Hkv;
+    const int b = fast_div(u, p.div_hkv), h = u - b * at.Hkv;
     const int32_t* bt_row = at.block_table + (size_t)b * Pmax;
     uint64_t* srow = p.scores + (size_t)u * Pmax;
     float* srow_out = p.scores_out ? p.scores_out + (size_t)u * Pmax : nullptr;
@@ -673,6 +681,7 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
     if (kCluster && xcds > 1 && (int)padded <= cap1) {
       grid = padded;
       p.xcds = xcds;
+      p.div_xcds = make_fast_div(xcds);
     }
     if (p.k_new)
       app_kernel<<<grid, kThreads, pl.lds_fused, s>>>(p);
@@ -688,6 +697,7 @@ static int launch_fused_shape(const ts_layout* layout, FusedParams& p, const Pla
   if (kCluster && xcds > 1 && clusters >= xcds) {
     clusters = clusters / xcds * xcds;
     p.xcds = xcds;
+    p.div_xcds = make_fast_div(xcds);
   }
   p.n_arrive = clusters * pl.g;
   loop_kernel<<<(unsigned)(clusters * pl.g), kThreads, pl.lds_fused, s>>>(p);

@@ -40,7 +40,8 @@ struct ScoreLanes {
   struct QueryRegs { uint4 w[kQueryLoads]; };
 
   // Every thread loads and every thread stages what it loaded (thread i takes
-  // chunk i modulo the number of chunks; duplicates carry identical data): a
+  // chunk i, threads past the last chunk take the last one again; duplicates carry
+  // identical data): a
   // load under a branch makes the compiler wait for ALL outstanding loads
   // wherever it needs one of them, instead of counting, and a load whose only
   // use sits under a branch is moved down into that branch.
@@ -48,7 +49,7 @@ struct ScoreLanes {
     const int n16 = G * D / 8;
 #pragma unroll
     for (int k = 0; k < kQueryLoads; ++k)
-      r.w[k] = reinterpret_cast<const uint4*>(q_group)[(threadIdx.x + k * kThreads) % n16];
+      r.w[k] = reinterpret_cast<const uint4*>(q_group)[min((int)threadIdx.x + k * kThreads, n16 - 1)];
   }
 
   // Two barriers.
@@ -58,7 +59,7 @@ struct ScoreLanes {
     const int n16 = G * D / 8;
 #pragma unroll
     for (int k = 0; k < kQueryLoads; ++k) {
-      raw[(threadIdx.x + k * kThreads) % n16] = r.w[k];
+      raw[min((int)threadIdx.x + k * kThreads, n16 - 1)] = r.w[k];
     }
     TS_MARK(20);
     __syncthreads();
@@ -80,15 +81,19 @@ struct ScoreLanes {
     for (int i = 0; i < 8; ++i) { qp[i] = red[cg * 8 + i]; qn[i] = red[D + cg * 8 + i]; }
   }
 
+  // Two chains of eight (the max terms, the min terms) instead of one of sixteen: with
+  // four rows a wave has eight independent chains to interleave.
   __device__ __forceinline__ double row_partial(const uint4& mn, const uint4& mx) const {
     float lo[8], hi[8];
     unpack8e<kHalf>(mn, lo);
     unpack8e<kHalf>(mx, hi);
-    double s = 0.0;
+    double sp = 0.0, sn = 0.0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      s = fma(qp[i], static_cast<double>(hi[i]), fma(qn[i], static_cast<double>(lo[i]), s));
-    return s;
+    for (int i = 0; i < 8; ++i) {
+      sp = fma(qp[i], static_cast<double>(hi[i]), sp);
+      sn = fma(qn[i], static_cast<double>(lo[i]), sn);
+    }
+    return sp + sn;
   }
 };
 
@@ -116,21 +121,25 @@ struct MetaTile {
     }
   }
 
-  // sink(page, score) is called once per page < Pmax by one lane; pages >= Pb
-  // get -inf.  patch(min_row, max_row, page) may first amend the row chunks this
-  // lane holds (a token appended in the same launch).
+  // sink(page, score) is called once per page < Pmax by one lane (a lane takes at most
+  // one page of the tile); pages >= Pb get -inf.  patch(min_row, max_row, page) may first
+  // amend the row chunks this lane holds (a token appended in the same launch).
   template <typename Patch, typename Sink>
   __device__ __forceinline__ void reduce(const ScoreLanes<D, kHalf>& ql, int base, int Pb, int Pmax,
                                          int rstep, Patch patch, Sink sink) {
     constexpr int LPR = ScoreLanes<D, kHalf>::LPR;
+    static_assert(U == 4, "group_sum4_f64 folds four rows");
     const int lane = lane_id(), cg = lane % LPR, prow = lane / LPR;
+    double part[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int pg = base + u * rstep + prow;
-      patch(mn[u], mx[u], pg);
-      const double s = group_sum_f64<LPR>(ql.row_partial(mn[u], mx[u]));
-      if (cg == 0 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
+      patch(mn[u], mx[u], base + u * rstep + prow);
+      part[u] = ql.row_partial(mn[u], mx[u]);
     }
+    const double s = group_sum4_f64<LPR>(part, cg);
+    // lanes 0, 2, 4, 6 of a page's lanes hold the sums of rows 0, 1, 2, 3
+    const int pg = base + (cg >> 1) * rstep + prow;
+    if ((cg & 1) == 0 && cg < 8 && pg < Pmax) sink(pg, pg < Pb ? static_cast<float>(s) : -INFINITY);
   }
 };
 
