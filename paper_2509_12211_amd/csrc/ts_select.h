@@ -191,9 +191,11 @@ __device__ __forceinline__ void select_deposited_range(const SelectLds& L, uint3
 // would put a whole binade, or everything on one side of zero, into a handful
 // of bins).  Every wave then finds the cut-off bin for itself (no exchange
 // between waves, no barrier).  If that bin has to be split, its few pages are
-// listed in LDS and every wave ranks them directly; only a cut-off bin with
-// more than kMaxCandidates pages (heavy ties) goes through exact radix passes
-// on the integer keys instead.
+// listed in LDS and every wave ranks them directly; the list and the per-wave
+// counts of the pages above the bin share ONE barrier, behind which a page's place
+// in the ascending list follows without a further exchange.  Only a cut-off bin
+// with more than kMaxCandidates pages (heavy ties) goes through exact radix passes
+// on the integer keys and a separate compaction instead.
 //
 // fp: the always-kept pages (their keys become kForcedKey: linear_slot puts them
 // into the top bin, everything after that works on the integer keys).
@@ -303,12 +305,8 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const BinMap bins = kCounted ? counted : BinMap::exact(kmin, kmax);
   auto linear_slot = [&](uint32_t k) { return bins.template slot<kCounted>(k); };
   int need = Kb, cut_slot = 0;
-  // how the pages at the cut are told apart from those above it
-  enum { kWholeSlot, kThreshold, kRadix } mode = kWholeSlot;
-  uint32_t key_t = 0u;        // kThreshold: kept iff (key, -page) >= (key_t, -page_t)
-  int page_t = 0;
-  uint32_t clo = kmin, chi = kmax, base = 0u;  // kRadix
-  int bits = 0;
+  uint32_t clo = kmin, chi = kmax, base = 0u;  // stage 2b: the keys still undecided are
+  int bits = 0;                                // those k with k - clo in [base, base + 2^bits)
   if (kmax > kmin) {
     if (!kCounted) {
       for_my_keys([&](uint32_t k, int) { atomicAdd(&L.hist[bin_slot_index(linear_slot(k))], 1u); });
@@ -319,34 +317,72 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     find_cut(need, cut_slot, above, cnt);
     TS_MARK(12);
     need -= above;
-    if (cnt == need) {
-      mode = kWholeSlot;
-    } else if (cnt <= kMaxCandidates) {
-      // ---- stage 2a: list the cut-off bin's pages, every wave ranks them -------
-      mode = kThreshold;
+    if (cnt == need || cnt <= kMaxCandidates) {
+      // ---- stage 2a, the usual case: the cut-off bin is kept whole, or holds few enough
+      // pages to list them.  ONE pass over the keys and ONE barrier: every thread marks
+      // the pages of its chunk that are kept for certain (above the cut-off bin), lists
+      // those in the bin, and the per-wave counts of the certain ones go out with the
+      // list.  Behind the barrier every wave ranks the listed pages by itself; a page's
+      // place in the ascending list is then the certain pages before it (a prefix over
+      // the threads) plus the listed pages kept before it (counted off the list).
+      const bool whole = uniform(cnt == need ? 1 : 0) != 0;
+      uint64_t sbits = 0, cbits = 0;   // chunk masks (C <= 64): kept for certain / in the cut-off bin
       for_my_keys([&](uint32_t k, int i) {
-        if (linear_slot(k) == cut_slot) {
+        const int s = linear_slot(k);
+        const bool in_cut = s == cut_slot;
+        sbits |= (uint64_t)((s < cut_slot || (whole && in_cut)) ? 1 : 0) << i;
+        if (!whole && in_cut) {
+          cbits |= 1ull << i;
           const int at = atomicAdd(&L.red[40], 1);
           L.cand[2 * at] = k;
           L.cand[2 * at + 1] = (uint32_t)(my_first + i);
         }
       });
+      const int cs = __popcll(sbits);
+      int incl = wave_inclusive_sum(cs);
+      if (lane == kWave - 1) L.red[wave] = incl;   // slots 0..7 are used by nothing else
       __syncthreads();
-      const uint32_t ck = lane < cnt ? L.cand[2 * lane] : 0u;
-      const int cp = lane < cnt ? (int)L.cand[2 * lane + 1] : 0x7fffffff;
-      int rank = 0;  // candidates that come before mine (higher key, or equal key and lower page)
-      for (int t = 0; t < cnt; ++t) {
-        const uint32_t ok = (uint32_t)__builtin_amdgcn_readlane((int)ck, t);
-        const int op = __builtin_amdgcn_readlane(cp, t);
-        rank += (ok > ck || (ok == ck && op < cp)) ? 1 : 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const int t = uniform(L.red[w]);
+        if (w < wave) incl += t;
       }
-      const uint64_t mt = __ballot(lane < cnt && rank == need - 1);
-      const int tl = mt ? __builtin_ctzll(mt) : 0;
-      key_t = (uint32_t)__builtin_amdgcn_readlane((int)ck, tl);
-      page_t = __builtin_amdgcn_readlane(cp, tl);
+      TS_MARK(13);
+      int rank = incl - cs;   // certain pages before this thread's chunk
+      uint64_t gbits = sbits;
+      if (!whole) {
+        const uint32_t ck = lane < cnt ? L.cand[2 * lane] : 0u;
+        const int cp = lane < cnt ? (int)L.cand[2 * lane + 1] : 0x7fffffff;
+        int before = 0;  // listed pages that come before mine (higher key, or equal key and lower page)
+        for (int t = 0; t < cnt; ++t) {
+          const uint32_t ok = (uint32_t)__builtin_amdgcn_readlane((int)ck, t);
+          const int op = __builtin_amdgcn_readlane(cp, t);
+          before += (ok > ck || (ok == ck && op < cp)) ? 1 : 0;
+        }
+        const int kept = (lane < cnt && before < need) ? 1 : 0;   // the listed page in this lane is kept
+        const uint64_t mt = __ballot(lane < cnt && before == need - 1);
+        const int tl = mt ? __builtin_ctzll(mt) : 0;
+        const uint32_t key_t = (uint32_t)__builtin_amdgcn_readlane((int)ck, tl);
+        const int page_t = __builtin_amdgcn_readlane(cp, tl);
+        // listed pages kept in the chunks before mine
+        for (int t = 0; t < cnt; ++t) {
+          const int kt = __builtin_amdgcn_readlane(kept, t);
+          const int op = __builtin_amdgcn_readlane(cp, t);
+          rank += (kt != 0 && op < my_first) ? 1 : 0;
+        }
+        // my own listed pages: kept iff at or before the threshold
+        for (uint64_t todo = cbits; todo != 0; todo &= todo - 1) {
+          const int i = __builtin_ctzll(todo);
+          const uint32_t k = my_keys[i];
+          const int page = my_first + i;
+          if (k > key_t || (k == key_t && page <= page_t)) gbits |= 1ull << i;
+        }
+      }
+      TS_MARK(14);
+      for (uint64_t todo = gbits; todo != 0; todo &= todo - 1) emit(rank++, my_first + __builtin_ctzll(todo));
+      return;
     } else {
       // ---- stage 2b: exact radix passes on the keys of the cut-off bin ----------
-      mode = kRadix;
       __syncthreads();  // every wave has read the stage-1 counts
       clear_bins();
       clo = 0xffffffffu;
@@ -377,40 +413,21 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     }
   }
   TS_MARK(13);
-  // Kept for certain (g) / kept while the quota `need` lasts, in page order (e):
-  //   kWholeSlot  g: slot at or above the cut-off slot (need == its size)
-  //   kThreshold  g: (key, page) at or before the threshold in the order above
-  //   kRadix      g: above the cut;  e: keys k with k - clo in [base, base + 2^bits),
-  //               one exact value when bits == 0
-  // (all keys equal: kRadix with bits == 0, every page is e)
-  if (!(kmax > kmin)) {  // all scores equal: the always-kept pages, then the lowest ids
-    mode = kRadix;
-    need = Kb - fp.count;
-  }
+  // Heavy ties (or all scores equal).  Kept for certain (g): above the cut; kept while the
+  // quota `need` lasts, in page order (e): keys k with k - clo in [base, base + 2^bits),
+  // one exact value when bits == 0.
+  if (!(kmax > kmin)) need = Kb - fp.count;  // all scores equal: the always-kept pages, then the lowest ids
   // Ordered compaction in one pass: every thread classifies its own chunk of
   // consecutive pages (bit masks in registers), a workgroup scan of the packed
   // counts gives its starting offsets, and it emits its kept pages in order.
-  // (One loop per mode: the test of the mode stays outside the pass over the keys,
-  // and the two common modes carry no e class.)
   uint64_t gbits = 0, ebits = 0;  // chunk masks (C <= 64)
-  if (mode == kWholeSlot) {
-    for_my_keys([&](uint32_t k, int i) {
-      gbits |= (uint64_t)(linear_slot(k) <= cut_slot ? 1 : 0) << i;
-    });
-  } else if (mode == kThreshold) {
-    for_my_keys([&](uint32_t k, int i) {
-      const int page = my_first + i;
-      gbits |= (uint64_t)((k > key_t || (k == key_t && page <= page_t)) ? 1 : 0) << i;
-    });
-  } else {
-    for_my_keys([&](uint32_t k, int i) {
-      const uint32_t nk = k - clo, d = nk - base;
-      const bool inside = bits >= 32 || (d >> bits) == 0u;
-      const bool in = k >= clo && k <= chi && nk >= base;
-      gbits |= (uint64_t)((k > chi || (in && !inside)) ? 1 : 0) << i;
-      ebits |= (uint64_t)((in && inside) ? 1 : 0) << i;
-    });
-  }
+  for_my_keys([&](uint32_t k, int i) {
+    const uint32_t nk = k - clo, d = nk - base;
+    const bool inside = bits >= 32 || (d >> bits) == 0u;
+    const bool in = k >= clo && k <= chi && nk >= base;
+    gbits |= (uint64_t)((k > chi || (in && !inside)) ? 1 : 0) << i;
+    ebits |= (uint64_t)((in && inside) ? 1 : 0) << i;
+  });
   const int cg = __popcll(gbits), ce = __popcll(ebits);
   const int packed = cg | (ce << 16);  // both sums stay below 2^15
   int incl = wave_inclusive_sum(packed);
@@ -425,17 +442,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
   const int excl = incl - packed;
   const int goff = excl & 0xffff, eoff = excl >> 16;
   // only the marked pages are visited (few threads hold any when K << P)
-  if (mode != kRadix) {   // no e class: the kept pages are the g pages, in order
-    int rank = goff;
-    for (uint64_t todo = gbits; todo != 0; todo &= todo - 1) emit(rank++, my_first + __builtin_ctzll(todo));
-  } else {
-    for (uint64_t todo = gbits | ebits; todo != 0; todo &= todo - 1) {
-      const int i = __builtin_ctzll(todo);
-      const uint64_t below = (1ull << i) - 1;
-      const int gb = goff + __popcll(gbits & below), eb = eoff + __popcll(ebits & below);
-      if ((gbits >> i) & 1) emit(gb + min(eb, need), my_first + i);
-      else if (eb < need) emit(gb + eb, my_first + i);
-    }
+  for (uint64_t todo = gbits | ebits; todo != 0; todo &= todo - 1) {
+    const int i = __builtin_ctzll(todo);
+    const uint64_t below = (1ull << i) - 1;
+    const int gb = goff + __popcll(gbits & below), eb = eoff + __popcll(ebits & below);
+    if ((gbits >> i) & 1) emit(gb + min(eb, need), my_first + i);
+    else if (eb < need) emit(gb + eb, my_first + i);
   }
 }
 
