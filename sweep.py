@@ -51,7 +51,7 @@ def measure(torch, ts, wl, spec, steps, dev):
     reps = max(1, steps // per_graph)
     spec = wl.scaled(spec, headroom=max(64, 3 * (reps + 3) * (per_graph // n_layers) + 8))
     layers = [bench.Layer(ts, wl, spec, 1000 + 17 * i, dev, 1) for i in range(n_layers)]
-    g = bench.capture_graph(torch, layers, lambda ly, st: ly.both(st, 0), per_graph)
+    g = bench.capture_graph(torch, layers, lambda ly, st, qi: ly.both(st, 0), per_graph)
     g.replay()
     wall, _ = bench.time_region(torch, lambda i: g.replay(), reps)
     step_us = wall / (reps * per_graph) * 1e6
