@@ -351,25 +351,22 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
       int rank = incl - cs;   // certain pages before this thread's chunk
       uint64_t gbits = sbits;
       if (!whole) {
+        // a listed page as one 64-bit number that sorts the way the selection does
+        // (higher key first, then lower page): key in the upper half, ~page in the lower
         const uint32_t ck = lane < cnt ? L.cand[2 * lane] : 0u;
         const int cp = lane < cnt ? (int)L.cand[2 * lane + 1] : 0x7fffffff;
-        int before = 0;  // listed pages that come before mine (higher key, or equal key and lower page)
+        const uint64_t mine = ((uint64_t)ck << 32) | (uint32_t)~cp;
+        int before = 0;  // listed pages that come before the one in this lane
         for (int t = 0; t < cnt; ++t) {
-          const uint32_t ok = (uint32_t)__builtin_amdgcn_readlane((int)ck, t);
-          const int op = __builtin_amdgcn_readlane(cp, t);
-          before += (ok > ck || (ok == ck && op < cp)) ? 1 : 0;
+          const uint64_t other = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)ck, t) << 32) |
+                                 (uint32_t)~__builtin_amdgcn_readlane(cp, t);
+          before += other > mine ? 1 : 0;
         }
-        const int kept = (lane < cnt && before < need) ? 1 : 0;   // the listed page in this lane is kept
+        const bool kept = lane < cnt && before < need;   // the listed page in this lane is kept
         const uint64_t mt = __ballot(lane < cnt && before == need - 1);
         const int tl = mt ? __builtin_ctzll(mt) : 0;
         const uint32_t key_t = (uint32_t)__builtin_amdgcn_readlane((int)ck, tl);
         const int page_t = __builtin_amdgcn_readlane(cp, tl);
-        // listed pages kept in the chunks before mine
-        for (int t = 0; t < cnt; ++t) {
-          const int kt = __builtin_amdgcn_readlane(kept, t);
-          const int op = __builtin_amdgcn_readlane(cp, t);
-          rank += (kt != 0 && op < my_first) ? 1 : 0;
-        }
         // my own listed pages: kept iff at or before the threshold
         for (uint64_t todo = cbits; todo != 0; todo &= todo - 1) {
           const int i = __builtin_ctzll(todo);
@@ -377,6 +374,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
           const int page = my_first + i;
           if (k > key_t || (k == key_t && page <= page_t)) gbits |= 1ull << i;
         }
+        // listed pages kept in the chunks before mine: those of the waves before mine (the
+        // owner of page p is thread p / C; one ballot over the list), and those of the
+        // lanes before mine in my own wave, which are these lanes' own (a scan)
+        const int owner_wave = (C == 1 ? cp : (int)__umulhi((uint32_t)cp, kl.magic)) >> 6;
+        const int own = __popcll(gbits & ~sbits);
+        rank += __popcll(__ballot(kept && owner_wave < wave)) + (wave_inclusive_sum(own) - own);
       }
       TS_MARK(14);
       for (uint64_t todo = gbits; todo != 0; todo &= todo - 1) emit(rank++, my_first + __builtin_ctzll(todo));
