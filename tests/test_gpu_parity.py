@@ -220,6 +220,44 @@ def test_select_on_given_scores_is_exact(oracle, built):
         assert np.array_equal(sel.cpu().numpy(), osel), (per_seq, kf, kl)
 
 
+@pytest.mark.parametrize("crowd", [2, 9, 24, 32, 33, 200])
+def test_select_with_a_crowded_cut_off_bin(oracle, built, crowd):
+    """The cut falls into a bin that holds `crowd` pages with distinct scores a hair apart
+    (up to 32 are listed and ranked, more go through the exact passes), owned by threads
+    of several waves and, some of them, by one thread; every rank offset behind them must
+    still come out right: the lists are the oracle's, bit for bit."""
+    print(f"[case] crowded cut-off bin {crowd}", flush=True)
+    B, Hkv, S, Pmax, Kmax = 3, 2, 16, 4096, 512
+    rng = np.random.default_rng(1000 + crowd)
+    lens = np.array([4096 * 16, 3000 * 16 + 5, 4096 * 16], dtype=np.int32)
+    sc = (rng.random((B, Hkv, Pmax)) * 0.8).astype(np.float32)
+    n_sure = 150
+    need = max(1, crowd // 3)
+    for b in range(B):
+        Pb = -(-int(lens[b]) // S)
+        for h in range(Hkv):
+            pages = rng.permutation(Pb)
+            sure, rest = pages[:n_sure], pages[n_sure:]
+            sc[b, h, sure] = (0.95 + 0.05 * rng.random(n_sure)).astype(np.float32)
+            # the crowd: a run of consecutive pages (one thread owns several), the rest scattered
+            start = int(rest[0]) // 8 * 8
+            run = [p for p in range(start, min(start + 6, Pb)) if p not in set(sure.tolist())]
+            others = [int(p) for p in rest[1:] if p not in run][:max(0, crowd - len(run))]
+            members = (run + others)[:crowd]
+            sc[b, h, members] = (0.9 + 1e-6 * rng.permutation(len(members))).astype(np.float32)
+    topk = n_sure + need
+    lens_d = torch.from_numpy(lens).to(DEV)
+    lay = ts.make_layout(B, Hkv, Hkv, 64, S, Pmax, None, None, None, lens_d, None, None)
+    lay.num_phys_pages = 1      # no pool is read by the selection
+    sel = torch.full((B, Hkv, Kmax), -7, dtype=torch.int32, device=DEV)
+    cnt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ts.select_topk_pages(lay, torch.from_numpy(sc).to(DEV), topk, Kmax, sel, cnt)
+    torch.cuda.synchronize()
+    osel, ocnt, _ = oracle.select_topk_pages(sc.astype(np.float64), lens, S, topk, Kmax)
+    assert np.array_equal(cnt.cpu().numpy(), ocnt)
+    assert np.array_equal(sel.cpu().numpy(), osel)
+
+
 @pytest.mark.parametrize("name,keep", [("mha_d64_s16", (1, 2)), ("gqa8_d64_s32_walk", (2, 0)),
                                        ("mha_d128_s16_ragged", (0, 3)), ("gqa8_d64_s4", (4, 8)),
                                        ("gqa4_d64_s64", (1, 1)), ("k_exceeds_p", (3, 3)),
@@ -883,6 +921,28 @@ def test_one_workgroup_per_unit_on_request(oracle, built, name):
             compare_units(oracle, sess, units, scale, what=f"cluster_size={cs}/{name}")
     finally:
         ts.set_tuning(0, 0, 0)
+
+
+@pytest.mark.parametrize("topk", [3, 12, 31, 32, 33, 64, 72, 130, 257])
+@pytest.mark.parametrize("cluster", [1, 2])
+def test_every_length_of_a_wave_s_fragment_list(oracle, built, topk, cluster):
+    """The attention's ring of buffers is laid out by how many of them are in use: fewer
+    fragments than buffers, exactly a ring, whole rounds, a round refilled in part, a last
+    partial ring.  With one or two workgroups per unit and these budgets a wave gets 0 to
+    33 fragments, which walks through every one of those paths (S = 16, one page a fragment)."""
+    print(f"[case] ring topk={topk} cluster={cluster}", flush=True)
+    spec = wl.WorkloadSpec("ring", 2, 8, 2, 64, 16, 6000, topk, keys="walk", headroom=40)
+    w = wl.make_workload(spec, DEV, seed=500 + topk, n_q=1, n_new=1)
+    units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
+    scale = 1.0 / math.sqrt(spec.d)
+    sess = Session(w, cluster_size=cluster)
+    ts.build_page_meta(sess.layout)
+    sess.fused(scale)
+    compare_units(oracle, sess, units, scale, what=f"ring/topk={topk}/cluster={cluster}")
+    fused_out = sess.out.clone()
+    sess.staged(scale)     # the staged attention kernel walks the same ring
+    compare_units(oracle, sess, units, scale, what=f"ring/topk={topk}/staged")
+    assert torch.equal(sess.out, fused_out) or float((sess.out - fused_out).abs().max()) <= 2e-3
 
 
 def test_an_expired_wait_raises_the_sticky_word_and_the_launch_still_ends(oracle, built):
