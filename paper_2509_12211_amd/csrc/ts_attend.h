@@ -544,9 +544,15 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
 
 // Partials handed on as tagged words (attend_split with a tag): merges the first
 // `n` partials of a unit into the running state (M, Lsum, O) of head g, channel c.
-// The thread polls the words it needs until all carry this launch's tag, so the
-// data arrive with the flag, in one trip through the memory system, with no
-// counter and no wait for store acknowledgements on the producers' side.
+// The words are polled until all carry this launch's tag, so the data arrive with the
+// flag, in one trip through the memory system, with no counter and no wait for store
+// acknowledgements on the producers' side.  To be called by whole waves whose threads
+// share the head g (D is a multiple of the wave size).  What a round of polls costs
+// grows with the loads in it (measured: 24 agent-scope loads per thread take 1.7 us to
+// come back, 8 take under 1), so a thread fetches its own channel of every partial,
+// the head's max and sum are fetched once per wave (lane i: the max of partial i, lane
+// 32 + i: its sum) and handed round in registers, and a round asks only for what the
+// rounds before have not brought.
 // `spins` counts the polls of this thread against spin_limit; returns false if
 // the bounded wait expired (the state is then invalid).
 // NB: partials polled together (all their loads in flight at once).
@@ -554,40 +560,82 @@ template <int D, int NB>
 __device__ __forceinline__ bool merge_tagged(const uint64_t* part, int G, int g, int c, int n,
                                              uint32_t tag, int spin_limit, int& spins, float& M,
                                              float& Lsum, float& O) {
+  static_assert(D % kWave == 0 && NB <= 16, "a wave works on one head; lanes i and 32 + i serve partial i");
   constexpr int RS = D + 2;
+  const int lane = lane_id();
   bool ok = true;
+  // (the empty asm keeps the address arithmetic below from being moved up in front of
+  // the attention, where it would only hold registers)
+  asm volatile("" : "+v"(c));
+  const uint32_t off_o = (uint32_t)(g * RS + c);            // this thread's word of a partial
+  const uint32_t stride = (uint32_t)(G * RS);               // words per partial
   for (int s0 = 0; s0 < n; s0 += NB) {
-    uint64_t o[NB], m[NB], l[NB];
-    for (;;) {
-      bool all = true;
+    const int nb = uniform(min(NB, n - s0));
+    // the head's running max and sum of the batch's partials: lane i holds the max of
+    // partial s0 + i, lane 32 + i its sum (one load for the wave instead of two per
+    // partial and thread)
+    const bool ml_role = (lane & 31) < nb;
+    const uint64_t* base = part + (size_t)s0 * stride;      // (uniform)
+    const uint32_t off_ml = (uint32_t)(ml_role ? (lane & 31) : 0) * stride + (uint32_t)(g * RS + D + (lane >> 5));
+    uint64_t ml = 0, v[NB];
 #pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        const bool on = s0 + i < n;  // rows past the end re-read row 0
-        const uint64_t* row = part + ((size_t)(on ? s0 + i : 0) * G + g) * RS;
-        o[i] = load_agent_u64(row + c);
-        m[i] = load_agent_u64(row + D);
-        l[i] = load_agent_u64(row + D + 1);
-        all = all && (uint32_t)(o[i] >> 32) == tag && (uint32_t)(m[i] >> 32) == tag &&
-              (uint32_t)(l[i] >> 32) == tag;
-      }
-      if (all) break;
+    for (int i = 0; i < NB; ++i) v[i] = 0;
+    // bit i: partial s0 + i has not arrived yet; bit 31: this lane's max / sum word
+    uint32_t pending = ((1u << nb) - 1u) | (ml_role ? 0x80000000u : 0u);
+    for (;;) {
+      // only what has not arrived yet is asked for again: a round's cost grows with the
+      // loads in it, and the last rounds wait for one or two late members
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+        if ((pending >> i) & 1u) v[i] = load_agent_u64(base + (size_t)i * stride + off_o);
+      if (pending >> 31) ml = load_agent_u64(base + off_ml);
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+        if ((uint32_t)(v[i] >> 32) == tag) pending &= ~(1u << i);
+      if ((uint32_t)(ml >> 32) == tag) pending &= 0x7fffffffu;
+      if (__ballot(pending != 0u) == 0ull) break;   // the wave leaves together
       if (++spins > spin_limit) { ok = false; break; }
       __builtin_amdgcn_s_sleep(1);
     }
+    // merged in the order of the partials, whatever order they arrived in
+    const uint32_t mlw = (uint32_t)ml;
     float Mn = M;
+    if constexpr (NB <= 4) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
-      if (s0 + i < n) Mn = fmaxf(Mn, __uint_as_float((uint32_t)m[i]));
-    const float sc = __builtin_amdgcn_exp2f(M - Mn);
-    Lsum *= sc;
-    O *= sc;
+      for (int i = 0; i < NB; ++i)
+        if (i < nb) Mn = fmaxf(Mn, __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)mlw, i)));
+      const float sc = __builtin_amdgcn_exp2f(M - Mn);
+      Lsum *= sc;
+      O *= sc;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      if (s0 + i < n) {
-        const float wgt = __builtin_amdgcn_exp2f(__uint_as_float((uint32_t)m[i]) - Mn);
-        Lsum += __uint_as_float((uint32_t)l[i]) * wgt;
-        O += __uint_as_float((uint32_t)o[i]) * wgt;
+      for (int i = 0; i < NB; ++i) {
+        if (i < nb) {
+          const float mi = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)mlw, i));
+          const float li = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)mlw, 32 + i));
+          const float wgt = __builtin_amdgcn_exp2f(mi - Mn);
+          Lsum += li * wgt;
+          O += __uint_as_float((uint32_t)v[i]) * wgt;
+        }
       }
+    } else {
+      // a large batch: the weights are worked out side by side, lane i that of partial
+      // s0 + i, and a thread then needs one broadcast and one multiply-add per partial
+      const float mval = (lane < 32 && ml_role) ? __uint_as_float(mlw) : -INFINITY;
+      Mn = fmaxf(M, wave_max_f32(mval));
+      const float wgt = __builtin_amdgcn_exp2f(mval - Mn);   // 0 in the lanes without a partial
+      // lane 32 + i needs the weight of lane i: the halves swapped and added (the upper
+      // half holds zeros)
+      const uint2s_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(wgt), __float_as_uint(wgt), false, false);
+      const float wgt_both = __uint_as_float(r.x) + __uint_as_float(r.y);
+      const float lnew = wave_sum_f32((lane >= 32 && ml_role) ? __uint_as_float(mlw) * wgt_both : 0.f);
+      const float sc = __builtin_amdgcn_exp2f(M - Mn);
+      Lsum = Lsum * sc + lnew;
+      O *= sc;
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+        if (i < nb)
+          O += __uint_as_float((uint32_t)v[i]) *
+               __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(wgt), i));
     }
     M = Mn;
   }
@@ -879,11 +927,10 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
       uint64_t* unit64 = reinterpret_cast<uint64_t*>(p.partials) +
                          ((size_t)b * p.Hkv + h) * p.n_split * (size_t)G * RS;
       if (split == p.n_split - 1) {   // (uniform) the merging split: its own partial never leaves
-        // (small clusters poll four partials at a time, large ones eight)
-        ok = (p.n_split - 1 <= 4 ? merge_tagged<D, 4>(unit64, G, g, c, p.n_split - 1, tag, spin_limit,
-                                                      spins, M, Lsum, O)
-                                 : merge_tagged<D, 8>(unit64, G, g, c, p.n_split - 1, tag, spin_limit,
-                                                      spins, M, Lsum, O)) && ok;
+        // (small clusters take the partials four at a time, large ones sixteen)
+        const int others = p.n_split - 1;
+        ok = (others <= 4 ? merge_tagged<D, 4>(unit64, G, g, c, others, tag, spin_limit, spins, M, Lsum, O)
+                          : merge_tagged<D, 16>(unit64, G, g, c, others, tag, spin_limit, spins, M, Lsum, O)) && ok;
         store_out(p, ((size_t)b * p.Hq + (size_t)h * G + g) * D + c, Lsum > 0.f ? O / Lsum : 0.f);
         if (c == 0 && p.lse) p.lse[(size_t)b * p.Hq + (size_t)h * G + g] = log_sum_exp(M, Lsum);
       } else {

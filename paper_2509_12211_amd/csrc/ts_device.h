@@ -194,6 +194,30 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane(x, 63);
 }
 
+__device__ __forceinline__ float wave_max_f32(float v) {
+  const int id = (int)0xff800000u;  // -inf
+  int x = (int)__float_as_uint(v);
+  auto mx = [](int a, int b) { return (int)__float_as_uint(fmaxf(__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)b))); };
+  x = mx(x, dpp_move<kDppRowShr1>(id, x));
+  x = mx(x, dpp_move<kDppRowShr2>(id, x));
+  x = mx(x, dpp_move<kDppRowShr4>(id, x));
+  x = mx(x, dpp_move<kDppRowShr8>(id, x));
+  x = mx(x, dpp_move<kDppRowBcast15, 0xa>(id, x));
+  x = mx(x, dpp_move<kDppRowBcast31, 0xc>(id, x));
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane(x, 63));
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+  int x = (int)__float_as_uint(v);
+  auto ad = [](int a, int b) { return (int)__float_as_uint(__uint_as_float((uint32_t)a) + __uint_as_float((uint32_t)b)); };
+  x = ad(x, dpp_move<kDppRowShr1>(0, x));
+  x = ad(x, dpp_move<kDppRowShr2>(0, x));
+  x = ad(x, dpp_move<kDppRowShr4>(0, x));
+  x = ad(x, dpp_move<kDppRowShr8>(0, x));
+  x = ad(x, dpp_move<kDppRowBcast15, 0xa>(0, x));
+  x = ad(x, dpp_move<kDppRowBcast31, 0xc>(0, x));
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane(x, 63));
+}
+
 // x / d for 0 <= x < 2^16 and 1 <= d < 2^16 by one multiply, with a constant the host
 // works out: magic = floor(2^32 / d) + 1 (exact as long as x * d < 2^32); 0 stands for
 // d == 1.  The kernels' first instructions run ahead of their first loads, and a
