@@ -945,6 +945,28 @@ def test_every_length_of_a_wave_s_fragment_list(oracle, built, topk, cluster):
     assert torch.equal(sess.out, fused_out) or float((sess.out - fused_out).abs().max()) <= 2e-3
 
 
+@pytest.mark.parametrize("cluster", [5, 6, 9, 17, 18, 24, 40])
+@pytest.mark.parametrize("shape", ["d64_g4", "d128_g8"])
+def test_cluster_merge_in_batches(oracle, built, cluster, shape):
+    """The cluster's last member takes the other members' partial results four at a time
+    (up to five members) or sixteen at a time: cluster sizes on either side of both limits,
+    two and three batches, members that have no page at all, a head handled by one wave
+    (d = 64) and by two (d = 128, where a thread also works through two channels' worth of
+    the unit's G * d outputs)."""
+    print(f"[case] merge batches cluster={cluster} {shape}", flush=True)
+    spec = (wl.WorkloadSpec("merge64", 2, 8, 2, 64, 16, 5000, 48, keys="walk", headroom=40) if shape == "d64_g4"
+            else wl.WorkloadSpec("merge128", 1, 16, 2, 128, 16, 4000, 36, keys="offset", headroom=40))
+    w = wl.make_workload(spec, DEV, seed=700 + cluster, n_q=1, n_new=1)
+    units = [(b, h) for b in range(spec.B) for h in range(spec.Hkv)]
+    scale = 1.0 / math.sqrt(spec.d)
+    sess = Session(w, cluster_size=cluster)
+    ts.build_page_meta(sess.layout)
+    for step in range(2):     # the second launch finds the first one's words in the workspace
+        sess.out.fill_(float("nan"))
+        sess.fused(scale)
+        compare_units(oracle, sess, units, scale, what=f"merge/cluster={cluster}/{shape}/launch {step}")
+
+
 def test_an_expired_wait_raises_the_sticky_word_and_the_launch_still_ends(oracle, built):
     """ts_layout.wait_limit = 1 lets a workgroup give up on its partners after two looks.  Such a
     launch must still run to its end (nothing hangs, nothing is read out of bounds) and
