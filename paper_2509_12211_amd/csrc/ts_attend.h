@@ -270,15 +270,37 @@ __device__ __forceinline__ void load_page8(PageFrag8<D, PageGeom<S>::F>& f, cons
     f.ks[t] = *reinterpret_cast<const float4*>(kscale + tok0);
     f.vs[t] = *reinterpret_cast<const float4*>(vscale + tok0);
   }
+  if constexpr (F == 16 && S == 16) {
+    // A channel's 16 tokens are 16 contiguous bytes: lane (r, kb) fetches the whole row of
+    // channel 16 * (4 * q + kb) + r (a wave-wide load covers 1 KiB in one piece, a quarter
+    // of the instructions of four-byte loads), and the four lanes r, r + 16, r + 32, r + 48
+    // then trade words so that each ends up with its own four tokens of four channel
+    // blocks: a 4 x 4 transpose over the wave's four rows of lanes, two row-swap steps.
+    static_assert(PageFrag8<D, F>::NCB % 4 == 0, "channel blocks in fours");
 #pragma unroll
-  for (int cb = 0; cb < PageFrag8<D, F>::NCB; ++cb) {
-    const uint8_t* vrow = vtile + (16 * cb * spread + r) * S + hoff;
-    if (F == 16) {
-      f.v[0][cb] = load_stream4(vrow + 4 * kb);
-    } else {
-      const uint2 w = load_stream8(vrow + 8 * kb);
-      f.v[0][cb] = w.x;
-      f.v[F == 16 ? 0 : 1][cb] = w.y;
+    for (int q = 0; q < PageFrag8<D, F>::NCB / 4; ++q) {
+      const uint4 w = load_stream16(vtile + ((64 * q * spread + 16 * kb + r) * S));
+      // rows 2, 3 of (x, y) against rows 0, 1 of (z, w), then odd rows against even rows
+      const uint2s_t xz = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+      const uint2s_t yw = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+      const uint2s_t a = __builtin_amdgcn_permlane16_swap(xz.x, yw.x, false, false);
+      const uint2s_t b = __builtin_amdgcn_permlane16_swap(xz.y, yw.y, false, false);
+      f.v[0][4 * q] = a.x;
+      f.v[0][4 * q + 1] = a.y;
+      f.v[0][4 * q + 2] = b.x;
+      f.v[0][4 * q + 3] = b.y;
+    }
+  } else {
+#pragma unroll
+    for (int cb = 0; cb < PageFrag8<D, F>::NCB; ++cb) {
+      const uint8_t* vrow = vtile + (16 * cb * spread + r) * S + hoff;
+      if (F == 16) {
+        f.v[0][cb] = load_stream4(vrow + 4 * kb);
+      } else {
+        const uint2 w = load_stream8(vrow + 8 * kb);
+        f.v[0][cb] = w.x;
+        f.v[F == 16 ? 0 : 1][cb] = w.y;
+      }
     }
   }
 }
