@@ -206,6 +206,16 @@ query_aware_decode_kernel(FusedParams p) {
   TS_MARK_INIT();
   TS_MARK(22);
   const AttendParams& at = p.at;
+  // Everything the unit's first loads are addressed with is asked for here, ahead of the
+  // first branch: the compiler fetches a kernel argument in the block that first uses it,
+  // and arguments first used behind the tests below came in a second and a third trip to
+  // memory, each waited for, before the first load could go out.
+  asm volatile("" ::"s"(p.ctrl), "s"(p.page_min), "s"(p.page_max), "s"(p.topk_per_seq), "s"(p.k_new),
+               "s"(p.v_new), "s"(p.topk), "s"(p.units), "s"(p.g), "s"(p.xcds), "s"(p.div_hkv.d),
+               "s"(p.div_hkv.magic), "s"(p.div_g.d), "s"(p.div_g.magic), "s"(p.div_xcds.d),
+               "s"(p.div_xcds.magic), "s"(at.q), "s"(at.block_table), "s"(at.seq_lens), "s"(at.Hq),
+               "s"(at.Hkv), "s"(at.G), "s"(at.Pmax), "s"(at.chunk), "s"(at.lse), "s"(at.k_scale),
+               "s"(at.v_scale));
   const int g = kCluster ? p.g : 1, G = at.G, Pmax = at.Pmax;
   const ClusterSlot where = kCluster ? cluster_of(blockIdx.x, p.div_g, p.div_xcds, p.xcds > 1)
                                      : ClusterSlot{(int)blockIdx.x, 0};
