@@ -266,11 +266,12 @@ __device__ __forceinline__ void select_topk_lds(const SelectLds& L, const KeyLay
     }
     for (; i0 < C; i0 += kBatch) {
       uint32_t k[kBatch];
+      // (the first test is uniform: a chunk shorter than a batch skips the rest of it)
 #pragma unroll
-      for (int i = 0; i < kBatch; ++i) k[i] = i0 + i < my_n ? my_keys[i0 + i] : 0u;
+      for (int i = 0; i < kBatch; ++i) k[i] = (i0 + i < C && i0 + i < my_n) ? my_keys[i0 + i] : 0u;
 #pragma unroll
       for (int i = 0; i < kBatch; ++i)
-        if (i0 + i < my_n) fn(k[i], i0 + i);
+        if (i0 + i < C && i0 + i < my_n) fn(k[i], i0 + i);
     }
   };
   // Top-down scan of the bins by ONE wave (every wave does it for itself): the
