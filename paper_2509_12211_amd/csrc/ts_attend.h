@@ -564,6 +564,34 @@ __device__ __forceinline__ void attend_page(const PageFrag<D, F>& f, const short
   }
 }
 
+// The query operand of the attention: the G rows as MFMA fragments (for the INT8 cache
+// converted to halves, with the bias term of this lane's row).  The fused kernel fetches
+// it while it waits for the other members' scores, long before the selection is through.
+template <int D, bool kInt8>
+struct QOperand {
+  short4_t qf[D / 16];
+  float qbias;   // INT8 cache: kI8Bias * sum over the channels of this lane's query row
+  __device__ __forceinline__ void load(const uint16_t* rows, int G) {
+    load_q_frag<D>(qf, rows, G);
+    qbias = 0.f;
+    if constexpr (kInt8) {
+      typedef __fp16 h2_t __attribute__((ext_vector_type(2)));
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) {
+        const uint32_t w0 = (uint32_t)(uint16_t)qf[i][0] | ((uint32_t)(uint16_t)qf[i][1] << 16);
+        const uint32_t w1 = (uint32_t)(uint16_t)qf[i][2] | ((uint32_t)(uint16_t)qf[i][3] << 16);
+        const h2_t a = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w0), bf16_hi(w0));
+        const h2_t c = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w1), bf16_hi(w1));
+        part += ((float)a[0] + (float)a[1]) + ((float)c[0] + (float)c[1]);
+        qf[i] = as_short4(__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c));
+      }
+      // the row is spread over the four lanes head, head + 16, head + 32, head + 48
+      qbias = kI8Bias * rows_sum_f32(part);
+    }
+  }
+};
+
 // Partials handed on as tagged words (attend_split with a tag): merges the first
 // `n` partials of a unit into the running state (M, Lsum, O) of head g, channel c.
 // The words are polled until all carry this launch's tag, so the data arrive with the
@@ -685,12 +713,13 @@ __device__ __forceinline__ bool merge_tagged(const uint64_t* part, int G, int g,
 // split keeps its own partial in registers, polls for the others (bounded by
 // spin_limit polls per thread) and writes the unit's output; the function
 // returns false if that wait expired.
-template <int D, int S, bool kLatency, bool kPatch, bool kInt8, bool kHalf, typename SelAt,
-          typename PhysAt>
+template <int D, int S, bool kLatency, bool kPatch, bool kInt8, bool kHalf, bool kHaveQ = false,
+          typename SelAt, typename PhysAt>
 __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h, int split,
                                              int count, int L, const NewToken& nt, SelAt sel_at,
                                              PhysAt phys_at, float* lds, uint32_t tag = 0u,
-                                             const uint16_t* q_rows = nullptr, int spin_limit = 0) {
+                                             const uint16_t* q_rows = nullptr, int spin_limit = 0,
+                                             const QOperand<D, kInt8>* q_ready = nullptr) {
   using Geo = PageGeom<S>;
   constexpr int F = Geo::F, NS = Geo::NS, NH = Geo::NH;
   static_assert(!(kHalf && kInt8), "the INT8 cache goes with bf16 queries");
@@ -705,26 +734,14 @@ __device__ __forceinline__ bool attend_split(const AttendParams& p, int b, int h
   const int n_items = Geo::items(count);
   TS_MARK(26);
 
-  short4_t qf[D / 16];
   // q_rows: the unit's G query rows where the caller already holds them (the fused
-  // kernel: in LDS, staged by the scoring phase); nullptr: fetched from memory
-  load_q_frag<D>(qf, q_rows ? q_rows : p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
-  float qbias = 0.f;   // INT8 cache: kI8Bias * sum over the channels of this lane's query row
-  if constexpr (kInt8) {
-    typedef __fp16 h2_t __attribute__((ext_vector_type(2)));
-    float part = 0.f;
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) {
-      const uint32_t w0 = (uint32_t)(uint16_t)qf[i][0] | ((uint32_t)(uint16_t)qf[i][1] << 16);
-      const uint32_t w1 = (uint32_t)(uint16_t)qf[i][2] | ((uint32_t)(uint16_t)qf[i][3] << 16);
-      const h2_t a = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w0), bf16_hi(w0));
-      const h2_t c = __builtin_amdgcn_cvt_pkrtz(bf16_lo(w1), bf16_hi(w1));
-      part += ((float)a[0] + (float)a[1]) + ((float)c[0] + (float)c[1]);
-      qf[i] = as_short4(__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c));
-    }
-    // the row is spread over the four lanes head, head + 16, head + 32, head + 48
-    qbias = kI8Bias * rows_sum_f32(part);
-  }
+  // kernel: in LDS, staged by the scoring phase); nullptr: fetched from memory.
+  // kHaveQ: the caller has the operand in registers already (q_ready).
+  QOperand<D, kInt8> qop;
+  if constexpr (kHaveQ) qop = *q_ready;
+  else qop.load(q_rows ? q_rows : p.q + ((size_t)b * p.Hq + (size_t)h * G) * D, G);
+  const short4_t (&qf)[D / 16] = qop.qf;
+  const float qbias = qop.qbias;
   // The new token's page is the sequence's last, so in the ascending list it can
   // only be the very last entry: one wave of one workgroup ever needs the token.
   // splice_item: the fragment it falls into, splice_x: its position there.

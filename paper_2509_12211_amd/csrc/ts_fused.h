@@ -398,6 +398,10 @@ query_aware_decode_kernel(FusedParams p) {
       counted = true;
     }
 
+    // (the attention's query operand, out of the rows the scoring staged in LDS: fetched
+    // here, where the waves are about to wait for the other members anyway)
+    QOperand<D, kInt8> qop;
+    qop.load(reinterpret_cast<const uint16_t*>(q_stage), G);   // the raw rows head the staging area
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
     const ForcedPages forced = ForcedPages::make(p.keep_first, p.keep_last, Pb);
@@ -537,11 +541,10 @@ query_aware_decode_kernel(FusedParams p) {
     // words; the cluster's last member (its chunk of the list is the one that
     // can be short) keeps its own in registers, polls for the others and writes
     // the output.  Nobody else waits for anything.
-    const bool merged = attend_split<D, S, !kLoop, kApp, kInt8, kHalf>(
+    const bool merged = attend_split<D, S, !kLoop, kApp, kInt8, kHalf, true>(
         at, b, h, member, count, L, nt, [&](int i) { return my_sel[i]; },
         [&](int j) { return bt_lds[j]; }, reinterpret_cast<float*>(smem), exchange ? tag : 0u,
-        reinterpret_cast<const uint16_t*>(q_stage),   // the raw rows head the staging area
-        p.spin_limit);
+        nullptr, p.spin_limit, &qop);
     TS_MARK(6);
     if (!merged) atomic_store_agent(&p.ctrl[kCtrlError], 1);
     if (!kLoop) break;
