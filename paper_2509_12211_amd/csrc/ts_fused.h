@@ -404,67 +404,6 @@ query_aware_decode_kernel(FusedParams p) {
     qop.load(reinterpret_cast<const uint16_t*>(q_stage), G);   // the raw rows head the staging area
     // 2. exchange the scores inside the cluster
     TS_MARK(1);
-    const ForcedPages forced = ForcedPages::make(p.keep_first, p.keep_last, Pb);
-    BinMap bins{0.f, 0.f};
-    if (exchange) {
-      // The selection's first stage (counting the pages into score bins) is done
-      // here, key by key as the scores come in, instead of in a pass of its own
-      // after them.  The bins need a score range before the first score of the
-      // other members is looked at: the range of this workgroup's own share
-      // (every g-th group of pages: a fair sample), widened; any monotone map
-      // keeps the selection exact.  Each member bins in its own way and all
-      // arrive at the same pages.
-      select_begin(sl, tmin, tmax);
-      __syncthreads();
-      {
-        uint32_t lo_key, hi_key;
-        select_deposited_range(sl, lo_key, hi_key);
-        bins = BinMap::widened(lo_key, hi_key);
-      }
-      // every thread polls its own entries of the row until all carry this
-      // launch's tag (all loads of a round in flight together; bounded)
-      bool expired = false;
-      int spins = 0;
-      auto poll = [&](auto np_tag) {
-        constexpr int NP = decltype(np_tag)::value;
-        for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * NP) {
-          uint64_t v[NP];
-          for (;;) {
-            bool all = true;
-#pragma unroll
-            for (int i = 0; i < NP; ++i) {
-              v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
-              all = all && (uint32_t)(v[i] >> 32) == tag;
-            }
-            if (all) break;
-            if (++spins > p.spin_limit) { expired = true; break; }
-            __builtin_amdgcn_s_sleep(1);
-          }
-#pragma unroll
-          for (int i = 0; i < NP; ++i) {
-            const int j = j0 + i * kThreads;
-            if (j < Pb) {
-              const bool always = j < forced.first || j >= forced.last_begin;
-              const uint32_t k = always ? kForcedKey : score_key(__uint_as_float((uint32_t)v[i]));
-              sl.keys[kl.at(j)] = k;
-              atomicAdd(&sl.hist[bin_slot_index(bins.slot<true>(k))], 1u);
-            }
-          }
-        }
-      };
-      const int per_thread = uniform((Pb + kThreads - 1) / kThreads);
-      if (per_thread <= 1) poll(std::integral_constant<int, 1>{});
-      else if (per_thread <= 2) poll(std::integral_constant<int, 2>{});
-      else if (per_thread <= 4) poll(std::integral_constant<int, 4>{});
-      else poll(std::integral_constant<int, 8>{});
-      if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
-      TS_MARK(3);
-      TS_MARK_WAVE(40);
-    } else {
-      select_begin(sl, tmin, tmax);
-    }
-    __syncthreads();
-    TS_MARK(4);
     // The new token lands in its pool slot (one member's first lanes; the
     // block-table row is complete in LDS once the barrier above is passed).
     // Nothing in this launch reads it from there: the attention splices it in
@@ -518,7 +457,69 @@ query_aware_decode_kernel(FusedParams p) {
       }
     };
 
-    if (kApp) store_new_token();
+    const ForcedPages forced = ForcedPages::make(p.keep_first, p.keep_last, Pb);
+    BinMap bins{0.f, 0.f};
+    if (exchange) {
+      // The selection's first stage (counting the pages into score bins) is done
+      // here, key by key as the scores come in, instead of in a pass of its own
+      // after them.  The bins need a score range before the first score of the
+      // other members is looked at: the range of this workgroup's own share
+      // (every g-th group of pages: a fair sample), widened; any monotone map
+      // keeps the selection exact.  Each member bins in its own way and all
+      // arrive at the same pages.
+      select_begin(sl, tmin, tmax);
+      __syncthreads();
+      if (kApp) store_new_token();   // (the block-table row is complete behind this barrier)
+      {
+        uint32_t lo_key, hi_key;
+        select_deposited_range(sl, lo_key, hi_key);
+        bins = BinMap::widened(lo_key, hi_key);
+      }
+      // every thread polls its own entries of the row until all carry this
+      // launch's tag (all loads of a round in flight together; bounded)
+      bool expired = false;
+      int spins = 0;
+      auto poll = [&](auto np_tag) {
+        constexpr int NP = decltype(np_tag)::value;
+        for (int j0 = threadIdx.x; j0 < Pb; j0 += kThreads * NP) {
+          uint64_t v[NP];
+          for (;;) {
+            bool all = true;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+              v[i] = load_agent_u64(srow + min(j0 + i * kThreads, Pb - 1));  // no branch around the load
+              all = all && (uint32_t)(v[i] >> 32) == tag;
+            }
+            if (all) break;
+            if (++spins > p.spin_limit) { expired = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            const int j = j0 + i * kThreads;
+            if (j < Pb) {
+              const bool always = j < forced.first || j >= forced.last_begin;
+              const uint32_t k = always ? kForcedKey : score_key(__uint_as_float((uint32_t)v[i]));
+              sl.keys[kl.at(j)] = k;
+              atomicAdd(&sl.hist[bin_slot_index(bins.slot<true>(k))], 1u);
+            }
+          }
+        }
+      };
+      const int per_thread = uniform((Pb + kThreads - 1) / kThreads);
+      if (per_thread <= 1) poll(std::integral_constant<int, 1>{});
+      else if (per_thread <= 2) poll(std::integral_constant<int, 2>{});
+      else if (per_thread <= 4) poll(std::integral_constant<int, 4>{});
+      else poll(std::integral_constant<int, 8>{});
+      if (expired) atomic_store_agent(&p.ctrl[kCtrlError], 1);
+      TS_MARK(3);
+      TS_MARK_WAVE(40);
+    } else {
+      select_begin(sl, tmin, tmax);
+    }
+    __syncthreads();
+    TS_MARK(4);
+    if (kApp && !exchange) store_new_token();
 
     // 3. select; keep my own chunk of the ascending list
     const int c0 = min(member * at.chunk, Kb), count = min(c0 + at.chunk, Kb) - c0;
